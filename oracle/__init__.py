@@ -1,0 +1,14 @@
+"""CPU oracle (test infrastructure): see specattn_oracle.c for what it computes.
+
+Only tests/, the smoke check and the bench's cpu_baseline leg may import this
+package.  It never imports the HIP binding.
+"""
+from .oracle import (  # noqa: F401
+    ROW_INVALID,
+    ROW_NEAR_BOUNDARY,
+    SelectResult,
+    masked_attention,
+    nucleus_bisection,
+    set_threads,
+    topp_select,
+)

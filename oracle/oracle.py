@@ -1,0 +1,136 @@
+"""ctypes front end of the C oracle: argument marshalling only."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional, Sequence
+
+import numpy as np
+
+from . import build as _build
+
+ROW_INVALID = 1
+ROW_NEAR_BOUNDARY = 2
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        path = _build.build(force=False)
+        lib = C.CDLL(path)
+        lib.oracle_set_threads.restype = C.c_int
+        lib.oracle_set_threads.argtypes = [C.c_int]
+        lib.oracle_topp_select.restype = C.c_int
+        lib.oracle_topp_select.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_void_p, C.c_float,
+                                           C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
+                                           C.c_void_p, C.c_void_p]
+        lib.oracle_nucleus_bisection.restype = C.c_int
+        lib.oracle_nucleus_bisection.argtypes = [C.c_void_p, C.c_int, C.c_double, C.c_int,
+                                                 C.POINTER(C.c_double), C.POINTER(C.c_double),
+                                                 C.POINTER(C.c_double)]
+        lib.oracle_masked_attention.restype = C.c_int
+        lib.oracle_masked_attention.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
+                                                C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                                                C.c_void_p, C.c_void_p, C.c_double,
+                                                C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
+        _lib = lib
+    return _lib
+
+
+def set_threads(t: int = 0) -> int:
+    """Set (t > 0) and return the number of OpenMP threads the oracle uses."""
+    return int(_load().oracle_set_threads(int(t)))
+
+
+@dataclass
+class SelectResult:
+    indices: np.ndarray     # [rows, n] int32; row r valid on [:counts[r]], ascending
+    counts: np.ndarray      # [rows] int32
+    tau: np.ndarray         # [rows] float32
+    flags: np.ndarray       # [rows] uint32 (ROW_* bits)
+    diag: np.ndarray        # [rows, 4] float64: S, target, mass{>= tau}, mass{> tau}
+
+    def row_set(self, r: int) -> np.ndarray:
+        return self.indices[r, : self.counts[r]]
+
+    def mask(self) -> np.ndarray:
+        """[rows, n] uint8 membership mask."""
+        m = np.zeros(self.indices.shape, dtype=np.uint8)
+        for r in range(m.shape[0]):
+            m[r, self.row_set(r)] = 1
+        return m
+
+
+def topp_select(probs: np.ndarray, top_p: float, lens: Optional[np.ndarray] = None) -> SelectResult:
+    """probs [rows, n] float32; lens [rows] (default: n for every row)."""
+    probs = np.ascontiguousarray(probs, dtype=np.float32)
+    assert probs.ndim == 2
+    rows, n = probs.shape
+    lens = (np.full(rows, n, dtype=np.int32) if lens is None
+            else np.ascontiguousarray(lens, dtype=np.int32))
+    assert lens.shape == (rows,) and (lens <= n).all()
+    idx = np.full((rows, max(n, 1)), -1, dtype=np.int32)
+    counts = np.zeros(rows, dtype=np.int32)
+    tau = np.zeros(rows, dtype=np.float32)
+    flags = np.zeros(rows, dtype=np.uint32)
+    diag = np.zeros((rows, 4), dtype=np.float64)
+    rc = _load().oracle_topp_select(probs.ctypes.data, n, rows, lens.ctypes.data, float(top_p),
+                                    idx.ctypes.data, idx.shape[1], counts.ctypes.data,
+                                    tau.ctypes.data, flags.ctypes.data, diag.ctypes.data)
+    if rc != 0:
+        raise ValueError(f"oracle_topp_select failed with {rc} (top_p must be in (0, 1])")
+    return SelectResult(idx, counts, tau, flags, diag)
+
+
+def nucleus_bisection(row: np.ndarray, p: float, iters: int):
+    """Algorithm 2's bisection on one row; returns (theta_low, theta_high, theta_mid)."""
+    row = np.ascontiguousarray(row, dtype=np.float32)
+    lo, hi, mid = C.c_double(), C.c_double(), C.c_double()
+    _load().oracle_nucleus_bisection(row.ctypes.data, row.size, float(p), int(iters),
+                                     C.byref(lo), C.byref(hi), C.byref(mid))
+    return lo.value, hi.value, mid.value
+
+
+def masked_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, mask: np.ndarray,
+                     *, bf16: bool = False, lens: Optional[np.ndarray] = None,
+                     sm_scale: Optional[float] = None,
+                     which: Optional[Sequence[Sequence[int]]] = None):
+    """Masked dense attention in fp64.
+
+    q [B,H_q,T,d], k/v [B,H_kv,n,d]: float32 arrays, or uint16 bf16 bit
+    patterns when bf16=True.  mask [B,H_kv,n] (nonzero = selected).
+    which: optional list of (b, h_q, t) rows; default all, returned as
+    out [B,H_q,T,d] / lse [B,H_q,T].  With `which`, out is [len(which), d].
+    """
+    want = np.uint16 if bf16 else np.float32
+    q, k, v = (np.ascontiguousarray(a) for a in (q, k, v))
+    assert q.dtype == want and k.dtype == want and v.dtype == want
+    B, H_q, T, d = q.shape
+    _, H_kv, n, _ = k.shape
+    assert k.shape == v.shape == (B, H_kv, n, d)
+    mask = np.ascontiguousarray(mask, dtype=np.uint8)
+    assert mask.shape == (B, H_kv, n)
+    lens = (np.full(B, n, dtype=np.int32) if lens is None
+            else np.ascontiguousarray(lens, dtype=np.int32))
+    scale = float(1.0 / np.sqrt(np.float64(d))) if sm_scale is None else float(sm_scale)
+    full = which is None
+    if full:
+        which_a = np.array([(b, h, t) for b in range(B) for h in range(H_q) for t in range(T)],
+                           dtype=np.int32)
+    else:
+        which_a = np.ascontiguousarray(which, dtype=np.int32).reshape(-1, 3)
+    rows = which_a.shape[0]
+    out = np.zeros((rows, d), dtype=np.float64)
+    lse = np.zeros(rows, dtype=np.float64)
+    rc = _load().oracle_masked_attention(q.ctypes.data, k.ctypes.data, v.ctypes.data, int(bf16),
+                                         B, H_q, H_kv, T, d, n, mask.ctypes.data,
+                                         lens.ctypes.data, scale, which_a.ctypes.data, rows,
+                                         out.ctypes.data, lse.ctypes.data)
+    if rc != 0:
+        raise ValueError(f"oracle_masked_attention failed with {rc}")
+    if full:
+        return out.reshape(B, H_q, T, d), lse.reshape(B, H_q, T)
+    return out, lse
