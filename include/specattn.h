@@ -1,0 +1,151 @@
+/*
+ * specattn.h - C ABI of the MI355X (gfx950) SpecAttn hot path:
+ * sorting-free top-p selection of KV positions from draft attention rows,
+ * and sparse decode attention of the verifier's gamma+1 queries over the
+ * selected K/V only.
+ *
+ * General rules for every entry point
+ *  - Every pointer inside the argument structs is a DEVICE pointer owned by
+ *    the caller.  The structs themselves are HOST memory, read during the
+ *    call and not kept.
+ *  - Calls are asynchronous on `stream` (a hipStream_t passed as void*; NULL
+ *    is the default stream).  The library never synchronises, never allocates
+ *    and never frees device memory; scratch space comes in through the
+ *    workspace arguments (size from specattn_workspace_size).
+ *  - Return value: SPECATTN_OK or a negative specattn_status.  Argument
+ *    errors are found on the host before anything is launched; on error no
+ *    output is written.  specattn_last_error() gives a thread-local text.
+ *  - "row" always means one (batch b, kv head h) pair, numbered r = b*H_kv+h.
+ *  - GQA: query head h_q reads kv head h_q / (H_q / H_kv).
+ */
+#ifndef SPECATTN_H
+#define SPECATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum specattn_status {
+    SPECATTN_OK = 0,
+    SPECATTN_EINVAL = -1,       /* NULL required pointer, top_p outside (0,1] or NaN, size <= 0 */
+    SPECATTN_ESHAPE = -2,       /* H_q % H_kv != 0, unsupported d / T / n, capacity < 1, page size */
+    SPECATTN_EALIGN = -3,       /* q/k/v base or strides not 16-byte aligned */
+    SPECATTN_EWORKSPACE = -4,   /* workspace NULL, misaligned (256 B) or too small */
+    SPECATTN_EUNSUPPORTED = -5, /* dtype / layout combination not built */
+    SPECATTN_EHIP = -6          /* a launch failed; text in specattn_last_error() */
+} specattn_status;
+
+typedef enum specattn_dtype { SPECATTN_F32 = 0, SPECATTN_BF16 = 1 } specattn_dtype;
+
+/* bits of row_flags[r] */
+#define SPECATTN_ROW_INVALID 1u        /* NaN / negative / infinite entry, zero row sum or length 0: count = 0 */
+#define SPECATTN_ROW_NEAR_BOUNDARY 2u  /* kept or strictly-above mass within 1e-6 * row sum of the target */
+#define SPECATTN_ROW_OVERFLOW 4u       /* count > idx_capacity: list truncated to the first idx_capacity */
+
+/* limits */
+#define SPECATTN_MAX_N (1 << 20)       /* longest row the selection handles */
+#define SPECATTN_MAX_T 8               /* most verifier queries (gamma + 1) per head */
+
+/*
+ * Selection (Section 3.4, Algorithm 2; objective: Appendix A, Eq. 8).
+ *
+ * For every row the call finds tau* = max{ t : sum of probs >= t is at least
+ * top_p * (row sum) } exactly - tau* is always one of the row's values - and
+ * emits { j : probs[j] >= tau* } in ascending j.  Entries tied with tau* are
+ * all kept.  Exact zeros are never kept.  No sort is performed.
+ */
+typedef struct specattn_select_args {
+    const float *probs;          /* [B][H_kv][n_max] fp32, non-negative; need not be normalised */
+    int64_t probs_stride_b;      /* element strides; the last dimension is contiguous */
+    int64_t probs_stride_h;
+    int32_t B, H_kv, n_max;
+    const int32_t *seq_lens;     /* [B] valid length per sequence, or NULL for n_max everywhere */
+    float top_p;                 /* p in (0, 1] */
+
+    int32_t *indices;            /* out [B*H_kv][idx_stride_row]: ascending positions; may be NULL
+                                    only in specattn_fused */
+    int64_t idx_stride_row;      /* elements between rows, >= idx_capacity */
+    int32_t idx_capacity;        /* most entries written per row */
+    int32_t *counts;             /* out [B*H_kv]: TRUE number kept, even when > idx_capacity */
+    float *thresholds;           /* out [B*H_kv] tau*; optional (NULL) */
+    uint32_t *row_flags;         /* out [B*H_kv] SPECATTN_ROW_* bits; optional (NULL) */
+
+    /* optional paged output: emit pool slots instead of logical positions */
+    const int32_t *page_table;   /* [B][max_pages_per_seq] page ids, or NULL */
+    int32_t page_size;           /* tokens per page, power of two (16 in the paged workload) */
+    int32_t max_pages_per_seq;
+    int32_t emit_physical;       /* 1: indices[j] = page_table[b][pos/page_size]*page_size + pos%page_size
+                                       (still in ascending pos order); needs page_table */
+} specattn_select_args;
+
+/*
+ * Sparse decode attention (Section 3.1.2, Eq. 2-3; Section 3.5).
+ *
+ * out[b][h_q][t] = softmax over the row's kept positions of
+ *                  (q[b][h_q][t] . k[b][h_kv][j]) * sm_scale, times v.
+ * All T queries of all G query heads of a kv head share that head's list.
+ * A row with count 0 gives out = 0 and lse = -inf.  Accumulation is fp32;
+ * `out` is fp32 whatever the input dtype.
+ */
+typedef struct specattn_attn_args {
+    const void *q;               /* [B][H_q][T][d] */
+    const void *k, *v;           /* contiguous: [B][H_kv][n_max][d] via the strides below
+                                    paged:      pool [pages][H_kv][page_size][d] */
+    specattn_dtype dtype;        /* element type of q, k and v */
+    int32_t B, H_q, H_kv, T, d, n_max;
+    float sm_scale;              /* <= 0 selects 1/sqrt(d) (Eq. 1) */
+    int64_t q_stride_b, q_stride_h, q_stride_t;        /* elements; last dim contiguous */
+    int64_t kv_stride_b, kv_stride_h, kv_stride_n;     /* contiguous layout; kv_stride_n >= d */
+
+    const int32_t *page_table;   /* NULL = contiguous layout */
+    int32_t page_size, max_pages_per_seq;
+    int64_t kv_stride_page;      /* paged: elements between pages; kv_stride_h / kv_stride_n then
+                                    address head and in-page token */
+
+    const int32_t *seq_lens;     /* [B] or NULL; only used by specattn_fused (selection side) */
+    const int32_t *indices;      /* [B*H_kv][idx_stride_row], as written by specattn_topp_select */
+    int64_t idx_stride_row;
+    const int32_t *counts;       /* [B*H_kv]; values above idx_capacity are clamped to it */
+    int32_t idx_capacity;
+    int32_t indices_are_physical;/* 1: entries are pool slots (page*page_size + offset) */
+
+    float *out;                  /* [B][H_q][T][d] fp32, contiguous */
+    float *lse;                  /* [B][H_q][T] log-sum-exp of the kept scaled scores; optional */
+    void *workspace;             /* split partials; 256-byte aligned */
+    size_t workspace_bytes;
+} specattn_attn_args;
+
+/* Selection alone.  `workspace` may be NULL when specattn_workspace_size(sel, NULL) is 0. */
+specattn_status specattn_topp_select(const specattn_select_args *sel, void *workspace,
+                                     size_t workspace_bytes, void *stream);
+
+/* Attention alone, over an index list already in device memory. */
+specattn_status specattn_sparse_decode_attn(const specattn_attn_args *attn, void *stream);
+
+/*
+ * Selection + attention without the index list going through HBM: the first
+ * phase writes only tau*, counts and per-block counts; the attention
+ * workgroups re-derive their share of the list from `probs` on chip.
+ * sel->indices may be NULL; attn->indices / attn->counts are ignored
+ * (sel->counts is written and used).  attn->workspace serves both phases.
+ */
+specattn_status specattn_fused(const specattn_select_args *sel, const specattn_attn_args *attn,
+                               void *stream);
+
+/* Bytes of workspace needed: selection alone (attn NULL), attention alone (sel NULL), or the
+   fused call (both).  0 is returned for invalid arguments. */
+size_t specattn_workspace_size(const specattn_select_args *sel, const specattn_attn_args *attn);
+
+/* Text of the calling thread's last error ("" if none).  Never NULL. */
+const char *specattn_last_error(void);
+
+/* ABI version: major * 1000 + minor. */
+int specattn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPECATTN_H */

@@ -1,0 +1,208 @@
+"""Thin ctypes binding of libspecattn.so: argument marshalling only.
+
+Tensors are torch tensors on the GPU (torch is used for device memory and
+streams, nothing else); every step of the path runs inside the library's
+kernels.  There is no CPU fallback: a missing library is an error.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libspecattn.so")
+
+OK, EINVAL, ESHAPE, EALIGN, EWORKSPACE, EUNSUPPORTED, EHIP = 0, -1, -2, -3, -4, -5, -6
+ROW_INVALID, ROW_NEAR_BOUNDARY, ROW_OVERFLOW = 1, 2, 4
+F32, BF16 = 0, 1
+
+EXPORTS = ("specattn_topp_select", "specattn_sparse_decode_attn", "specattn_fused",
+           "specattn_workspace_size", "specattn_last_error", "specattn_version")
+
+
+class SelectArgs(C.Structure):
+    _fields_ = [
+        ("probs", C.c_void_p), ("probs_stride_b", C.c_int64), ("probs_stride_h", C.c_int64),
+        ("B", C.c_int32), ("H_kv", C.c_int32), ("n_max", C.c_int32),
+        ("seq_lens", C.c_void_p), ("top_p", C.c_float),
+        ("indices", C.c_void_p), ("idx_stride_row", C.c_int64), ("idx_capacity", C.c_int32),
+        ("counts", C.c_void_p), ("thresholds", C.c_void_p), ("row_flags", C.c_void_p),
+        ("page_table", C.c_void_p), ("page_size", C.c_int32), ("max_pages_per_seq", C.c_int32),
+        ("emit_physical", C.c_int32),
+    ]
+
+
+class AttnArgs(C.Structure):
+    _fields_ = [
+        ("q", C.c_void_p), ("k", C.c_void_p), ("v", C.c_void_p), ("dtype", C.c_int),
+        ("B", C.c_int32), ("H_q", C.c_int32), ("H_kv", C.c_int32), ("T", C.c_int32),
+        ("d", C.c_int32), ("n_max", C.c_int32), ("sm_scale", C.c_float),
+        ("q_stride_b", C.c_int64), ("q_stride_h", C.c_int64), ("q_stride_t", C.c_int64),
+        ("kv_stride_b", C.c_int64), ("kv_stride_h", C.c_int64), ("kv_stride_n", C.c_int64),
+        ("page_table", C.c_void_p), ("page_size", C.c_int32), ("max_pages_per_seq", C.c_int32),
+        ("kv_stride_page", C.c_int64),
+        ("seq_lens", C.c_void_p),
+        ("indices", C.c_void_p), ("idx_stride_row", C.c_int64), ("counts", C.c_void_p),
+        ("idx_capacity", C.c_int32), ("indices_are_physical", C.c_int32),
+        ("out", C.c_void_p), ("lse", C.c_void_p),
+        ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
+    ]
+
+
+class SpecAttnError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"specattn status {status}: {text}")
+        self.status = status
+
+
+_lib = None
+
+
+def load() -> C.CDLL:
+    """Load libspecattn.so (built by `python -m paper_2510_27641_amd.build`)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2510_27641_amd.build`")
+        lib = C.CDLL(LIB_PATH)
+        lib.specattn_topp_select.restype = C.c_int
+        lib.specattn_topp_select.argtypes = [C.POINTER(SelectArgs), C.c_void_p, C.c_size_t, C.c_void_p]
+        lib.specattn_sparse_decode_attn.restype = C.c_int
+        lib.specattn_sparse_decode_attn.argtypes = [C.POINTER(AttnArgs), C.c_void_p]
+        lib.specattn_fused.restype = C.c_int
+        lib.specattn_fused.argtypes = [C.POINTER(SelectArgs), C.POINTER(AttnArgs), C.c_void_p]
+        lib.specattn_workspace_size.restype = C.c_size_t
+        lib.specattn_workspace_size.argtypes = [C.POINTER(SelectArgs), C.POINTER(AttnArgs)]
+        lib.specattn_last_error.restype = C.c_char_p
+        lib.specattn_last_error.argtypes = []
+        lib.specattn_version.restype = C.c_int
+        lib.specattn_version.argtypes = []
+        _lib = lib
+    return _lib
+
+
+def last_error() -> str:
+    return load().specattn_last_error().decode()
+
+
+def _check(status: int):
+    if status != OK:
+        raise SpecAttnError(status, last_error())
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> C.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+# ------------------------------------------------------------------------------------------
+# argument structs from tensors
+# ------------------------------------------------------------------------------------------
+def select_args(probs: torch.Tensor, top_p: float, *, indices: Optional[torch.Tensor],
+                counts: torch.Tensor, thresholds: Optional[torch.Tensor] = None,
+                row_flags: Optional[torch.Tensor] = None, seq_lens: Optional[torch.Tensor] = None,
+                page_table: Optional[torch.Tensor] = None, page_size: int = 0,
+                emit_physical: bool = False) -> SelectArgs:
+    """probs [B,H_kv,n] fp32 (last dim contiguous); indices [B*H_kv, cap] int32."""
+    assert probs.dtype == torch.float32 and probs.dim() == 3 and probs.stride(2) == 1
+    B, H, n = probs.shape
+    a = SelectArgs()
+    a.probs = probs.data_ptr()
+    a.probs_stride_b, a.probs_stride_h = probs.stride(0), probs.stride(1)
+    a.B, a.H_kv, a.n_max = B, H, n
+    a.seq_lens = None if seq_lens is None else seq_lens.data_ptr()
+    a.top_p = top_p
+    if indices is not None:
+        assert indices.dtype == torch.int32 and indices.dim() == 2 and indices.stride(1) == 1
+        a.indices = indices.data_ptr()
+        a.idx_stride_row, a.idx_capacity = indices.stride(0), indices.shape[1]
+    a.counts = counts.data_ptr()
+    a.thresholds = None if thresholds is None else thresholds.data_ptr()
+    a.row_flags = None if row_flags is None else row_flags.data_ptr()
+    if page_table is not None:
+        assert page_table.dtype == torch.int32 and page_table.is_contiguous()
+        a.page_table = page_table.data_ptr()
+        a.page_size, a.max_pages_per_seq = page_size, page_table.shape[1]
+    a.emit_physical = int(emit_physical)
+    return a
+
+
+def attn_args(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, *, out: torch.Tensor,
+              indices: Optional[torch.Tensor] = None, counts: Optional[torch.Tensor] = None,
+              lse: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+              n_max: Optional[int] = None, sm_scale: float = 0.0,
+              page_table: Optional[torch.Tensor] = None, page_size: int = 0,
+              indices_are_physical: bool = False, seq_lens: Optional[torch.Tensor] = None) -> AttnArgs:
+    """q [B,H_q,T,d]; contiguous k/v [B,H_kv,n,d]; paged k/v pool [pages,H_kv,page_size,d]."""
+    assert q.dim() == 4 and k.dim() == 4 and k.shape == v.shape and k.stride() == v.stride()
+    assert q.dtype == k.dtype == v.dtype and q.dtype in (torch.float32, torch.bfloat16)
+    assert q.stride(3) == 1 and k.stride(3) == 1
+    B, H_q, T, d = q.shape
+    paged = page_table is not None or indices_are_physical
+    a = AttnArgs()
+    a.q, a.k, a.v = q.data_ptr(), k.data_ptr(), v.data_ptr()
+    a.dtype = BF16 if q.dtype == torch.bfloat16 else F32
+    a.B, a.H_q, a.H_kv, a.T, a.d = B, H_q, k.shape[1], T, d
+    a.sm_scale = sm_scale
+    a.q_stride_b, a.q_stride_h, a.q_stride_t = q.stride(0), q.stride(1), q.stride(2)
+    if paged:
+        a.n_max = int(n_max if n_max is not None else
+                      (page_table.shape[1] * page_size if page_table is not None else 0))
+        a.kv_stride_page, a.kv_stride_h, a.kv_stride_n = k.stride(0), k.stride(1), k.stride(2)
+        a.kv_stride_b = 0
+        a.page_size = page_size
+        if page_table is not None:
+            assert page_table.dtype == torch.int32 and page_table.is_contiguous()
+            a.page_table = page_table.data_ptr()
+            a.max_pages_per_seq = page_table.shape[1]
+    else:
+        a.n_max = k.shape[2] if n_max is None else n_max
+        a.kv_stride_b, a.kv_stride_h, a.kv_stride_n = k.stride(0), k.stride(1), k.stride(2)
+    a.seq_lens = None if seq_lens is None else seq_lens.data_ptr()
+    if indices is not None:
+        assert indices.dtype == torch.int32 and indices.dim() == 2 and indices.stride(1) == 1
+        a.indices = indices.data_ptr()
+        a.idx_stride_row, a.idx_capacity = indices.stride(0), indices.shape[1]
+    a.counts = None if counts is None else counts.data_ptr()
+    a.indices_are_physical = int(indices_are_physical)
+    assert out.dtype == torch.float32 and out.is_contiguous() and tuple(out.shape) == (B, H_q, T, d)
+    a.out = out.data_ptr()
+    a.lse = None if lse is None else lse.data_ptr()
+    if workspace is not None:
+        a.workspace, a.workspace_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    return a
+
+
+# ------------------------------------------------------------------------------------------
+# the three entry points (same names as the C ABI)
+# ------------------------------------------------------------------------------------------
+def specattn_workspace_size(sel: Optional[SelectArgs], attn: Optional[AttnArgs]) -> int:
+    return int(load().specattn_workspace_size(None if sel is None else C.byref(sel),
+                                              None if attn is None else C.byref(attn)))
+
+
+def specattn_topp_select(sel: SelectArgs, workspace: Optional[torch.Tensor] = None, stream=None) -> None:
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().specattn_topp_select(C.byref(sel), _ptr(workspace), nbytes, _stream(stream)))
+
+
+def specattn_sparse_decode_attn(attn: AttnArgs, stream=None) -> None:
+    _check(load().specattn_sparse_decode_attn(C.byref(attn), _stream(stream)))
+
+
+def specattn_fused(sel: SelectArgs, attn: AttnArgs, stream=None) -> None:
+    _check(load().specattn_fused(C.byref(sel), C.byref(attn), _stream(stream)))
+
+
+def alloc_workspace(nbytes: int, device="cuda") -> torch.Tensor:
+    """A 256-byte aligned device buffer of at least nbytes (torch's allocator aligns to 512)."""
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)

@@ -1,0 +1,218 @@
+// C ABI of the library: host-side argument checks and dispatch.  Nothing here touches device
+// memory; every check runs before the first launch so that a failing call writes nothing.
+#include "common.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+
+namespace specattn {
+
+static thread_local char g_error[512] = "";
+
+void set_error(const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_error, sizeof(g_error), fmt, ap);
+    va_end(ap);
+}
+
+void clear_error() { g_error[0] = '\0'; }
+
+int cu_count()
+{
+    static int cached = 0;
+    if (cached > 0) return cached;
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0) {
+        cached = cus;
+        return cus;
+    }
+    (void)hipGetLastError();
+    return 256;
+}
+
+specattn_status check_launch(const char *what)
+{
+    const hipError_t e = hipGetLastError();
+    if (e == hipSuccess) return SPECATTN_OK;
+    set_error("%s: %s", what, hipGetErrorString(e));
+    return SPECATTN_EHIP;
+}
+
+namespace {
+
+bool is_pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
+int log2i(int x) { int s = 0; while ((1 << s) < x) ++s; return s; }
+bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+specattn_status check_select(const specattn_select_args *s, bool fused)
+{
+    if (!s) { set_error("select args are NULL"); return SPECATTN_EINVAL; }
+    if (!s->probs || !s->counts) { set_error("probs and counts must not be NULL"); return SPECATTN_EINVAL; }
+    if (!fused && !s->indices) { set_error("indices must not be NULL"); return SPECATTN_EINVAL; }
+    if (s->B <= 0 || s->H_kv <= 0 || s->n_max <= 0) { set_error("B, H_kv and n_max must be positive"); return SPECATTN_EINVAL; }
+    if (!(s->top_p > 0.0f && s->top_p <= 1.0f)) { set_error("top_p must lie in (0, 1]"); return SPECATTN_EINVAL; }
+    if (s->n_max > SPECATTN_MAX_N) { set_error("n_max %d exceeds %d", s->n_max, SPECATTN_MAX_N); return SPECATTN_ESHAPE; }
+    if ((int64_t)s->B * s->H_kv > (1 << 24)) { set_error("too many rows"); return SPECATTN_ESHAPE; }
+    if (s->indices) {
+        if (s->idx_capacity < 1) { set_error("idx_capacity must be at least 1"); return SPECATTN_ESHAPE; }
+        if (s->idx_stride_row < s->idx_capacity) { set_error("idx_stride_row is smaller than idx_capacity"); return SPECATTN_ESHAPE; }
+    }
+    if (s->probs_stride_h < s->n_max || s->probs_stride_b < s->n_max) { set_error("probs strides are smaller than n_max"); return SPECATTN_ESHAPE; }
+    if (s->emit_physical) {
+        if (!s->page_table) { set_error("emit_physical needs a page table"); return SPECATTN_EINVAL; }
+        if (!is_pow2(s->page_size)) { set_error("page_size must be a power of two"); return SPECATTN_ESHAPE; }
+        if ((int64_t)s->max_pages_per_seq * s->page_size < s->n_max) { set_error("page table is shorter than n_max"); return SPECATTN_ESHAPE; }
+    }
+    return SPECATTN_OK;
+}
+
+specattn_status check_attn(const specattn_attn_args *a, bool fused)
+{
+    if (!a) { set_error("attention args are NULL"); return SPECATTN_EINVAL; }
+    if (!a->q || !a->k || !a->v || !a->out) { set_error("q, k, v and out must not be NULL"); return SPECATTN_EINVAL; }
+    if (!fused && (!a->indices || !a->counts)) { set_error("indices and counts must not be NULL"); return SPECATTN_EINVAL; }
+    if (a->B <= 0 || a->H_q <= 0 || a->H_kv <= 0 || a->T <= 0 || a->d <= 0 || a->n_max <= 0) { set_error("sizes must be positive"); return SPECATTN_EINVAL; }
+    if (a->dtype != SPECATTN_F32 && a->dtype != SPECATTN_BF16) { set_error("unknown dtype %d", (int)a->dtype); return SPECATTN_EUNSUPPORTED; }
+    if (a->H_q % a->H_kv) { set_error("H_q is not a multiple of H_kv"); return SPECATTN_ESHAPE; }
+    if (a->T > SPECATTN_MAX_T) { set_error("T exceeds %d", SPECATTN_MAX_T); return SPECATTN_ESHAPE; }
+    if (a->d != 64 && a->d != 128) { set_error("d must be 64 or 128"); return SPECATTN_ESHAPE; }
+    if ((a->H_q / a->H_kv) * a->T > 64) { set_error("G*T exceeds 64 query rows per kv head"); return SPECATTN_ESHAPE; }
+    if (!fused && a->idx_capacity < 1) { set_error("idx_capacity must be at least 1"); return SPECATTN_ESHAPE; }
+    if (!fused && a->idx_stride_row < a->idx_capacity) { set_error("idx_stride_row is smaller than idx_capacity"); return SPECATTN_ESHAPE; }
+    const bool paged = a->page_table != nullptr || a->indices_are_physical;
+    if (paged) {
+        if (!is_pow2(a->page_size)) { set_error("page_size must be a power of two"); return SPECATTN_ESHAPE; }
+        if (a->page_table && (int64_t)a->max_pages_per_seq * a->page_size < a->n_max) { set_error("page table is shorter than n_max"); return SPECATTN_ESHAPE; }
+        if (a->kv_stride_page <= 0) { set_error("kv_stride_page must be positive"); return SPECATTN_ESHAPE; }
+    }
+    if (a->kv_stride_n < a->d) { set_error("kv_stride_n is smaller than d"); return SPECATTN_ESHAPE; }
+    const size_t es = a->dtype == SPECATTN_BF16 ? 2 : 4;
+    if (!aligned(a->q, 16) || !aligned(a->k, 16) || !aligned(a->v, 16) || !aligned(a->out, 16)) { set_error("q, k, v and out must be 16-byte aligned"); return SPECATTN_EALIGN; }
+    const int64_t strides[] = {a->q_stride_b, a->q_stride_h, a->q_stride_t, a->kv_stride_b, a->kv_stride_h,
+                               a->kv_stride_n, paged ? a->kv_stride_page : 0};
+    for (int64_t st : strides)
+        if ((st * (int64_t)es) % 16) { set_error("strides must be multiples of 16 bytes"); return SPECATTN_EALIGN; }
+    return SPECATTN_OK;
+}
+
+specattn_status check_workspace(const void *ws, size_t have, size_t need)
+{
+    if (need == 0) return SPECATTN_OK;
+    if (!ws) { set_error("workspace is NULL, %zu bytes needed", need); return SPECATTN_EWORKSPACE; }
+    if (!aligned(ws, 256)) { set_error("workspace must be 256-byte aligned"); return SPECATTN_EWORKSPACE; }
+    if (have < need) { set_error("workspace has %zu bytes, %zu needed", have, need); return SPECATTN_EWORKSPACE; }
+    return SPECATTN_OK;
+}
+
+SelectLaunch make_select(const specattn_select_args *s)
+{
+    SelectLaunch l{};
+    l.probs = s->probs;
+    l.stride_b = s->probs_stride_b;
+    l.stride_h = s->probs_stride_h;
+    l.B = s->B; l.H_kv = s->H_kv; l.n_max = s->n_max;
+    l.seq_lens = s->seq_lens;
+    l.top_p = s->top_p;
+    l.indices = s->indices;
+    l.idx_stride = s->idx_stride_row;
+    l.idx_capacity = s->indices ? s->idx_capacity : 0;
+    l.counts = s->counts;
+    l.thresholds = s->thresholds;
+    l.row_flags = s->row_flags;
+    l.page_table = s->page_table;
+    l.page_shift = s->emit_physical ? log2i(s->page_size) : 0;
+    l.max_pages = s->max_pages_per_seq;
+    l.emit_physical = s->emit_physical;
+    l.block_counts = nullptr;
+    l.blocks_per_row = 0;
+    return l;
+}
+
+AttnLaunch make_attn(const specattn_attn_args *a)
+{
+    AttnLaunch l{};
+    l.q = a->q; l.k = a->k; l.v = a->v;
+    l.dtype = (int)a->dtype;
+    l.B = a->B; l.H_q = a->H_q; l.H_kv = a->H_kv; l.T = a->T; l.d = a->d; l.n_max = a->n_max;
+    l.sm_scale = a->sm_scale > 0.0f ? a->sm_scale : 1.0f / std::sqrt((float)a->d);
+    l.q_stride_b = a->q_stride_b; l.q_stride_h = a->q_stride_h; l.q_stride_t = a->q_stride_t;
+    l.kv_stride_b = a->kv_stride_b; l.kv_stride_h = a->kv_stride_h; l.kv_stride_n = a->kv_stride_n;
+    l.page_table = a->page_table;
+    const bool paged = a->page_table != nullptr || a->indices_are_physical;
+    l.page_shift = paged ? log2i(a->page_size) : 0;
+    l.max_pages = a->max_pages_per_seq;
+    l.kv_stride_page = a->kv_stride_page;
+    l.indices = a->indices;
+    l.idx_stride = a->idx_stride_row;
+    l.counts = a->counts;
+    l.idx_capacity = a->idx_capacity;
+    l.indices_are_physical = a->indices_are_physical;
+    l.out = a->out;
+    l.lse = a->lse;
+    l.workspace = a->workspace;
+    l.workspace_bytes = a->workspace_bytes;
+    l.seq_lens = a->seq_lens;
+    return l;
+}
+
+}  // namespace
+}  // namespace specattn
+
+using namespace specattn;
+
+extern "C" {
+
+specattn_status specattn_topp_select(const specattn_select_args *sel, void *workspace, size_t workspace_bytes,
+                                     void *stream)
+{
+    clear_error();
+    specattn_status st = check_select(sel, false);
+    if (st != SPECATTN_OK) return st;
+    st = check_workspace(workspace, workspace_bytes, specattn_workspace_size(sel, nullptr));
+    if (st != SPECATTN_OK) return st;
+    return launch_select(make_select(sel), static_cast<hipStream_t>(stream));
+}
+
+specattn_status specattn_sparse_decode_attn(const specattn_attn_args *attn, void *stream)
+{
+    clear_error();
+    specattn_status st = check_attn(attn, false);
+    if (st != SPECATTN_OK) return st;
+    st = check_workspace(attn->workspace, attn->workspace_bytes, specattn_workspace_size(nullptr, attn));
+    if (st != SPECATTN_OK) return st;
+    return launch_attn(make_attn(attn), static_cast<hipStream_t>(stream));
+}
+
+specattn_status specattn_fused(const specattn_select_args *sel, const specattn_attn_args *attn, void *stream)
+{
+    clear_error();
+    specattn_status st = check_select(sel, true);
+    if (st != SPECATTN_OK) return st;
+    st = check_attn(attn, true);
+    if (st != SPECATTN_OK) return st;
+    (void)stream;
+    set_error("the fused path is not built yet");
+    return SPECATTN_EUNSUPPORTED;
+}
+
+size_t specattn_workspace_size(const specattn_select_args *sel, const specattn_attn_args *attn)
+{
+    if (!sel && !attn) return 0;
+    if (sel && !attn) return 0;                       // selection keeps its state on chip
+    if (attn->B <= 0 || attn->H_kv <= 0 || attn->H_q <= 0 || attn->T <= 0 || attn->d <= 0) return 0;
+    if (attn->H_q % attn->H_kv) return 0;
+    const int rows = attn->B * attn->H_kv;
+    const int cap = sel ? attn->n_max : attn->idx_capacity;
+    if (cap <= 0) return 0;
+    return attn_workspace_bytes(rows, attn->H_q / attn->H_kv, attn->T, attn->d, cap);
+}
+
+const char *specattn_last_error(void) { return g_error; }
+
+int specattn_version(void) { return 1000; }
+
+}  // extern "C"

@@ -1,0 +1,80 @@
+// Shared host-side declarations of the HIP library (internal; the public ABI is include/specattn.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "specattn.h"
+
+namespace specattn {
+
+// thread-local error text behind specattn_last_error()
+void set_error(const char *fmt, ...);
+void clear_error();
+
+// number of compute units of the current device (256 when no device can be queried)
+int cu_count();
+
+// records a failed launch in the error text; returns SPECATTN_EHIP or SPECATTN_OK
+specattn_status check_launch(const char *what);
+
+// ---- selection -----------------------------------------------------------------------------
+// Per-block kept counts for the fused path: block_counts[r][blk] = number kept among positions
+// [blk*SEL_BLOCK, (blk+1)*SEL_BLOCK) of row r.
+constexpr int SEL_BLOCK = 1024;
+
+struct SelectLaunch {
+    const float *probs;
+    int64_t stride_b, stride_h;
+    int B, H_kv, n_max;
+    const int32_t *seq_lens;
+    float top_p;
+    int32_t *indices;        // may be null (fused path)
+    int64_t idx_stride;
+    int idx_capacity;
+    int32_t *counts;
+    float *thresholds;       // may be null
+    uint32_t *row_flags;     // may be null
+    const int32_t *page_table;
+    int page_shift;          // log2(page_size)
+    int max_pages;
+    int emit_physical;
+    int32_t *block_counts;   // may be null; [rows][blocks_per_row]
+    int blocks_per_row;
+};
+specattn_status launch_select(const SelectLaunch &a, hipStream_t stream);
+
+// ---- attention -----------------------------------------------------------------------------
+struct AttnLaunch {
+    const void *q, *k, *v;
+    int dtype;               // specattn_dtype
+    int B, H_q, H_kv, T, d, n_max;
+    float sm_scale;
+    int64_t q_stride_b, q_stride_h, q_stride_t;
+    int64_t kv_stride_b, kv_stride_h, kv_stride_n;
+    const int32_t *page_table;
+    int page_shift, max_pages;
+    int64_t kv_stride_page;
+    const int32_t *indices;
+    int64_t idx_stride;
+    const int32_t *counts;
+    int idx_capacity;
+    int indices_are_physical;
+    float *out;
+    float *lse;              // may be null
+    void *workspace;
+    size_t workspace_bytes;
+    // fused path: the list is rebuilt on chip from probs / tau / block counts
+    const float *probs;      // null = unfused
+    int64_t probs_stride_b, probs_stride_h;
+    const int32_t *seq_lens;
+    const float *tau;
+    const int32_t *block_counts;
+    int blocks_per_row;
+};
+// number of splits per row the attention launch will use for this shape
+int attn_num_splits(int rows, int idx_capacity);
+size_t attn_workspace_bytes(int rows, int G, int T, int d, int idx_capacity);
+specattn_status launch_attn(const AttnLaunch &a, hipStream_t stream);
+
+}  // namespace specattn

@@ -72,6 +72,8 @@ def draft_probs(
     out = np.zeros((rows, n), dtype=np.float32)
     for r in range(rows):
         ln = int(n if lens is None else lens[r])
+        if ln == 0:
+            continue
         if student_t_nu is None:
             z = rng.standard_normal(ln)
         else:

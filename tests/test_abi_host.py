@@ -1,0 +1,91 @@
+"""Host-only checks of the C ABI: the library loads, exports every declared symbol, and rejects
+bad arguments before anything is launched (no GPU needed, no compute call is made)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2510_27641_amd import binding as sa
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "specattn.h")).read()
+    declared = set(re.findall(r"\b(specattn_[a-z_]+)\s*\(", header))
+    assert declared == set(sa.EXPORTS)
+    lib = sa.load()
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert lib.specattn_version() >= 1000
+    assert sa.last_error() == "" or isinstance(sa.last_error(), str)
+
+
+def _sel(**kw):
+    a = sa.SelectArgs()
+    a.probs, a.counts, a.indices = 0x1000, 0x2000, 0x3000      # never dereferenced on the host
+    a.B, a.H_kv, a.n_max = 2, 4, 1024
+    a.probs_stride_b, a.probs_stride_h = 4096, 1024
+    a.top_p = 0.9
+    a.idx_stride_row, a.idx_capacity = 1024, 1024
+    for k, v in kw.items():
+        setattr(a, k, v)
+    return a
+
+
+def _attn(**kw):
+    a = sa.AttnArgs()
+    a.q, a.k, a.v, a.out = 0x1000, 0x2000, 0x3000, 0x4000
+    a.indices, a.counts = 0x5000, 0x6000
+    a.dtype = sa.BF16
+    a.B, a.H_q, a.H_kv, a.T, a.d, a.n_max = 2, 32, 8, 5, 128, 4096
+    a.q_stride_b, a.q_stride_h, a.q_stride_t = 32 * 5 * 128, 5 * 128, 128
+    a.kv_stride_b, a.kv_stride_h, a.kv_stride_n = 8 * 4096 * 128, 4096 * 128, 128
+    a.idx_stride_row, a.idx_capacity = 4096, 4096
+    for k, v in kw.items():
+        setattr(a, k, v)
+    return a
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(probs=None), sa.EINVAL), (dict(counts=None), sa.EINVAL), (dict(indices=None), sa.EINVAL),
+    (dict(top_p=0.0), sa.EINVAL), (dict(top_p=1.5), sa.EINVAL), (dict(top_p=float("nan")), sa.EINVAL),
+    (dict(B=0), sa.EINVAL), (dict(n_max=(1 << 20) + 1, probs_stride_h=1 << 21, probs_stride_b=1 << 23), sa.ESHAPE),
+    (dict(idx_capacity=0), sa.ESHAPE), (dict(idx_stride_row=8), sa.ESHAPE), (dict(probs_stride_h=512), sa.ESHAPE),
+    (dict(emit_physical=1), sa.EINVAL),
+    (dict(emit_physical=1, page_table=0x9000, page_size=12, max_pages_per_seq=999), sa.ESHAPE),
+    (dict(emit_physical=1, page_table=0x9000, page_size=16, max_pages_per_seq=8), sa.ESHAPE),
+])
+def test_select_argument_errors(kw, status):
+    lib = sa.load()
+    a = _sel(**kw)
+    assert lib.specattn_topp_select(C.byref(a), None, 0, None) == status
+    assert sa.last_error() != ""
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(q=None), sa.EINVAL), (dict(out=None), sa.EINVAL), (dict(indices=None), sa.EINVAL),
+    (dict(H_q=30), sa.ESHAPE), (dict(T=9), sa.ESHAPE), (dict(d=96), sa.ESHAPE), (dict(dtype=7), sa.EUNSUPPORTED),
+    (dict(H_q=128, T=8), sa.ESHAPE), (dict(k=0x2004), sa.EALIGN), (dict(kv_stride_n=132), sa.EALIGN),
+    (dict(kv_stride_n=64), sa.ESHAPE), (dict(idx_capacity=0), sa.ESHAPE),
+    (dict(page_table=0x9000, page_size=10, max_pages_per_seq=1000, kv_stride_page=8 * 16 * 128), sa.ESHAPE),
+    (dict(page_table=0x9000, page_size=16, max_pages_per_seq=1000, kv_stride_page=0), sa.ESHAPE),
+    (dict(), sa.EWORKSPACE),                                      # valid arguments but no workspace
+    (dict(workspace=0x10040, workspace_bytes=1 << 30), sa.EWORKSPACE),   # misaligned workspace
+    (dict(workspace=0x10000, workspace_bytes=16), sa.EWORKSPACE),        # too small
+])
+def test_attention_argument_errors(kw, status):
+    lib = sa.load()
+    a = _attn(**kw)
+    assert lib.specattn_sparse_decode_attn(C.byref(a), None) == status
+    assert sa.last_error() != ""
+
+
+def test_workspace_size_is_monotone_and_zero_for_selection():
+    assert sa.specattn_workspace_size(_sel(), None) == 0
+    small = sa.specattn_workspace_size(None, _attn())
+    big = sa.specattn_workspace_size(None, _attn(B=4))
+    assert 0 < small <= big
+    assert small % 256 == 0
+    assert sa.specattn_workspace_size(None, _attn(H_q=30)) == 0

@@ -1,0 +1,185 @@
+"""GPU parity: specattn_topp_select (HIP, through the C ABI) against the oracle, element by element.
+
+Index lists, counts and thresholds must be bit-exact on every row the oracle does not flag as
+near-boundary (kept or strictly-above mass within 1e-6 of p); flagged rows are counted and their
+mismatches reported.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2510_27641_amd import binding as sa
+from paper_2510_27641_amd import workloads as W
+from helpers import compare_select, dev, gpu_select
+
+pytestmark = pytest.mark.gpu
+
+
+def _check(probs3, top_p, allow_flagged_mismatch=False, **kw):
+    B, H, n = probs3.shape
+    lens = kw.get("seq_lens")
+    row_lens = None if lens is None else np.repeat(np.asarray(lens, dtype=np.int32), H)
+    ref = oracle.topp_select(probs3.reshape(B * H, n), top_p, row_lens)
+    got = gpu_select(probs3, top_p, **kw)
+    flagged, mism = compare_select(got, ref, capacity=kw.get("capacity"))
+    print(f"rows={B * H} n={n} p={top_p} flagged={flagged} flagged_mismatch={mism}")
+    if not allow_flagged_mismatch:
+        assert mism == 0      # not required by the contract, but expected of fp64 suffix sums
+    return got, ref
+
+
+def test_tiny_f32_workload():
+    w = W.tiny_f32()
+    _check(w.probs, w.top_p)
+
+
+def test_llama_layer_8k():
+    w = W.llama8b_layer(seed=1, with_kv=False)
+    _check(w.probs, w.top_p)
+
+
+@pytest.mark.parametrize("n", [1, 2, 5, 63, 64, 65, 1000, 1023, 1025, 2047, 3000, 4097, 8191, 12000,
+                               16385, 20000, 32768, 40000, 65536])
+def test_row_lengths_span_every_kernel_variant(n):
+    rng = np.random.default_rng(n)
+    probs = W.draft_probs(rng, 6, n, recency_len=min(64, n), spike_frac=0.01).reshape(2, 3, n)
+    for p in (0.9, 0.5):
+        _check(probs, p)
+
+
+def test_long_rows_streaming_variant():
+    rng = np.random.default_rng(7)
+    probs = W.draft_probs(rng, 4, 131072).reshape(2, 2, 131072)
+    _check(probs, 0.9)
+    probs = W.draft_probs(rng, 2, 70001).reshape(1, 2, 70001)
+    _check(probs, 0.95)
+
+
+def test_32k_batch_like_the_headline_workload():
+    w = W.llama8b_layer(seed=3, B=4, n=32768, top_p=0.9, with_kv=False)
+    got, ref = _check(w.probs, w.top_p)
+    frac = got["counts"].mean() / 32768
+    assert 0.15 < frac < 0.35
+
+
+@pytest.mark.parametrize("top_p", [1.0, 0.999999, 0.99, 0.8, 0.3, 1e-3, 1e-7])
+def test_top_p_sweep_including_limits(top_p):
+    rng = np.random.default_rng(17)
+    probs = W.draft_probs(rng, 8, 5000).reshape(2, 4, 5000)
+    got, ref = _check(probs, top_p)
+    if top_p == 1.0:
+        assert (got["counts"] == 5000).all()
+    if top_p == 1e-7:
+        assert (got["counts"] == 1).all() and (got["indices"][:, 0] == probs.reshape(8, -1).argmax(1)).all()
+
+
+def test_heavy_tailed_rows_with_underflowed_zeros():
+    w = W.long_context(seed=0, B=1, n=32768, H_kv=4, with_kv=False)
+    assert (w.probs == 0).any()
+    for p in (0.8, 0.99):
+        _check(w.probs, p)
+    # p = 1 on a row whose tail lies below 2^-53 of the row sum: which of those entries still
+    # "add mass" depends on the order of the fp64 sums, so only the flagged-row contract holds
+    _check(w.probs, 1.0, allow_flagged_mismatch=True)
+    w = W.long_context(seed=1, B=1, n=32768, H_kv=4, logit_clip=8.0, with_kv=False)
+    for p in (0.8, 0.9, 0.95, 0.99):
+        _check(w.probs, p)
+
+
+def test_ties_zeros_denormals_and_scaling():
+    rng = np.random.default_rng(23)
+    n = 3000
+    rows = []
+    q = np.round(rng.random(n) * 8) / 8 + 0.125                 # 9 distinct values: massive ties
+    rows.append(q)
+    rows.append(np.full(n, 0.25))                               # uniform
+    z = rng.random(n) ** 4
+    z[rng.random(n) < 0.5] = 0.0                                # half zeros
+    rows.append(z)
+    rows.append(rng.random(n) * 1e-41)                          # all denormal
+    mix = rng.random(n) ** 6
+    mix[::7] *= 1e-39                                           # denormals among normals
+    rows.append(mix)
+    rows.append(rng.random(n) * 2.0 ** 100)                     # huge, far from normalised
+    one = np.zeros(n)
+    one[1234] = 3.0                                             # one non-zero entry
+    rows.append(one)
+    neg0 = rng.random(n)
+    neg0[5] = -0.0
+    rows.append(neg0)
+    probs = np.stack(rows).astype(np.float32).reshape(1, len(rows), n)
+    for p in (0.9, 0.5, 1.0):
+        got, ref = _check(probs, p)
+    assert got["counts"][1] == n and got["counts"][6] == 1
+
+
+def test_invalid_rows_are_flagged_and_empty():
+    rng = np.random.default_rng(29)
+    probs = W.draft_probs(rng, 6, 2000).reshape(1, 6, 2000)
+    probs[0, 1, 77] = np.nan
+    probs[0, 2, 1999] = -1e-3
+    probs[0, 3, :] = 0.0
+    probs[0, 4, 3] = np.inf
+    got, ref = _check(probs, 0.9)
+    assert [bool(f & sa.ROW_INVALID) for f in got["flags"]] == [False, True, True, True, True, False]
+
+
+def test_sequence_lengths_including_zero():
+    rng = np.random.default_rng(31)
+    lens = np.array([4096, 1, 0, 777, 4095], dtype=np.int32)
+    probs = W.draft_probs(rng, 10, 4096, lens=np.repeat(lens, 2)).reshape(5, 2, 4096)
+    probs[3, :, 777:] = 0.5           # garbage past the end must be ignored
+    got, ref = _check(probs, 0.9, seq_lens=lens)
+    assert (got["counts"][4:6] == 0).all()
+
+
+def test_capacity_overflow_truncates_and_reports_true_count():
+    rng = np.random.default_rng(37)
+    probs = W.draft_probs(rng, 4, 8192).reshape(1, 4, 8192)
+    got, ref = _check(probs, 0.95, capacity=512)
+    assert (got["counts"] > 512).all()
+    assert all(f & sa.ROW_OVERFLOW for f in got["flags"])
+
+
+def test_strided_and_unaligned_rows():
+    rng = np.random.default_rng(41)
+    n = 1500
+    base = np.zeros((2, 3, 2048 + 3), dtype=np.float32)
+    base[:, :, 1:1 + n] = W.draft_probs(rng, 6, n).reshape(2, 3, n)
+    t = dev(base)
+    view = t[:, :, 1:1 + n]           # rows start 4 bytes off a 16-byte boundary
+    ref = oracle.topp_select(base[:, :, 1:1 + n].reshape(6, n), 0.9)
+    got = gpu_select(None, 0.9, probs_dev=view)
+    assert compare_select(got, ref)[1] == 0
+
+
+def test_paged_physical_indices():
+    w = W.ragged_paged(seed=2, B=5, len_lo=100, len_hi=6000, H_kv=2, H_q=2, with_kv=False)
+    ref = oracle.topp_select(w.probs.reshape(-1, w.n), w.top_p, w.row_lens())
+    got = gpu_select(w.probs, w.top_p, seq_lens=w.seq_lens, page_table=w.page_table,
+                     page_size=W.PAGE_SIZE, emit_physical=True)
+
+    def to_physical(r, pos):
+        b = r // w.H_kv
+        return w.page_table[b, pos // W.PAGE_SIZE] * W.PAGE_SIZE + pos % W.PAGE_SIZE
+
+    assert compare_select(got, ref, to_physical=to_physical)[1] == 0
+    got2 = gpu_select(w.probs, w.top_p, seq_lens=w.seq_lens)       # logical positions
+    assert compare_select(got2, ref)[1] == 0
+
+
+def test_run_to_run_determinism():
+    w = W.llama8b_layer(seed=5, B=2, n=16384, with_kv=False)
+    a = gpu_select(w.probs, 0.9)
+    for _ in range(3):
+        b = gpu_select(w.probs, 0.9)
+        assert np.array_equal(a["indices"], b["indices"]) and np.array_equal(a["counts"], b["counts"])
+        assert np.array_equal(a["tau"], b["tau"]) and np.array_equal(a["flags"], b["flags"])
+
+
+def test_near_boundary_flag_matches_oracle_on_clear_rows():
+    """The device flag is a diagnostic: it must be set on exact hits and clear on wide margins."""
+    row = np.array([0.5, 0.25, 0.125, 0.0625, 0.0625], dtype=np.float32).reshape(1, 1, 5)
+    assert gpu_select(row, 0.5)["flags"][0] & sa.ROW_NEAR_BOUNDARY
+    assert not gpu_select(row, 0.6)["flags"][0] & sa.ROW_NEAR_BOUNDARY
