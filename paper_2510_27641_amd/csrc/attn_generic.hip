@@ -225,11 +225,17 @@ size_t attn_workspace_bytes(int rows, int G, int T, int d, int idx_capacity)
     const size_t ns = (size_t)attn_num_splits(rows, idx_capacity);
     const size_t qt = (size_t)G * T;
     size_t bytes = (size_t)rows * ns * qt * (size_t)(d + 2) * sizeof(float);
-    return (bytes + 255) & ~(size_t)255;
+    bytes = (bytes + 255) & ~(size_t)255;
+    if (d == 128 && qt <= 32) {                      // the matrix-core variant may take this shape
+        const size_t other = attn_mfma_workspace_bytes(rows, G, T);
+        if (other > bytes) bytes = other;
+    }
+    return bytes;
 }
 
 specattn_status launch_attn(const AttnLaunch &a, hipStream_t stream)
 {
+    if (attn_mfma_supported(a)) return launch_attn_mfma(a, stream);
     const int rows = a.B * a.H_kv;
     const int G = a.H_q / a.H_kv;
     const int QT = G * a.T;

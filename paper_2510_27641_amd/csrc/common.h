@@ -77,4 +77,9 @@ int attn_num_splits(int rows, int idx_capacity);
 size_t attn_workspace_bytes(int rows, int G, int T, int d, int idx_capacity);
 specattn_status launch_attn(const AttnLaunch &a, hipStream_t stream);
 
+// matrix-core variant (bf16, d = 128, G*T <= 32)
+bool attn_mfma_supported(const AttnLaunch &a);
+size_t attn_mfma_workspace_bytes(int rows, int G, int T);
+specattn_status launch_attn_mfma(const AttnLaunch &a, hipStream_t stream);
+
 }  // namespace specattn
