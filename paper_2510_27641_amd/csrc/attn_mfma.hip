@@ -5,13 +5,15 @@
 // tiles, form one sequence; workgroup w takes an equal contiguous share of it, so the split is
 // balanced by the *kept* count whatever the per-row counts are.  A share that crosses row
 // boundaries yields one partial (m, l, o) per (row, workgroup); partial (r, w) lives in slot w + r.
-// merge_streamk_kernel combines a row's partials.
+// The workgroup that delivers a row's last partial combines them into the output.
 //
-// Data path per wave and tile: the 32 gathered K rows and V rows (256 B each) go from HBM straight
-// into LDS (global_load_lds, 16 lanes per row = one full row per quarter wave, XOR-swizzled chunk
-// order), one tile in flight while the previous one is computed.
-//   S^T = K Q^T  : mfma 16x16x32 bf16, A = K fragment (ds_read_b128), B = Q fragment (registers)
-//   softmax      : running max per query row with lazy rescale, exp2, fp32 row sums
+// Data path per wave and tile: the 32 gathered K rows and the 32 V rows (256 B each) go from HBM
+// straight into LDS (global_load_lds: 16 lanes fetch one full row, four rows per instruction,
+// XOR-swizzled chunk order).  Each wave owns one K buffer and one V buffer; the next tile's K is
+// requested as soon as this tile's K fragments are in registers, the next V as soon as this tile's
+// V has been consumed, so 8-16 KiB per wave (64-128 KiB per CU) are always in flight.
+//   S^T = K Q^T    : mfma 16x16x32 bf16, A = K fragment (ds_read_b128), B = Q fragment (registers)
+//   softmax        : running reference max per query row, rescaled only when exceeded by 2^8
 //   O^T += V^T P^T : A = V^T fragment (ds_read_b64_tr_b16), B = P split into bf16 hi + lo parts
 // The mfma output layout puts each query row in a fixed lane, so scores, weights and output
 // accumulators of that row never leave the lane.
@@ -21,7 +23,6 @@ namespace specattn {
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
@@ -31,42 +32,37 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T *)(p))
 #define GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
 
-constexpr int NW = 4;                 // waves per workgroup
+constexpr int NW = 8;                 // waves per workgroup
 constexpr int THREADS = NW * 64;
 constexpr int TILE = 32;              // positions per tile
 constexpr int D = 128;
 constexpr int ROW_BYTES = D * 2;      // one K or V row
 constexpr int TILE_BYTES = TILE * ROW_BYTES;          // 8 KiB per tensor
-constexpr int STAGE_BYTES = 2 * TILE_BYTES;           // K then V
-constexpr int NSTAGE = 2;
-constexpr int WAVE_LDS = NSTAGE * STAGE_BYTES;        // 32 KiB
+constexpr int WAVE_LDS = 2 * TILE_BYTES;              // K buffer, V buffer
 constexpr int MAX_ROWS = 2048;        // rows whose tile prefix fits the LDS table
-constexpr int CHUNK_TILES = 128;      // tiles whose slots are staged in LDS at a time
-constexpr int OPAD = 132;             // floats per query row in the wave-merge dump
+constexpr int CHUNK_TILES = 64;       // tiles whose row offsets are staged in LDS at a time
+constexpr float RESCALE_SLACK = 8.0f; // log2 units the running max may exceed the reference by
 
 // 16-byte chunk c of row `row` is stored in slot c ^ swz(row): makes both the K fragment reads
 // (16 rows x one chunk) and the V transpose reads (8 rows x 32 B) spread over all banks.
 __device__ __forceinline__ int swz(int row) { return ((row & 7) << 1) | ((row >> 3) & 1); }
 
-// Where the gathered rows live.  The index a lane carries is a logical position (contiguous
-// layout) or a pool slot page * page_size + offset (paged layouts; logical positions are turned
-// into slots once, when the index is fetched).
+// Where the gathered rows live.  A list entry is a logical position (contiguous layout) or a pool
+// slot page * page_size + offset (paged layouts; logical positions are mapped through the page
+// table once, when the chunk's list is staged).
 enum Layout { CONTIGUOUS = 0, PAGE_TABLE = 1, PHYSICAL = 2 };
 
 struct KvMap {
     int64_t base, stride_n, stride_page;
     const int32_t *ptab;
     int page_shift;
-    template <int LAYOUT> __device__ __forceinline__ int to_slot(int idx) const
+    // element offset of the row, relative to `base`
+    template <int LAYOUT> __device__ __forceinline__ int64_t rel(int idx) const
     {
-        if (LAYOUT != PAGE_TABLE) return idx;
-        return (ptab[idx >> page_shift] << page_shift) | (idx & ((1 << page_shift) - 1));
-    }
-    template <int LAYOUT> __device__ __forceinline__ int64_t off(int slot) const
-    {
-        if (LAYOUT == CONTIGUOUS) return base + (int64_t)slot * stride_n;
-        return base + (int64_t)(slot >> page_shift) * stride_page +
-               (int64_t)(slot & ((1 << page_shift) - 1)) * stride_n;
+        if (LAYOUT == CONTIGUOUS) return (int64_t)idx * stride_n;
+        const int mask = (1 << page_shift) - 1;
+        const int page = LAYOUT == PAGE_TABLE ? ptab[idx >> page_shift] : (idx >> page_shift);
+        return (int64_t)page * stride_page + (int64_t)(idx & mask) * stride_n;
     }
 };
 
@@ -88,14 +84,14 @@ __device__ __forceinline__ u32x4 lds_read_b128(uint32_t addr)
     asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(addr) : "memory");
     return v;
 }
-// Transposing read: within each group of 16 lanes, lane i receives element i%4 of the four
-// 8-byte rows addressed by lanes i/4, i/4+4, i/4+8 and i/4+12.
 __device__ __forceinline__ uint32_t lds_read_b32(uint32_t addr)
 {
     uint32_t v;
     asm volatile("ds_read_b32 %0, %1" : "=v"(v) : "v"(addr) : "memory");
     return v;
 }
+// Transposing read: within each group of 16 lanes, lane i receives element i%4 of the four
+// 8-byte rows addressed by lanes i/4, i/4+4, i/4+8 and i/4+12.
 __device__ __forceinline__ u32x2 lds_read_tr_b64(uint32_t addr)
 {
     u32x2 v;
@@ -103,17 +99,37 @@ __device__ __forceinline__ u32x2 lds_read_tr_b64(uint32_t addr)
     return v;
 }
 
+// Device-coherent (agent scope) accesses for data that workgroups on different XCDs hand to each
+// other inside one launch: they go past the per-XCD L2, so no cache write-back / invalidate is needed.
+__device__ __forceinline__ void st_agent(float *p, float v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_agent(const float *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 struct Plan {
-    int32_t *tile_prefix;     // [rows + 1] in the workspace (written by workgroup 0, read by the merge)
     float *part_ml;           // [slots][QTP][2]
     float *part_o;            // [slots][QTP][D]
+    int32_t *arrivals;        // [rows] partials written so far (zeroed before the launch)
     int n_wg;
+#ifdef SPECATTN_TIMING
+    long long *timing;        // [n_wg][8] wall-clock stamps (development builds only)
+#endif
 };
+
+#ifdef SPECATTN_TIMING
+#define STAMP(k) do { if (threadIdx.x == 0) plan.timing[blockIdx.x * 8 + (k)] = wall_clock64(); } while (0)
+#else
+#define STAMP(k) do { } while (0)
+#endif
 
 __device__ __forceinline__ int clamp_count(int c, int cap) { return c < 0 ? 0 : (c > cap ? cap : c); }
 
 // Exclusive prefix of tiles per row into pre[0..rows], every workgroup for itself.
-__device__ __forceinline__ void tile_prefix(const AttnLaunch &a, int rows, int *pre, int *wsum)
+__device__ __forceinline__ void tile_prefix(const AttnLaunch &a, int rows, int *pre, int *cnt, int *wsum)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int per = (rows + THREADS - 1) / THREADS;
@@ -121,7 +137,11 @@ __device__ __forceinline__ void tile_prefix(const AttnLaunch &a, int rows, int *
     int local = 0;
     for (int k = 0; k < per; ++k) {
         const int r = r0 + k;
-        if (r < rows) local += (clamp_count(a.counts[r], a.idx_capacity) + TILE - 1) / TILE;
+        if (r < rows) {
+            const int c = clamp_count(a.counts[r], a.idx_capacity);
+            cnt[r] = c;
+            local += (c + TILE - 1) / TILE;
+        }
     }
     int inc = local;
 #pragma unroll
@@ -138,7 +158,7 @@ __device__ __forceinline__ void tile_prefix(const AttnLaunch &a, int rows, int *
         const int r = r0 + k;
         if (r < rows) {
             pre[r] = run;
-            run += (clamp_count(a.counts[r], a.idx_capacity) + TILE - 1) / TILE;
+            run += (cnt[r] + TILE - 1) / TILE;
         }
     }
     if (tid == THREADS - 1) pre[rows] = base + inc;
@@ -151,19 +171,22 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     constexpr int QTP = NQT * 16;
     const int rows = a.B * a.H_kv;
-    int *pre = reinterpret_cast<int *>(smem + NW * WAVE_LDS);          // [rows + 1]
-    int *wsum = pre + MAX_ROWS + 1;                                     // [NW]
-    int *idx_lds = wsum + NW;                                           // [CHUNK_TILES * TILE]
+    int *pre = reinterpret_cast<int *>(smem + NW * WAVE_LDS);          // [MAX_ROWS + 1]
+    int *cnt_lds = pre + MAX_ROWS + 1;                                  // [MAX_ROWS] kept counts, clamped
+    int *wsum = cnt_lds + MAX_ROWS;                                     // [NW], then one flag
+    uint32_t *ent_lds = reinterpret_cast<uint32_t *>(wsum + NW + 1);    // [CHUNK_TILES * TILE] row offsets / 16 B
+    float *ml_lds = reinterpret_cast<float *>(ent_lds);                 // wave merge: [NW][2][32], same space
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l16 = lane & 15, g = lane >> 4;
     char *wave_lds = smem + wave * WAVE_LDS;
-    const uint32_t lds_base = (uint32_t)(uintptr_t)LDS_PTR(char, wave_lds);
-    const uint32_t idx_lds_addr = (uint32_t)(uintptr_t)LDS_PTR(int, idx_lds);
+    const uint32_t ks_addr = (uint32_t)(uintptr_t)LDS_PTR(char, wave_lds);
+    const uint32_t vs_addr = ks_addr + TILE_BYTES;
+    const uint32_t ent_addr = (uint32_t)(uintptr_t)LDS_PTR(uint32_t, ent_lds);
     // K fragment of k-step c: row l16 (+16 per position tile), 16-byte chunk 4c + g
     uint32_t k_off[4];
 #pragma unroll
-    for (int c = 0; c < 4; ++c) k_off[c] = (uint32_t)(l16 * ROW_BYTES + (((4 * c + g) ^ swz(l16)) << 4));
+    for (int c = 0; c < 4; ++c) k_off[c] = ks_addr + (uint32_t)(l16 * ROW_BYTES + (((4 * c + g) ^ swz(l16)) << 4));
     // V^T fragment of dv tile t: source lane points at row 4g + l16/4 (+16 per half), 4 values from
     // column 16t + 4*(l16%4)
     uint32_t v_off[8];
@@ -171,12 +194,17 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
         const int row = 4 * g + (l16 >> 2);
 #pragma unroll
         for (int t = 0; t < 8; ++t)
-            v_off[t] = (uint32_t)(row * ROW_BYTES + (((2 * t + ((l16 & 3) >> 1)) ^ swz(row)) << 4) + ((l16 & 1) << 3));
+            v_off[t] = vs_addr + (uint32_t)(row * ROW_BYTES + (((2 * t + ((l16 & 3) >> 1)) ^ swz(row)) << 4) + ((l16 & 1) << 3));
     }
+    // gather instruction i moves rows 4i .. 4i+3; this lane fetches chunk l16 ^ swz(4i + g), which
+    // depends on i only through i % 4
+    int64_t lane_chunk[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) lane_chunk[j] = (int64_t)((l16 ^ swz(4 * j + g)) << 4);
 
-    tile_prefix(a, rows, pre, wsum);
-    if (blockIdx.x == 0)
-        for (int r = tid; r <= rows; r += THREADS) plan.tile_prefix[r] = pre[r];
+    STAMP(0);
+    tile_prefix(a, rows, pre, cnt_lds, wsum);
+    STAMP(1);
     const int total = pre[rows];
     const int share = (total + plan.n_wg - 1) / plan.n_wg;
     int t0 = blockIdx.x * share;
@@ -195,17 +223,17 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
     const int G = a.H_q / a.H_kv;
     const int QT = G * a.T;
     const float scale2 = a.sm_scale * 1.4426950408889634f;            // scores in log2 units
-    const uint16_t *kbase = static_cast<const uint16_t *>(a.k);
-    const uint16_t *vbase = static_cast<const uint16_t *>(a.v);
 
     while (t0 < t1) {
         while (pre[r + 1] <= t0) ++r;
         const int seg_end = pre[r + 1] < t1 ? pre[r + 1] : t1;
         const int lt_begin = t0 - pre[r], lt_end = seg_end - pre[r];   // local tile range in row r
         const int b = r / a.H_kv, h = r - b * a.H_kv;
-        const int count = clamp_count(a.counts[r], a.idx_capacity);
+        const int count = cnt_lds[r];
         const int32_t *idx = a.indices + (int64_t)r * a.idx_stride;
         const KvMap map = make_map<LAYOUT>(a, b, h);
+        const char *kbh = static_cast<const char *>(a.k) + map.base * 2;
+        const char *vbh = static_cast<const char *>(a.v) + map.base * 2;
 
         // ---- Q fragments: lane (q = l16, g) holds Q[q][32c + 8g .. +8) for c = 0..3 -----------------
         bf16x8 qf[NQT][4];
@@ -223,7 +251,7 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
         }
 
         f32x4 o[NQT][8];                     // O^T[dv = 16t + 4g + i][q = l16]
-        float m_ref[NQT], l_sum[NQT];
+        float m_ref[NQT], l_sum[NQT];        // reference max (log2 units) and sum of weights
 #pragma unroll
         for (int qt = 0; qt < NQT; ++qt) {
             m_ref[qt] = -INFINITY;
@@ -232,154 +260,161 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
             for (int t = 0; t < 8; ++t) o[qt][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
         }
 
-        // gather one tile (32 K rows + 32 V rows) into stage `st`: instruction i moves rows 4i..4i+3,
-        // 16 lanes per row; the slot of row 4i + g comes from the chunk's list in LDS
-        auto issue_tile = [&](int tile_in_chunk, int st) {
-            const uint32_t ia = idx_lds_addr + (uint32_t)((tile_in_chunk * TILE + g) << 2);
-            uint32_t slot[8];
+        // row offsets (in 16-byte units) of the 8 rows this lane helps to fetch for one tile
+        auto read_entries = [&](int tile_in_chunk, uint32_t (&ent)[8]) {
+            const uint32_t ia = ent_addr + (uint32_t)((tile_in_chunk * TILE + g) << 2);
 #pragma unroll
-            for (int i = 0; i < 8; ++i) slot[i] = lds_read_b32(ia + (uint32_t)(i << 4));
+            for (int i = 0; i < 8; ++i) ent[i] = lds_read_b32(ia + (uint32_t)(i << 4));
             asm volatile("s_waitcnt lgkmcnt(0)"
-                         : "+v"(slot[0]), "+v"(slot[1]), "+v"(slot[2]), "+v"(slot[3]), "+v"(slot[4]),
-                           "+v"(slot[5]), "+v"(slot[6]), "+v"(slot[7])
+                         : "+v"(ent[0]), "+v"(ent[1]), "+v"(ent[2]), "+v"(ent[3]), "+v"(ent[4]), "+v"(ent[5]),
+                           "+v"(ent[6]), "+v"(ent[7])
                          :: "memory");
-            char *ks = wave_lds + st * STAGE_BYTES;
-            char *vs = ks + TILE_BYTES;
+        };
+        // gather 32 rows of one tensor into this wave's buffer: 8 instructions of 4 rows x 256 B
+        auto issue = [&](const char *base, char *buf, const uint32_t (&ent)[8]) {
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                const int row = 4 * i + g;
-                const int64_t eo = map.off<LAYOUT>((int)slot[i]) + (int64_t)((l16 ^ swz(row)) * 8);
-                __builtin_amdgcn_global_load_lds(GLOBAL_PTR(kbase + eo), LDS_PTR(void, ks + i * 1024), 16, 0, 0);
-                __builtin_amdgcn_global_load_lds(GLOBAL_PTR(vbase + eo), LDS_PTR(void, vs + i * 1024), 16, 0, 0);
+                const char *src = base + ((int64_t)ent[i] << 4) + lane_chunk[i & 3];
+                __builtin_amdgcn_global_load_lds(GLOBAL_PTR(src), LDS_PTR(void, buf + i * 1024), 16, 0, 0);
             }
         };
 
         for (int ch_begin = lt_begin; ch_begin < lt_end; ch_begin += CHUNK_TILES) {
-        const int ch_end = (ch_begin + CHUNK_TILES) < lt_end ? (ch_begin + CHUNK_TILES) : lt_end;
-        // ---- stage this chunk's slots in LDS; entries past the end of the list repeat the last
-        //      kept position (their scores are masked) so that every gather stays in bounds -----------
-        __syncthreads();
-        for (int j = tid; j < (ch_end - ch_begin) * TILE; j += THREADS) {
-            int jj = ch_begin * TILE + j;
-            jj = jj < count ? jj : count - 1;
-            idx_lds[j] = map.to_slot<LAYOUT>(idx[jj]);
-        }
-        __syncthreads();
+            const int ch_end = (ch_begin + CHUNK_TILES) < lt_end ? (ch_begin + CHUNK_TILES) : lt_end;
+            // ---- stage this chunk's row offsets in LDS; entries past the end of the list repeat the
+            //      last kept position (their scores are masked) so that every gather stays in bounds --
+            __syncthreads();
+            for (int j = tid; j < (ch_end - ch_begin) * TILE; j += THREADS) {
+                int jj = ch_begin * TILE + j;
+                jj = jj < count ? jj : count - 1;
+                ent_lds[j] = (uint32_t)(map.rel<LAYOUT>(idx[jj]) >> 3);
+            }
+            __syncthreads();
+            // Touch the Q fragments here, so that the compiler's wait for their loads sits outside the
+            // tile loop (inside it, it would also wait for the gathers of the next tile).
+#pragma unroll
+            for (int qt = 0; qt < NQT; ++qt)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) asm volatile("" :: "v"(qf[qt][c]));
+            STAMP(2);
 
-        int lt = ch_begin + wave;
-        int stage = 0;
-        if (lt < ch_end) issue_tile(lt - ch_begin, 0);
-        for (; lt < ch_end; lt += NW) {
-            // The gathers are not tracked by the compiler's wait insertion: all but the 16 just
-            // issued (the next tile) must have landed before this tile is read from LDS.
-            if (lt + NW < ch_end) {
-                issue_tile(lt + NW - ch_begin, stage ^ 1);
-                asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
-            } else {
-                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            // The gathers are not tracked by the compiler's wait insertion; every wait on them is
+            // written out.  Per wave the order of issue is K(t), V(t), K(t+1), V(t+1), ...
+            uint32_t ent[8];
+            int lt = ch_begin + wave;
+            if (lt < ch_end) {
+                read_entries(lt - ch_begin, ent);
+                issue(kbh, wave_lds, ent);
+                issue(vbh, wave_lds + TILE_BYTES, ent);
             }
-            // ---- S^T[pos][q] = K Q^T ---------------------------------------------------------------
-            // LDS reads of the staged tile are issued by hand: the compiler must neither add waits
-            // for the gathers still in flight nor move these reads across the waits above.
-            const uint32_t ks_addr = lds_base + (uint32_t)(stage * STAGE_BYTES);
-            const uint32_t vs_addr = ks_addr + TILE_BYTES;
-            f32x4 s[NQT][2];
-            {
-                u32x4 kf[2][4];
-#pragma unroll
-                for (int pt = 0; pt < 2; ++pt)
-#pragma unroll
-                    for (int c = 0; c < 4; ++c)
-                        kf[pt][c] = lds_read_b128(ks_addr + k_off[c] + (uint32_t)(pt * 16 * ROW_BYTES));
-                asm volatile("s_waitcnt lgkmcnt(0)"
-                             : "+v"(kf[0][0]), "+v"(kf[0][1]), "+v"(kf[0][2]), "+v"(kf[0][3]),
-                               "+v"(kf[1][0]), "+v"(kf[1][1]), "+v"(kf[1][2]), "+v"(kf[1][3])
-                             :: "memory");
-#pragma unroll
-                for (int pt = 0; pt < 2; ++pt)
-#pragma unroll
-                    for (int qt = 0; qt < NQT; ++qt) {
-                        f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                        for (int c = 0; c < 4; ++c)
-                            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[pt][c]),
-                                                                          qf[qt][c], acc, 0, 0, 0);
-                        s[qt][pt] = acc;
-                    }
-            }
+            for (; lt < ch_end; lt += NW) {
+                const bool has_next = lt + NW < ch_end;
+                asm volatile("s_waitcnt vmcnt(8)" ::: "memory");        // K(t) landed; V(t) may be in flight
 
-            // ---- softmax weights, lane (q = l16, g) holds positions 16pt + 4g + i -------------------
-            const int remaining = count - lt * TILE;               // > 0
-            bf16x8 p_hi[NQT], p_lo[NQT];
+                // ---- S^T[pos][q] = K Q^T -----------------------------------------------------------
+                f32x4 s[NQT][2];
+                {
+                    u32x4 kf[2][4];
 #pragma unroll
-            for (int qt = 0; qt < NQT; ++qt) {
-                float x[8];
-                float mloc = -INFINITY;
+                    for (int pt = 0; pt < 2; ++pt)
 #pragma unroll
-                for (int pt = 0; pt < 2; ++pt)
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const int slot = 16 * pt + 4 * g + i;
-                        const float v = slot < remaining ? s[qt][pt][i] * scale2 : -INFINITY;
-                        x[pt * 4 + i] = v;
-                        mloc = fmaxf(mloc, v);
+                        for (int c = 0; c < 4; ++c) kf[pt][c] = lds_read_b128(k_off[c] + (uint32_t)(pt * 16 * ROW_BYTES));
+                    asm volatile("s_waitcnt lgkmcnt(0)"
+                                 : "+v"(kf[0][0]), "+v"(kf[0][1]), "+v"(kf[0][2]), "+v"(kf[0][3]),
+                                   "+v"(kf[1][0]), "+v"(kf[1][1]), "+v"(kf[1][2]), "+v"(kf[1][3])
+                                 :: "memory");
+                    if (has_next) {                                    // the K buffer is free again
+                        read_entries(lt + NW - ch_begin, ent);
+                        issue(kbh, wave_lds, ent);
                     }
-                if (__any(mloc > m_ref[qt])) {                     // lazy rescale: rare after the first tiles
-                    float mx = fmaxf(mloc, __shfl_xor(mloc, 16, 64));
-                    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-                    const float mnew = fmaxf(m_ref[qt], mx);
-                    const float alpha = (m_ref[qt] == -INFINITY) ? 0.0f : exp2f(m_ref[qt] - mnew);
-                    l_sum[qt] *= alpha;
 #pragma unroll
-                    for (int t = 0; t < 8; ++t) o[qt][t] *= alpha;
-                    m_ref[qt] = mnew;
-                }
-                const float mr = (m_ref[qt] == -INFINITY) ? 0.0f : m_ref[qt];
-                float psum = 0.0f;
+                    for (int pt = 0; pt < 2; ++pt)
 #pragma unroll
-                for (int e = 0; e < 8; e += 2) {
-                    const float p0 = exp2f(x[e] - mr), p1 = exp2f(x[e + 1] - mr);
-                    psum += p0 + p1;
-                    const bf16x2 hi = __builtin_convertvector((f32x2){p0, p1}, bf16x2);
-                    const f32x2 back = __builtin_convertvector(hi, f32x2);
-                    const bf16x2 lo = __builtin_convertvector((f32x2){p0 - back[0], p1 - back[1]}, bf16x2);
-                    p_hi[qt][e] = hi[0]; p_hi[qt][e + 1] = hi[1];
-                    p_lo[qt][e] = lo[0]; p_lo[qt][e + 1] = lo[1];
+                        for (int qt = 0; qt < NQT; ++qt) {
+                            f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                            for (int c = 0; c < 4; ++c)
+                                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[pt][c]),
+                                                                              qf[qt][c], acc, 0, 0, 0);
+                            s[qt][pt] = acc;
+                        }
                 }
-                l_sum[qt] += psum;
-            }
 
-            // ---- O^T += V^T P^T ---------------------------------------------------------------------
+                // ---- softmax weights; lane (q = l16, g) holds positions 16pt + 4g + i ---------------
+                const int remaining = count - lt * TILE;               // > 0; < TILE only on a row's last tile
+                bf16x8 p_hi[NQT], p_lo[NQT];
 #pragma unroll
-            for (int tb = 0; tb < 8; tb += 4) {                    // four 16-wide dv tiles per batch
-                u32x2 vh[4][2];
+                for (int qt = 0; qt < NQT; ++qt) {
+                    float x[8];
 #pragma unroll
-                for (int t = 0; t < 4; ++t)
+                    for (int e = 0; e < 8; ++e) x[e] = s[qt][e >> 2][e & 3];
+                    if (remaining < TILE) {
 #pragma unroll
-                    for (int hh = 0; hh < 2; ++hh)
-                        vh[t][hh] = lds_read_tr_b64(vs_addr + v_off[tb + t] + (uint32_t)(hh * 16 * ROW_BYTES));
-                asm volatile("s_waitcnt lgkmcnt(0)"
-                             : "+v"(vh[0][0]), "+v"(vh[0][1]), "+v"(vh[1][0]), "+v"(vh[1][1]),
-                               "+v"(vh[2][0]), "+v"(vh[2][1]), "+v"(vh[3][0]), "+v"(vh[3][1])
-                             :: "memory");
+                        for (int e = 0; e < 8; ++e)
+                            if (16 * (e >> 2) + 4 * g + (e & 3) >= remaining) x[e] = -INFINITY;
+                    }
+                    const float mloc = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])),
+                                             fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7]))) * scale2;
+                    if (__any(mloc > m_ref[qt] + RESCALE_SLACK)) {     // first tile, then rare
+                        float mx = fmaxf(mloc, __shfl_xor(mloc, 16, 64));
+                        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+                        const float mnew = fmaxf(m_ref[qt], mx);
+                        const float alpha = (m_ref[qt] == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(m_ref[qt] - mnew);
+                        l_sum[qt] *= alpha;
 #pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    const u32x4 both = (u32x4){vh[t][0][0], vh[t][0][1], vh[t][1][0], vh[t][1][1]};
-                    const bf16x8 vf = __builtin_bit_cast(bf16x8, both);
+                        for (int t = 0; t < 8; ++t) o[qt][t] *= alpha;
+                        m_ref[qt] = mnew;
+                    }
+                    const float mr = (m_ref[qt] == -INFINITY) ? 0.0f : m_ref[qt];
+                    float psum = 0.0f;
 #pragma unroll
-                    for (int qt = 0; qt < NQT; ++qt) {
-                        o[qt][tb + t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, p_hi[qt], o[qt][tb + t], 0, 0, 0);
-                        o[qt][tb + t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, p_lo[qt], o[qt][tb + t], 0, 0, 0);
+                    for (int e = 0; e < 8; e += 2) {
+                        const float p0 = __builtin_amdgcn_exp2f(fmaf(x[e], scale2, -mr));
+                        const float p1 = __builtin_amdgcn_exp2f(fmaf(x[e + 1], scale2, -mr));
+                        psum += p0 + p1;
+                        const bf16x2 hi = __builtin_convertvector((f32x2){p0, p1}, bf16x2);
+                        const f32x2 back = __builtin_convertvector(hi, f32x2);
+                        const bf16x2 lo = __builtin_convertvector((f32x2){p0 - back[0], p1 - back[1]}, bf16x2);
+                        p_hi[qt][e] = hi[0]; p_hi[qt][e + 1] = hi[1];
+                        p_lo[qt][e] = lo[0]; p_lo[qt][e + 1] = lo[1];
+                    }
+                    l_sum[qt] += psum;
+                }
+
+                // ---- O^T += V^T P^T -----------------------------------------------------------------
+                if (has_next) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");   // V(t) landed; K(t+1) in flight
+                else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+                for (int tb = 0; tb < 8; tb += 4) {                    // four 16-wide dv tiles per batch
+                    u32x2 vh[4][2];
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+#pragma unroll
+                        for (int hh = 0; hh < 2; ++hh)
+                            vh[t][hh] = lds_read_tr_b64(v_off[tb + t] + (uint32_t)(hh * 16 * ROW_BYTES));
+                    asm volatile("s_waitcnt lgkmcnt(0)"
+                                 : "+v"(vh[0][0]), "+v"(vh[0][1]), "+v"(vh[1][0]), "+v"(vh[1][1]),
+                                   "+v"(vh[2][0]), "+v"(vh[2][1]), "+v"(vh[3][0]), "+v"(vh[3][1])
+                                 :: "memory");
+                    if (tb == 4 && has_next) issue(vbh, wave_lds + TILE_BYTES, ent);   // the V buffer is free again
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        const u32x4 both = (u32x4){vh[t][0][0], vh[t][0][1], vh[t][1][0], vh[t][1][1]};
+                        const bf16x8 vf = __builtin_bit_cast(bf16x8, both);
+#pragma unroll
+                        for (int qt = 0; qt < NQT; ++qt) {
+                            o[qt][tb + t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, p_hi[qt], o[qt][tb + t], 0, 0, 0);
+                            o[qt][tb + t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, p_lo[qt], o[qt][tb + t], 0, 0, 0);
+                        }
                     }
                 }
             }
-            stage ^= 1;
-        }
         }   // chunks
 
         // ---- combine the waves of this workgroup, write the partial of (row r, this workgroup) -----
-        __syncthreads();                         // every wave is done with its stages
-        float *dump = reinterpret_cast<float *>(wave_lds);     // [QTP][OPAD] then m[QTP], l[QTP]
+        STAMP(3);
+        __syncthreads();                         // every wave is done with its buffers and with ent_lds
+        float *dump = reinterpret_cast<float *>(wave_lds);     // [QTP][D], 4-float blocks XOR-swizzled by q
 #pragma unroll
         for (int qt = 0; qt < NQT; ++qt) {
             float l = l_sum[qt];
@@ -388,72 +423,90 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
             const int q = qt * 16 + l16;
 #pragma unroll
             for (int t = 0; t < 8; ++t)
-                *reinterpret_cast<f32x4 *>(dump + q * OPAD + 16 * t + 4 * g) = o[qt][t];
-            if (g == 0) { dump[QTP * OPAD + q] = m_ref[qt]; dump[QTP * OPAD + QTP + q] = l; }
+                *reinterpret_cast<f32x4 *>(dump + q * D + (((4 * t + g) ^ (q & 31)) << 2)) = o[qt][t];
+            if (g == 0) { ml_lds[wave * 64 + q] = m_ref[qt]; ml_lds[wave * 64 + 32 + q] = l; }
         }
         __syncthreads();
+        // Workgroups w0..w1 share row r.  A row owned by one workgroup is finished here; otherwise the
+        // partial goes to slot w + r and the workgroup that delivers the last partial merges them all.
+        const int w0 = pre[r] / share, w1 = (pre[r + 1] - 1) / share;
         const int slot = blockIdx.x + r;
         float *po = plan.part_o + (int64_t)slot * QTP * D;
         float *pml = plan.part_ml + (int64_t)slot * QTP * 2;
         for (int e = tid; e < QT * D; e += THREADS) {
             const int q = e >> 7, dv = e & (D - 1);
+            const int col = (((dv >> 2) ^ (q & 31)) << 2) | (dv & 3);
             float m = -INFINITY;
 #pragma unroll
-            for (int w = 0; w < NW; ++w)
-                m = fmaxf(m, reinterpret_cast<const float *>(smem + w * WAVE_LDS)[QTP * OPAD + q]);
+            for (int w = 0; w < NW; ++w) m = fmaxf(m, ml_lds[w * 64 + q]);
             float acc = 0.0f, l = 0.0f;
 #pragma unroll
             for (int w = 0; w < NW; ++w) {
-                const float *dw = reinterpret_cast<const float *>(smem + w * WAVE_LDS);
-                const float mw = dw[QTP * OPAD + q];
-                const float f = (mw == -INFINITY) ? 0.0f : exp2f(mw - m);
-                acc += f * dw[q * OPAD + dv];
-                l += f * dw[QTP * OPAD + QTP + q];
+                const float mw = ml_lds[w * 64 + q];
+                const float f = (mw == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(mw - m);
+                acc += f * reinterpret_cast<const float *>(smem + w * WAVE_LDS)[q * D + col];
+                l += f * ml_lds[w * 64 + 32 + q];
             }
-            po[e] = acc;
-            if (dv == 0) { pml[2 * q] = m; pml[2 * q + 1] = l; }
+            if (w0 == w1) {
+                const int gh = q / a.T, tt = q - gh * a.T;
+                const int64_t orow = ((int64_t)b * a.H_q + (h * G + gh)) * a.T + tt;
+                a.out[orow * D + dv] = l > 0.0f ? acc / l : 0.0f;
+                if (a.lse && dv == 0) a.lse[orow] = l > 0.0f ? (m + log2f(l)) * 0.6931471805599453f : -INFINITY;
+            } else {
+                st_agent(po + e, acc);
+                if (dv == 0) { st_agent(pml + 2 * q, m); st_agent(pml + 2 * q + 1, l); }
+            }
         }
-        __syncthreads();                         // dumps are read before the stages are reused
-        t0 = seg_end;
+        if (w0 != w1) {
+            // Partials are written and read with device-coherent accesses, so no cache write-back or
+            // invalidation is needed: once this workgroup's stores have completed, it counts itself in.
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            if (tid == 0)
+                wsum[NW] = __hip_atomic_fetch_add(&plan.arrivals[r], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == w1 - w0;
+            __syncthreads();
+            if (wsum[NW]) {                      // uniform: this workgroup delivered the last partial
+                for (int e = tid; e < QT * D; e += THREADS) {
+                    const int q = e >> 7, dv = e & (D - 1);
+                    float m = -INFINITY;
+                    for (int w = w0; w <= w1; ++w) m = fmaxf(m, ld_agent(plan.part_ml + ((int64_t)(w + r) * QTP + q) * 2));
+                    float acc = 0.0f, l = 0.0f;
+                    for (int w = w0; w <= w1; ++w) {
+                        const float *pm = plan.part_ml + ((int64_t)(w + r) * QTP + q) * 2;
+                        const float mw = ld_agent(pm);
+                        const float f = (mw == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(mw - m);
+                        acc += f * ld_agent(plan.part_o + ((int64_t)(w + r) * QTP + q) * D + dv);
+                        l += f * ld_agent(pm + 1);
+                    }
+                    const int gh = q / a.T, tt = q - gh * a.T;
+                    const int64_t orow = ((int64_t)b * a.H_q + (h * G + gh)) * a.T + tt;
+                    a.out[orow * D + dv] = l > 0.0f ? acc / l : 0.0f;
+                    if (a.lse && dv == 0) a.lse[orow] = l > 0.0f ? (m + log2f(l)) * 0.6931471805599453f : -INFINITY;
+                }
+            }
+        }
+        t0 = seg_end;                            // the next segment starts with a barrier of its own
+        STAMP(4);
     }
 }
 
-// One workgroup per (row, query row): combine the partials (r, w) of the workgroups that touched row r.
-__global__ void merge_streamk_kernel(AttnLaunch a, Plan plan, int qtp)
+// Before the main kernel: clear the arrival counters and give rows without any kept position their
+// result (out = 0, lse = -inf), since no workgroup visits them.
+__global__ void attn_prep_kernel(AttnLaunch a, Plan plan)
 {
+    const int r = blockIdx.x;
     const int G = a.H_q / a.H_kv;
     const int QT = G * a.T;
-    const int rows = a.B * a.H_kv;
-    const int r = blockIdx.x / QT, qi = blockIdx.x - r * QT;
+    if (threadIdx.x == 0) plan.arrivals[r] = 0;
+    if (clamp_count(a.counts[r], a.idx_capacity) > 0) return;
     const int b = r / a.H_kv, h = r - b * a.H_kv;
-    const int gh = qi / a.T, t = qi - gh * a.T;
-    const int64_t orow = ((int64_t)b * a.H_q + (h * G + gh)) * a.T + t;
-    const int total = plan.tile_prefix[rows];
-    const int p0 = plan.tile_prefix[r], p1 = plan.tile_prefix[r + 1];
-    if (p0 == p1) {
-        for (int dd = threadIdx.x; dd < D; dd += blockDim.x) a.out[orow * D + dd] = 0.0f;
-        if (a.lse && threadIdx.x == 0) a.lse[orow] = -INFINITY;
-        return;
+    for (int e = threadIdx.x; e < QT * D; e += blockDim.x) {
+        const int q = e >> 7, dv = e & (D - 1);
+        const int gh = q / a.T, tt = q - gh * a.T;
+        const int64_t orow = ((int64_t)b * a.H_q + (h * G + gh)) * a.T + tt;
+        a.out[orow * D + dv] = 0.0f;
+        if (a.lse && dv == 0) a.lse[orow] = -INFINITY;
     }
-    const int share = (total + plan.n_wg - 1) / plan.n_wg;
-    const int w0 = p0 / share, w1 = (p1 - 1) / share;
-    float m = -INFINITY;
-    for (int w = w0; w <= w1; ++w) m = fmaxf(m, plan.part_ml[((int64_t)(w + r) * qtp + qi) * 2]);
-    float l = 0.0f;
-    for (int w = w0; w <= w1; ++w) {
-        const float *p = plan.part_ml + ((int64_t)(w + r) * qtp + qi) * 2;
-        if (p[0] != -INFINITY) l += exp2f(p[0] - m) * p[1];
-    }
-    for (int dd = threadIdx.x; dd < D; dd += blockDim.x) {
-        float o = 0.0f;
-        for (int w = w0; w <= w1; ++w) {
-            const float mw = plan.part_ml[((int64_t)(w + r) * qtp + qi) * 2];
-            if (mw != -INFINITY) o += exp2f(mw - m) * plan.part_o[((int64_t)(w + r) * qtp + qi) * D + dd];
-        }
-        a.out[orow * D + dd] = l > 0.0f ? o / l : 0.0f;
-    }
-    // m is in log2 units of the scaled scores
-    if (a.lse && threadIdx.x == 0) a.lse[orow] = l > 0.0f ? (m + log2f(l)) * 0.6931471805599453f : -INFINITY;
 }
 
 }  // namespace
@@ -470,7 +523,7 @@ size_t attn_mfma_workspace_bytes(int rows, int G, int T)
 {
     const size_t qtp = (G * T <= 16) ? 16 : 32;
     const size_t slots = (size_t)attn_mfma_workgroups() + rows;
-    size_t bytes = (((size_t)rows + 1) * sizeof(int32_t) + 255) & ~(size_t)255;
+    size_t bytes = ((size_t)rows * sizeof(int32_t) + 255) & ~(size_t)255;              // arrival counters
     bytes += slots * qtp * (D + 2) * sizeof(float);
     return (bytes + 255) & ~(size_t)255;
 }
@@ -485,11 +538,11 @@ specattn_status launch_attn_mfma(const AttnLaunch &a, hipStream_t stream)
     plan.n_wg = attn_mfma_workgroups();
     const size_t slots = (size_t)plan.n_wg + rows;
     char *ws = static_cast<char *>(a.workspace);
-    plan.tile_prefix = reinterpret_cast<int32_t *>(ws);
-    ws += (((size_t)rows + 1) * sizeof(int32_t) + 255) & ~(size_t)255;
+    plan.arrivals = reinterpret_cast<int32_t *>(ws);
+    ws += ((size_t)rows * sizeof(int32_t) + 255) & ~(size_t)255;
     plan.part_ml = reinterpret_cast<float *>(ws);
     plan.part_o = plan.part_ml + slots * qtp * 2;
-    const size_t lds = (size_t)NW * WAVE_LDS + (MAX_ROWS + 1 + NW + CHUNK_TILES * TILE) * sizeof(int);
+    const size_t lds = (size_t)NW * WAVE_LDS + (2 * MAX_ROWS + 1 + NW + 1 + CHUNK_TILES * TILE) * sizeof(int);
     const int layout = a.indices_are_physical ? PHYSICAL : (a.page_table ? PAGE_TABLE : CONTIGUOUS);
     const void *fn = nullptr;
 #define PICK(NQT, LAY) if (qtp == 16 * NQT && layout == LAY) fn = reinterpret_cast<const void *>(&attn_mfma_kernel<NQT, LAY>);
@@ -505,16 +558,20 @@ specattn_status launch_attn_mfma(const AttnLaunch &a, hipStream_t stream)
         }
         for (const void *&c : configured) if (!c) { c = fn; break; }
     }
+#ifdef SPECATTN_TIMING
+    extern long long *g_specattn_timing;
+    plan.timing = g_specattn_timing;
+#endif
+    hipLaunchKernelGGL(attn_prep_kernel, dim3(rows), dim3(128), 0, stream, a, plan);
+    specattn_status st = check_launch("attn_prep_kernel");
+    if (st != SPECATTN_OK) return st;
     void *kargs[] = {const_cast<AttnLaunch *>(&a), &plan};
     if (hipLaunchKernel(fn, dim3(plan.n_wg), dim3(THREADS), kargs, lds, stream) != hipSuccess) {
         set_error("attn_mfma_kernel: launch failed");
         (void)hipGetLastError();
         return SPECATTN_EHIP;
     }
-    specattn_status st = check_launch("attn_mfma_kernel");
-    if (st != SPECATTN_OK) return st;
-    hipLaunchKernelGGL(merge_streamk_kernel, dim3(rows * QT), dim3(D), 0, stream, a, plan, qtp);
-    return check_launch("merge_streamk_kernel");
+    return check_launch("attn_mfma_kernel");
 }
 
 }  // namespace specattn
