@@ -5,7 +5,7 @@
 // tiles, form one sequence; workgroup w takes an equal contiguous share of it, so the split is
 // balanced by the *kept* count whatever the per-row counts are.  A share that crosses row
 // boundaries yields one partial (m, l, o) per (row, workgroup); partial (r, w) lives in slot w + r.
-// The workgroup that delivers a row's last partial combines them into the output.
+// merge_partials_kernel combines a row's partials.
 //
 // Data path per wave and tile: the 32 gathered K rows and the 32 V rows (256 B each) go from HBM
 // straight into LDS (global_load_lds: 16 lanes fetch one full row, four rows per instruction,
@@ -41,6 +41,7 @@ constexpr int TILE_BYTES = TILE * ROW_BYTES;          // 8 KiB per tensor
 constexpr int WAVE_LDS = 2 * TILE_BYTES;              // K buffer, V buffer
 constexpr int MAX_ROWS = 2048;        // rows whose tile prefix fits the LDS table
 constexpr int CHUNK_TILES = 64;       // tiles whose row offsets are staged in LDS at a time
+constexpr int SEG_COST = 10;          // cost of starting a row segment, in tiles
 constexpr float RESCALE_SLACK = 8.0f; // log2 units the running max may exceed the reference by
 
 // 16-byte chunk c of row `row` is stored in slot c ^ swz(row): makes both the K fragment reads
@@ -77,43 +78,64 @@ template <int LAYOUT> __device__ __forceinline__ KvMap make_map(const AttnLaunch
     return m;
 }
 
-// LDS reads by byte address; the caller waits (s_waitcnt lgkmcnt) before using the result.
-__device__ __forceinline__ u32x4 lds_read_b128(uint32_t addr)
+// LDS reads are issued by hand, each batch together with its wait in one asm block: the compiler
+// then neither adds waits for the gathers still in flight (it cannot tell them from the data being
+// read) nor touches a result register before the data has arrived.
+struct KFrags { u32x4 f[2][4]; };     // [position tile][k-step]
+__device__ __forceinline__ void lds_read_k(KFrags &k, const uint32_t (&addr)[4])
 {
-    u32x4 v;
-    asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(addr) : "memory");
-    return v;
+    asm volatile(
+        "ds_read_b128 %0, %8\n ds_read_b128 %1, %9\n ds_read_b128 %2, %10\n ds_read_b128 %3, %11\n"
+        "ds_read_b128 %4, %8 offset:4096\n ds_read_b128 %5, %9 offset:4096\n"
+        "ds_read_b128 %6, %10 offset:4096\n ds_read_b128 %7, %11 offset:4096\n"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&v"(k.f[0][0]), "=&v"(k.f[0][1]), "=&v"(k.f[0][2]), "=&v"(k.f[0][3]),
+          "=&v"(k.f[1][0]), "=&v"(k.f[1][1]), "=&v"(k.f[1][2]), "=&v"(k.f[1][3])
+        : "v"(addr[0]), "v"(addr[1]), "v"(addr[2]), "v"(addr[3])
+        : "memory");
 }
-__device__ __forceinline__ uint32_t lds_read_b32(uint32_t addr)
+// Transposing reads: within each group of 16 lanes, lane i receives element i%4 of the four 8-byte
+// rows addressed by lanes i/4, i/4+4, i/4+8 and i/4+12.  Four dv tiles, both halves of the tile.
+struct VFrags { u32x2 f[4][2]; };     // [dv tile][half]
+__device__ __forceinline__ void lds_read_v(VFrags &v, uint32_t a0, uint32_t a1, uint32_t a2, uint32_t a3)
+{
+    asm volatile(
+        "ds_read_b64_tr_b16 %0, %8\n ds_read_b64_tr_b16 %1, %8 offset:4096\n"
+        "ds_read_b64_tr_b16 %2, %9\n ds_read_b64_tr_b16 %3, %9 offset:4096\n"
+        "ds_read_b64_tr_b16 %4, %10\n ds_read_b64_tr_b16 %5, %10 offset:4096\n"
+        "ds_read_b64_tr_b16 %6, %11\n ds_read_b64_tr_b16 %7, %11 offset:4096\n"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&v"(v.f[0][0]), "=&v"(v.f[0][1]), "=&v"(v.f[1][0]), "=&v"(v.f[1][1]),
+          "=&v"(v.f[2][0]), "=&v"(v.f[2][1]), "=&v"(v.f[3][0]), "=&v"(v.f[3][1])
+        : "v"(a0), "v"(a1), "v"(a2), "v"(a3)
+        : "memory");
+}
+// Row offsets of the 8 rows a lane helps to fetch: entries addr, addr + 16 B, ...
+__device__ __forceinline__ void lds_read_entries(uint32_t (&e)[8], uint32_t addr)
+{
+    asm volatile(
+        "ds_read_b32 %0, %8\n ds_read_b32 %1, %8 offset:16\n ds_read_b32 %2, %8 offset:32\n"
+        "ds_read_b32 %3, %8 offset:48\n ds_read_b32 %4, %8 offset:64\n ds_read_b32 %5, %8 offset:80\n"
+        "ds_read_b32 %6, %8 offset:96\n ds_read_b32 %7, %8 offset:112\n"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&v"(e[0]), "=&v"(e[1]), "=&v"(e[2]), "=&v"(e[3]), "=&v"(e[4]), "=&v"(e[5]), "=&v"(e[6]), "=&v"(e[7])
+        : "v"(addr)
+        : "memory");
+}
+// Wave-wide fetch-and-add on an LDS counter: lane 0 adds 1, the others add 0, so lane 0 reads the
+// value before the wave's own increment; that value is returned to the whole wave.
+__device__ __forceinline__ int lds_claim(uint32_t addr, int lane)
 {
     uint32_t v;
-    asm volatile("ds_read_b32 %0, %1" : "=v"(v) : "v"(addr) : "memory");
-    return v;
-}
-// Transposing read: within each group of 16 lanes, lane i receives element i%4 of the four
-// 8-byte rows addressed by lanes i/4, i/4+4, i/4+8 and i/4+12.
-__device__ __forceinline__ u32x2 lds_read_tr_b64(uint32_t addr)
-{
-    u32x2 v;
-    asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(v) : "v"(addr) : "memory");
-    return v;
-}
-
-// Device-coherent (agent scope) accesses for data that workgroups on different XCDs hand to each
-// other inside one launch: they go past the per-XCD L2, so no cache write-back / invalidate is needed.
-__device__ __forceinline__ void st_agent(float *p, float v)
-{
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ float ld_agent(const float *p)
-{
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const uint32_t inc = lane == 0 ? 1u : 0u;
+    asm volatile("ds_add_rtn_u32 %0, %1, %2\n s_waitcnt lgkmcnt(0)" : "=&v"(v) : "v"(addr), "v"(inc) : "memory");
+    return (int)__builtin_amdgcn_readfirstlane(v);
 }
 
 struct Plan {
     float *part_ml;           // [slots][QTP][2]
     float *part_o;            // [slots][QTP][D]
-    int32_t *arrivals;        // [rows] partials written so far (zeroed before the launch)
+    int32_t *cost_prefix;     // [rows + 1] in the workspace (written by workgroup 0, read by the merge)
     int n_wg;
 #ifdef SPECATTN_TIMING
     long long *timing;        // [n_wg][8] wall-clock stamps (development builds only)
@@ -128,8 +150,12 @@ struct Plan {
 
 __device__ __forceinline__ int clamp_count(int c, int cap) { return c < 0 ? 0 : (c > cap ? cap : c); }
 
-// Exclusive prefix of tiles per row into pre[0..rows], every workgroup for itself.
-__device__ __forceinline__ void tile_prefix(const AttnLaunch &a, int rows, int *pre, int *cnt, int *wsum)
+// Cost of a row on the line the workgroups share out: its tiles, plus SEG_COST for picking the row up
+// (fresh Q, pipeline refill, partial write) so that workgroups crossing a row boundary get fewer tiles.
+__device__ __forceinline__ int row_cost(int count) { return count > 0 ? (count + TILE - 1) / TILE + SEG_COST : 0; }
+
+// Exclusive prefix of the row costs into pre[0..rows], every workgroup for itself.
+__device__ __forceinline__ void cost_prefix(const AttnLaunch &a, int rows, int *pre, int *cnt, int *wsum)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int per = (rows + THREADS - 1) / THREADS;
@@ -140,7 +166,7 @@ __device__ __forceinline__ void tile_prefix(const AttnLaunch &a, int rows, int *
         if (r < rows) {
             const int c = clamp_count(a.counts[r], a.idx_capacity);
             cnt[r] = c;
-            local += (c + TILE - 1) / TILE;
+            local += row_cost(c);
         }
     }
     int inc = local;
@@ -158,23 +184,39 @@ __device__ __forceinline__ void tile_prefix(const AttnLaunch &a, int rows, int *
         const int r = r0 + k;
         if (r < rows) {
             pre[r] = run;
-            run += (cnt[r] + TILE - 1) / TILE;
+            run += row_cost(cnt[r]);
         }
     }
     if (tid == THREADS - 1) pre[rows] = base + inc;
     __syncthreads();
 }
 
+// One step of merging partial (m, l, o) triples that share the log2-unit convention.
+struct Merge {
+    float m = -INFINITY, l = 0.0f, o = 0.0f;
+    __device__ __forceinline__ void add(float mw, float lw, float ow)
+    {
+        const float mn = fmaxf(m, mw);
+        const float fa = (m == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(m - mn);
+        const float fb = (mw == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(mw - mn);
+        l = l * fa + lw * fb;
+        o = o * fa + ow * fb;
+        m = mn;
+    }
+};
+
 template <int NQT, int LAYOUT>
 __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan plan)
 {
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     constexpr int QTP = NQT * 16;
+    constexpr int EPT = CHUNK_TILES * TILE / THREADS;                   // list entries staged per thread
     const int rows = a.B * a.H_kv;
-    int *pre = reinterpret_cast<int *>(smem + NW * WAVE_LDS);          // [MAX_ROWS + 1]
+    int *pre = reinterpret_cast<int *>(smem + NW * WAVE_LDS);          // [MAX_ROWS + 1] cost prefix
     int *cnt_lds = pre + MAX_ROWS + 1;                                  // [MAX_ROWS] kept counts, clamped
-    int *wsum = cnt_lds + MAX_ROWS;                                     // [NW], then one flag
-    uint32_t *ent_lds = reinterpret_cast<uint32_t *>(wsum + NW + 1);    // [CHUNK_TILES * TILE] row offsets / 16 B
+    int *wsum = cnt_lds + MAX_ROWS;                                     // [NW]
+    int *tile_ctr = wsum + NW;                                          // tiles of the current chunk claimed so far
+    uint32_t *ent_lds = reinterpret_cast<uint32_t *>(tile_ctr + 1);       // [CHUNK_TILES * TILE] row offsets / 16 B
     float *ml_lds = reinterpret_cast<float *>(ent_lds);                 // wave merge: [NW][2][32], same space
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -183,6 +225,7 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
     const uint32_t ks_addr = (uint32_t)(uintptr_t)LDS_PTR(char, wave_lds);
     const uint32_t vs_addr = ks_addr + TILE_BYTES;
     const uint32_t ent_addr = (uint32_t)(uintptr_t)LDS_PTR(uint32_t, ent_lds);
+    const uint32_t ctr_addr = (uint32_t)(uintptr_t)LDS_PTR(int, tile_ctr);
     // K fragment of k-step c: row l16 (+16 per position tile), 16-byte chunk 4c + g
     uint32_t k_off[4];
 #pragma unroll
@@ -203,40 +246,52 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
     for (int j = 0; j < 4; ++j) lane_chunk[j] = (int64_t)((l16 ^ swz(4 * j + g)) << 4);
 
     STAMP(0);
-    tile_prefix(a, rows, pre, cnt_lds, wsum);
+    cost_prefix(a, rows, pre, cnt_lds, wsum);
     STAMP(1);
+    if (blockIdx.x == 0)
+        for (int rr = tid; rr <= rows; rr += THREADS) plan.cost_prefix[rr] = pre[rr];
+    // This workgroup's share of the cost line [c0, c1); tile k of row r sits at pre[r] + SEG_COST + k.
     const int total = pre[rows];
     const int share = (total + plan.n_wg - 1) / plan.n_wg;
-    int t0 = blockIdx.x * share;
-    const int t1 = (t0 + share) < total ? (t0 + share) : total;
-    if (t0 >= t1) return;
-
-    int r;                                          // row holding tile t0: pre[r] <= t0 < pre[r+1]
-    {
-        int lo = 0, hi = rows;
-        while (hi - lo > 1) {
-            const int mid = (lo + hi) >> 1;
-            if (pre[mid] <= t0) lo = mid; else hi = mid;
-        }
-        r = lo;
-    }
+    const int c0 = blockIdx.x * share;
+    const int c1 = (c0 + share) < total ? (c0 + share) : total;
+    if (c0 >= c1) return;
     const int G = a.H_q / a.H_kv;
     const int QT = G * a.T;
     const float scale2 = a.sm_scale * 1.4426950408889634f;            // scores in log2 units
 
-    while (t0 < t1) {
-        while (pre[r + 1] <= t0) ++r;
-        const int seg_end = pre[r + 1] < t1 ? pre[r + 1] : t1;
-        const int lt_begin = t0 - pre[r], lt_end = seg_end - pre[r];   // local tile range in row r
-        const int b = r / a.H_kv, h = r - b * a.H_kv;
-        const int count = cnt_lds[r];
-        const int32_t *idx = a.indices + (int64_t)r * a.idx_stride;
-        const KvMap map = make_map<LAYOUT>(a, b, h);
-        const char *kbh = static_cast<const char *>(a.k) + map.base * 2;
-        const char *vbh = static_cast<const char *>(a.v) + map.base * 2;
+    // local tile range of row r inside [c0, c1); empty when lt_begin >= lt_end
+    auto seg_range = [&](int r, int &lt_begin, int &lt_end) {
+        const int tiles = (cnt_lds[r] + TILE - 1) / TILE;
+        int lo = c0 - pre[r] - SEG_COST, hi = c1 - pre[r] - SEG_COST;
+        lt_begin = lo < 0 ? 0 : (lo > tiles ? tiles : lo);
+        lt_end = hi < 0 ? 0 : (hi > tiles ? tiles : hi);
+    };
+    // first row at or after r with work for this workgroup, or `rows`
+    auto next_seg = [&](int r) {
+        for (; r < rows && pre[r] < c1; ++r) {
+            int lb, le;
+            seg_range(r, lb, le);
+            if (lb < le) return r;
+        }
+        return rows;
+    };
+    int r;
+    {
+        int lo = 0, hi = rows;                      // row holding cost c0: pre[r] <= c0 < pre[r+1]
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (pre[mid] <= c0) lo = mid; else hi = mid;
+        }
+        r = next_seg(lo);
+    }
+    if (r >= rows) return;
 
-        // ---- Q fragments: lane (q = l16, g) holds Q[q][32c + 8g .. +8) for c = 0..3 -----------------
-        bf16x8 qf[NQT][4];
+    // ---- per-segment inputs that are fetched ahead of time -------------------------------------------
+    bf16x8 qf[NQT][4];                       // Q fragments: lane (q = l16, g) holds Q[q][32c + 8g .. +8)
+    uint32_t ent_pf[EPT];                    // this thread's entries of the segment's first chunk
+    auto fetch_q = [&](int rr) {
+        const int b = rr / a.H_kv, h = rr - b * a.H_kv;
 #pragma unroll
         for (int qt = 0; qt < NQT; ++qt) {
             const int qi = qt * 16 + l16;
@@ -249,6 +304,46 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
                 else qf[qt][c] = (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
             }
         }
+    };
+    // row offsets (16-byte units) of list entries [first, first + n) of row rr; entries past the end of
+    // the list repeat the last kept position (their scores are masked), so every gather stays in bounds
+    auto fetch_entries = [&](int rr, int first, int n, uint32_t (&out)[EPT]) {
+        const int b = rr / a.H_kv, h = rr - b * a.H_kv;
+        const KvMap map = make_map<LAYOUT>(a, b, h);
+        const int32_t *idx = a.indices + (int64_t)rr * a.idx_stride;
+        const int count = cnt_lds[rr];
+#pragma unroll
+        for (int k = 0; k < EPT; ++k) {
+            const int j = tid + k * THREADS;
+            int jj = first + j;
+            jj = jj < count ? jj : count - 1;
+            out[k] = j < n ? (uint32_t)(map.rel<LAYOUT>(idx[jj]) >> 3) : 0u;
+        }
+    };
+    auto store_entries = [&](int n, const uint32_t (&in)[EPT]) {
+#pragma unroll
+        for (int k = 0; k < EPT; ++k) {
+            const int j = tid + k * THREADS;
+            if (j < n) ent_lds[j] = in[k];
+        }
+    };
+    {
+        int lb, le;
+        seg_range(r, lb, le);
+        fetch_q(r);
+        const int n0 = ((le - lb) < CHUNK_TILES ? (le - lb) : CHUNK_TILES) * TILE;
+        fetch_entries(r, lb * TILE, n0, ent_pf);
+    }
+
+    while (r < rows) {
+        int lt_begin, lt_end;
+        seg_range(r, lt_begin, lt_end);
+        const int r_next = next_seg(r + 1);
+        const int b = r / a.H_kv, h = r - b * a.H_kv;
+        const int count = cnt_lds[r];
+        const KvMap map = make_map<LAYOUT>(a, b, h);
+        const char *kbh = static_cast<const char *>(a.k) + map.base * 2;
+        const char *vbh = static_cast<const char *>(a.v) + map.base * 2;
 
         f32x4 o[NQT][8];                     // O^T[dv = 16t + 4g + i][q = l16]
         float m_ref[NQT], l_sum[NQT];        // reference max (log2 units) and sum of weights
@@ -262,13 +357,7 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
 
         // row offsets (in 16-byte units) of the 8 rows this lane helps to fetch for one tile
         auto read_entries = [&](int tile_in_chunk, uint32_t (&ent)[8]) {
-            const uint32_t ia = ent_addr + (uint32_t)((tile_in_chunk * TILE + g) << 2);
-#pragma unroll
-            for (int i = 0; i < 8; ++i) ent[i] = lds_read_b32(ia + (uint32_t)(i << 4));
-            asm volatile("s_waitcnt lgkmcnt(0)"
-                         : "+v"(ent[0]), "+v"(ent[1]), "+v"(ent[2]), "+v"(ent[3]), "+v"(ent[4]), "+v"(ent[5]),
-                           "+v"(ent[6]), "+v"(ent[7])
-                         :: "memory");
+            lds_read_entries(ent, ent_addr + (uint32_t)((tile_in_chunk * TILE + g) << 2));
         };
         // gather 32 rows of one tensor into this wave's buffer: 8 instructions of 4 rows x 256 B
         auto issue = [&](const char *base, char *buf, const uint32_t (&ent)[8]) {
@@ -281,14 +370,11 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
 
         for (int ch_begin = lt_begin; ch_begin < lt_end; ch_begin += CHUNK_TILES) {
             const int ch_end = (ch_begin + CHUNK_TILES) < lt_end ? (ch_begin + CHUNK_TILES) : lt_end;
-            // ---- stage this chunk's row offsets in LDS; entries past the end of the list repeat the
-            //      last kept position (their scores are masked) so that every gather stays in bounds --
-            __syncthreads();
-            for (int j = tid; j < (ch_end - ch_begin) * TILE; j += THREADS) {
-                int jj = ch_begin * TILE + j;
-                jj = jj < count ? jj : count - 1;
-                ent_lds[j] = (uint32_t)(map.rel<LAYOUT>(idx[jj]) >> 3);
-            }
+            // ---- stage this chunk's row offsets in LDS (the first chunk's were fetched ahead) ----------
+            if (ch_begin != lt_begin) fetch_entries(r, ch_begin * TILE, (ch_end - ch_begin) * TILE, ent_pf);
+            __syncthreads();                                           // previous users of ent_lds are done
+            store_entries((ch_end - ch_begin) * TILE, ent_pf);
+            if (tid == 0) *tile_ctr = 0;
             __syncthreads();
             // Touch the Q fragments here, so that the compiler's wait for their loads sits outside the
             // tile loop (inside it, it would also wait for the gathers of the next tile).
@@ -300,31 +386,29 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
 
             // The gathers are not tracked by the compiler's wait insertion; every wait on them is
             // written out.  Per wave the order of issue is K(t), V(t), K(t+1), V(t+1), ...
+            // Tiles of the chunk are claimed by the waves as they go (a wave that gets its data later
+            // simply takes fewer), one claim ahead of the tile whose gathers are being issued.
             uint32_t ent[8];
-            int lt = ch_begin + wave;
-            if (lt < ch_end) {
-                read_entries(lt - ch_begin, ent);
+            const int n_ch = ch_end - ch_begin;
+            int cur = lds_claim(ctr_addr, lane);
+            if (cur < n_ch) {
+                read_entries(cur, ent);
                 issue(kbh, wave_lds, ent);
                 issue(vbh, wave_lds + TILE_BYTES, ent);
             }
-            for (; lt < ch_end; lt += NW) {
-                const bool has_next = lt + NW < ch_end;
+            int nxt = lds_claim(ctr_addr, lane);
+            while (cur < n_ch) {
+                const int lt = ch_begin + cur;
+                const bool has_next = nxt < n_ch;
                 asm volatile("s_waitcnt vmcnt(8)" ::: "memory");        // K(t) landed; V(t) may be in flight
 
                 // ---- S^T[pos][q] = K Q^T -----------------------------------------------------------
                 f32x4 s[NQT][2];
                 {
-                    u32x4 kf[2][4];
-#pragma unroll
-                    for (int pt = 0; pt < 2; ++pt)
-#pragma unroll
-                        for (int c = 0; c < 4; ++c) kf[pt][c] = lds_read_b128(k_off[c] + (uint32_t)(pt * 16 * ROW_BYTES));
-                    asm volatile("s_waitcnt lgkmcnt(0)"
-                                 : "+v"(kf[0][0]), "+v"(kf[0][1]), "+v"(kf[0][2]), "+v"(kf[0][3]),
-                                   "+v"(kf[1][0]), "+v"(kf[1][1]), "+v"(kf[1][2]), "+v"(kf[1][3])
-                                 :: "memory");
+                    KFrags kf;
+                    lds_read_k(kf, k_off);
                     if (has_next) {                                    // the K buffer is free again
-                        read_entries(lt + NW - ch_begin, ent);
+                        read_entries(nxt, ent);
                         issue(kbh, wave_lds, ent);
                     }
 #pragma unroll
@@ -334,7 +418,7 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
                             f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                             for (int c = 0; c < 4; ++c)
-                                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[pt][c]),
+                                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf.f[pt][c]),
                                                                               qf[qt][c], acc, 0, 0, 0);
                             s[qt][pt] = acc;
                         }
@@ -386,20 +470,12 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
                 else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #pragma unroll
                 for (int tb = 0; tb < 8; tb += 4) {                    // four 16-wide dv tiles per batch
-                    u32x2 vh[4][2];
-#pragma unroll
-                    for (int t = 0; t < 4; ++t)
-#pragma unroll
-                        for (int hh = 0; hh < 2; ++hh)
-                            vh[t][hh] = lds_read_tr_b64(v_off[tb + t] + (uint32_t)(hh * 16 * ROW_BYTES));
-                    asm volatile("s_waitcnt lgkmcnt(0)"
-                                 : "+v"(vh[0][0]), "+v"(vh[0][1]), "+v"(vh[1][0]), "+v"(vh[1][1]),
-                                   "+v"(vh[2][0]), "+v"(vh[2][1]), "+v"(vh[3][0]), "+v"(vh[3][1])
-                                 :: "memory");
+                    VFrags vh;
+                    lds_read_v(vh, v_off[tb], v_off[tb + 1], v_off[tb + 2], v_off[tb + 3]);
                     if (tb == 4 && has_next) issue(vbh, wave_lds + TILE_BYTES, ent);   // the V buffer is free again
 #pragma unroll
                     for (int t = 0; t < 4; ++t) {
-                        const u32x4 both = (u32x4){vh[t][0][0], vh[t][0][1], vh[t][1][0], vh[t][1][1]};
+                        const u32x4 both = (u32x4){vh.f[t][0][0], vh.f[t][0][1], vh.f[t][1][0], vh.f[t][1][1]};
                         const bf16x8 vf = __builtin_bit_cast(bf16x8, both);
 #pragma unroll
                         for (int qt = 0; qt < NQT; ++qt) {
@@ -408,12 +484,24 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
                         }
                     }
                 }
+                cur = nxt;
+                if (has_next) nxt = lds_claim(ctr_addr, lane);
             }
         }   // chunks
-
-        // ---- combine the waves of this workgroup, write the partial of (row r, this workgroup) -----
         STAMP(3);
+
+        // ---- request what the next segment needs, to arrive while this one is wrapped up --------------
+        if (r_next < rows) {
+            int lb, le;
+            seg_range(r_next, lb, le);
+            fetch_q(r_next);
+            const int n0 = ((le - lb) < CHUNK_TILES ? (le - lb) : CHUNK_TILES) * TILE;
+            fetch_entries(r_next, lb * TILE, n0, ent_pf);
+        }
+
+        // ---- combine the waves of this workgroup -------------------------------------------------------
         __syncthreads();                         // every wave is done with its buffers and with ent_lds
+        STAMP(4);
         float *dump = reinterpret_cast<float *>(wave_lds);     // [QTP][D], 4-float blocks XOR-swizzled by q
 #pragma unroll
         for (int qt = 0; qt < NQT; ++qt) {
@@ -427,9 +515,10 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
             if (g == 0) { ml_lds[wave * 64 + q] = m_ref[qt]; ml_lds[wave * 64 + 32 + q] = l; }
         }
         __syncthreads();
+        STAMP(5);
         // Workgroups w0..w1 share row r.  A row owned by one workgroup is finished here; otherwise the
-        // partial goes to slot w + r and the workgroup that delivers the last partial merges them all.
-        const int w0 = pre[r] / share, w1 = (pre[r + 1] - 1) / share;
+        // partial goes to slot w + r for the merge kernel.
+        const int w0 = (pre[r] + SEG_COST) / share, w1 = (pre[r + 1] - 1) / share;
         const int slot = blockIdx.x + r;
         float *po = plan.part_o + (int64_t)slot * QTP * D;
         float *pml = plan.part_ml + (int64_t)slot * QTP * 2;
@@ -453,60 +542,55 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
                 a.out[orow * D + dv] = l > 0.0f ? acc / l : 0.0f;
                 if (a.lse && dv == 0) a.lse[orow] = l > 0.0f ? (m + log2f(l)) * 0.6931471805599453f : -INFINITY;
             } else {
-                st_agent(po + e, acc);
-                if (dv == 0) { st_agent(pml + 2 * q, m); st_agent(pml + 2 * q + 1, l); }
+                po[e] = acc;
+                if (dv == 0) { pml[2 * q] = m; pml[2 * q + 1] = l; }
             }
         }
-        if (w0 != w1) {
-            // Partials are written and read with device-coherent accesses, so no cache write-back or
-            // invalidation is needed: once this workgroup's stores have completed, it counts itself in.
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            __syncthreads();
-            if (tid == 0)
-                wsum[NW] = __hip_atomic_fetch_add(&plan.arrivals[r], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == w1 - w0;
-            __syncthreads();
-            if (wsum[NW]) {                      // uniform: this workgroup delivered the last partial
-                for (int e = tid; e < QT * D; e += THREADS) {
-                    const int q = e >> 7, dv = e & (D - 1);
-                    float m = -INFINITY;
-                    for (int w = w0; w <= w1; ++w) m = fmaxf(m, ld_agent(plan.part_ml + ((int64_t)(w + r) * QTP + q) * 2));
-                    float acc = 0.0f, l = 0.0f;
-                    for (int w = w0; w <= w1; ++w) {
-                        const float *pm = plan.part_ml + ((int64_t)(w + r) * QTP + q) * 2;
-                        const float mw = ld_agent(pm);
-                        const float f = (mw == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(mw - m);
-                        acc += f * ld_agent(plan.part_o + ((int64_t)(w + r) * QTP + q) * D + dv);
-                        l += f * ld_agent(pm + 1);
-                    }
-                    const int gh = q / a.T, tt = q - gh * a.T;
-                    const int64_t orow = ((int64_t)b * a.H_q + (h * G + gh)) * a.T + tt;
-                    a.out[orow * D + dv] = l > 0.0f ? acc / l : 0.0f;
-                    if (a.lse && dv == 0) a.lse[orow] = l > 0.0f ? (m + log2f(l)) * 0.6931471805599453f : -INFINITY;
-                }
-            }
-        }
-        t0 = seg_end;                            // the next segment starts with a barrier of its own
-        STAMP(4);
+        STAMP(6);
+        r = r_next;                              // the next segment starts with a barrier of its own
     }
+    STAMP(7);
 }
 
-// Before the main kernel: clear the arrival counters and give rows without any kept position their
-// result (out = 0, lse = -inf), since no workgroup visits them.
-__global__ void attn_prep_kernel(AttnLaunch a, Plan plan)
+// After the main kernel, one workgroup per (row, query row): rows shared by several workgroups get
+// their partials (r, w) combined; rows without any kept position get out = 0, lse = -inf.
+__global__ void merge_partials_kernel(AttnLaunch a, Plan plan, int qtp)
 {
-    const int r = blockIdx.x;
     const int G = a.H_q / a.H_kv;
     const int QT = G * a.T;
-    if (threadIdx.x == 0) plan.arrivals[r] = 0;
-    if (clamp_count(a.counts[r], a.idx_capacity) > 0) return;
+    const int rows = a.B * a.H_kv;
+    const int r = blockIdx.x / QT, q = blockIdx.x - r * QT;
     const int b = r / a.H_kv, h = r - b * a.H_kv;
-    for (int e = threadIdx.x; e < QT * D; e += blockDim.x) {
-        const int q = e >> 7, dv = e & (D - 1);
-        const int gh = q / a.T, tt = q - gh * a.T;
-        const int64_t orow = ((int64_t)b * a.H_q + (h * G + gh)) * a.T + tt;
+    const int gh = q / a.T, t = q - gh * a.T;
+    const int64_t orow = ((int64_t)b * a.H_q + (h * G + gh)) * a.T + t;
+    const int dv = threadIdx.x;
+    const int total = plan.cost_prefix[rows];
+    const int p0 = plan.cost_prefix[r], p1 = plan.cost_prefix[r + 1];
+    if (p0 == p1) {
         a.out[orow * D + dv] = 0.0f;
         if (a.lse && dv == 0) a.lse[orow] = -INFINITY;
+        return;
     }
+    const int share = (total + plan.n_wg - 1) / plan.n_wg;
+    const int w0 = (p0 + SEG_COST) / share, w1 = (p1 - 1) / share;
+    if (w0 == w1) return;                       // finished by its only workgroup
+    Merge acc;
+    for (int wb = w0; wb <= w1; wb += 8) {      // eight partials per round trip
+        float mw[8], lw[8], ow[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int64_t s = (int64_t)(wb + k + r) * qtp + q;
+            const bool ok = wb + k <= w1;
+            mw[k] = ok ? plan.part_ml[s * 2] : -INFINITY;
+            lw[k] = ok ? plan.part_ml[s * 2 + 1] : 0.0f;
+            ow[k] = ok ? plan.part_o[s * D + dv] : 0.0f;
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k) acc.add(mw[k], lw[k], ow[k]);
+    }
+    a.out[orow * D + dv] = acc.l > 0.0f ? acc.o / acc.l : 0.0f;
+    // m is in log2 units of the scaled scores
+    if (a.lse && dv == 0) a.lse[orow] = acc.l > 0.0f ? (acc.m + log2f(acc.l)) * 0.6931471805599453f : -INFINITY;
 }
 
 }  // namespace
@@ -523,7 +607,7 @@ size_t attn_mfma_workspace_bytes(int rows, int G, int T)
 {
     const size_t qtp = (G * T <= 16) ? 16 : 32;
     const size_t slots = (size_t)attn_mfma_workgroups() + rows;
-    size_t bytes = ((size_t)rows * sizeof(int32_t) + 255) & ~(size_t)255;              // arrival counters
+    size_t bytes = (((size_t)rows + 1) * sizeof(int32_t) + 255) & ~(size_t)255;        // cost prefix
     bytes += slots * qtp * (D + 2) * sizeof(float);
     return (bytes + 255) & ~(size_t)255;
 }
@@ -538,8 +622,8 @@ specattn_status launch_attn_mfma(const AttnLaunch &a, hipStream_t stream)
     plan.n_wg = attn_mfma_workgroups();
     const size_t slots = (size_t)plan.n_wg + rows;
     char *ws = static_cast<char *>(a.workspace);
-    plan.arrivals = reinterpret_cast<int32_t *>(ws);
-    ws += ((size_t)rows * sizeof(int32_t) + 255) & ~(size_t)255;
+    plan.cost_prefix = reinterpret_cast<int32_t *>(ws);
+    ws += (((size_t)rows + 1) * sizeof(int32_t) + 255) & ~(size_t)255;
     plan.part_ml = reinterpret_cast<float *>(ws);
     plan.part_o = plan.part_ml + slots * qtp * 2;
     const size_t lds = (size_t)NW * WAVE_LDS + (2 * MAX_ROWS + 1 + NW + 1 + CHUNK_TILES * TILE) * sizeof(int);
@@ -562,16 +646,16 @@ specattn_status launch_attn_mfma(const AttnLaunch &a, hipStream_t stream)
     extern long long *g_specattn_timing;
     plan.timing = g_specattn_timing;
 #endif
-    hipLaunchKernelGGL(attn_prep_kernel, dim3(rows), dim3(128), 0, stream, a, plan);
-    specattn_status st = check_launch("attn_prep_kernel");
-    if (st != SPECATTN_OK) return st;
     void *kargs[] = {const_cast<AttnLaunch *>(&a), &plan};
     if (hipLaunchKernel(fn, dim3(plan.n_wg), dim3(THREADS), kargs, lds, stream) != hipSuccess) {
         set_error("attn_mfma_kernel: launch failed");
         (void)hipGetLastError();
         return SPECATTN_EHIP;
     }
-    return check_launch("attn_mfma_kernel");
+    specattn_status st = check_launch("attn_mfma_kernel");
+    if (st != SPECATTN_OK) return st;
+    hipLaunchKernelGGL(merge_partials_kernel, dim3(rows * QT), dim3(D), 0, stream, a, plan, qtp);
+    return check_launch("merge_partials_kernel");
 }
 
 }  // namespace specattn
