@@ -98,14 +98,20 @@ def main():
         for a in attn:
             sa.specattn_sparse_decode_attn(a)
 
-    # fused: one threshold launch for all layers, then per layer the attention re-derives its lists
+    # fused: the index list never goes through HBM.  One threshold launch for the rows of all layers
+    # writes tau*, counts and per-block counts; each layer's attention rebuilds its lists on chip.
     fused_ok = True
-    sel_layer, attn_f, ws_f = [], [], None
+    nblk = (n + sa.SEL_BLOCK - 1) // sa.SEL_BLOCK
     counts_f = torch.zeros((L * R,), dtype=torch.int32, device="cuda")
+    tau_f = torch.empty((L * R,), dtype=torch.float32, device="cuda")
+    bc_f = torch.empty((L * R, nblk), dtype=torch.int32, device="cuda")
     outs_f = [torch.empty((B, H_q, T, d), dtype=torch.float32, device="cuda") for _ in range(L)]
+    sel_all_f = sa.select_args(probs, top_p, indices=None, counts=counts_f, thresholds=tau_f, block_counts=bc_f)
+    sel_layer, attn_f, ws_f = [], [], None
     for layer in range(L):
-        s = sa.select_args(probs[layer * B:(layer + 1) * B], top_p, indices=None,
-                           counts=counts_f[layer * R:(layer + 1) * R])
+        rows = slice(layer * R, (layer + 1) * R)
+        s = sa.select_args(probs[layer * B:(layer + 1) * B], top_p, indices=None, counts=counts_f[rows],
+                           thresholds=tau_f[rows], block_counts=bc_f[rows], reuse_selection=True)
         a = sa.attn_args(qs[layer], ks[layer], vs[layer], out=outs_f[layer])
         if ws_f is None:
             ws_f = sa.alloc_workspace(sa.specattn_workspace_size(s, a))
@@ -114,6 +120,7 @@ def main():
         attn_f.append(a)
 
     def step_fused():
+        sa.specattn_topp_select(sel_all_f)
         for s, a in zip(sel_layer, attn_f):
             sa.specattn_fused(s, a)
 

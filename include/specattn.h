@@ -46,7 +46,8 @@ typedef enum specattn_dtype { SPECATTN_F32 = 0, SPECATTN_BF16 = 1 } specattn_dty
 #define SPECATTN_ROW_OVERFLOW 4u       /* count > idx_capacity: list truncated to the first idx_capacity */
 
 /* limits */
-#define SPECATTN_MAX_N (1 << 20)       /* longest row the selection handles */
+#define SPECATTN_MAX_N (1 << 19)       /* longest row the selection handles */
+#define SPECATTN_SEL_BLOCK 1024        /* positions per entry of block_counts */
 #define SPECATTN_MAX_T 8               /* most verifier queries (gamma + 1) per head */
 
 /*
@@ -65,8 +66,8 @@ typedef struct specattn_select_args {
     const int32_t *seq_lens;     /* [B] valid length per sequence, or NULL for n_max everywhere */
     float top_p;                 /* p in (0, 1] */
 
-    int32_t *indices;            /* out [B*H_kv][idx_stride_row]: ascending positions; may be NULL
-                                    only in specattn_fused */
+    int32_t *indices;            /* out [B*H_kv][idx_stride_row]: ascending positions; NULL = no list is
+                                    written (then block_counts must be given, or the call is specattn_fused) */
     int64_t idx_stride_row;      /* elements between rows, >= idx_capacity */
     int32_t idx_capacity;        /* most entries written per row */
     int32_t *counts;             /* out [B*H_kv]: TRUE number kept, even when > idx_capacity */
@@ -79,6 +80,12 @@ typedef struct specattn_select_args {
     int32_t max_pages_per_seq;
     int32_t emit_physical;       /* 1: indices[j] = page_table[b][pos/page_size]*page_size + pos%page_size
                                        (still in ascending pos order); needs page_table */
+
+    /* selection state without an index list (what specattn_fused works from) */
+    int32_t *block_counts;       /* out, optional: [B*H_kv][ceil(n_max / SPECATTN_SEL_BLOCK)] kept positions per block */
+    int32_t reuse_selection;     /* specattn_fused only: 1 = thresholds, counts and block_counts already hold the
+                                    result of an earlier specattn_topp_select / specattn_fused call on these rows
+                                    (e.g. one batched call for all layers); the threshold phase is skipped */
 } specattn_select_args;
 
 /*
@@ -127,10 +134,13 @@ specattn_status specattn_sparse_decode_attn(const specattn_attn_args *attn, void
 
 /*
  * Selection + attention without the index list going through HBM: the first
- * phase writes only tau*, counts and per-block counts; the attention
+ * phase writes only tau*, counts and per-block counts (into sel->thresholds /
+ * sel->block_counts when given, else into the workspace); the attention
  * workgroups re-derive their share of the list from `probs` on chip.
- * sel->indices may be NULL; attn->indices / attn->counts are ignored
+ * sel->indices is ignored; attn->indices / attn->counts are ignored
  * (sel->counts is written and used).  attn->workspace serves both phases.
+ * Supported for bf16, d = 128, G*T <= 32, contiguous or page-table layouts
+ * (SPECATTN_EUNSUPPORTED otherwise).
  */
 specattn_status specattn_fused(const specattn_select_args *sel, const specattn_attn_args *attn,
                                void *stream);

@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libspecattn.so")
 
 OK, EINVAL, ESHAPE, EALIGN, EWORKSPACE, EUNSUPPORTED, EHIP = 0, -1, -2, -3, -4, -5, -6
 ROW_INVALID, ROW_NEAR_BOUNDARY, ROW_OVERFLOW = 1, 2, 4
+SEL_BLOCK = 1024
 F32, BF16 = 0, 1
 
 EXPORTS = ("specattn_topp_select", "specattn_sparse_decode_attn", "specattn_fused",
@@ -32,6 +33,7 @@ class SelectArgs(C.Structure):
         ("counts", C.c_void_p), ("thresholds", C.c_void_p), ("row_flags", C.c_void_p),
         ("page_table", C.c_void_p), ("page_size", C.c_int32), ("max_pages_per_seq", C.c_int32),
         ("emit_physical", C.c_int32),
+        ("block_counts", C.c_void_p), ("reuse_selection", C.c_int32),
     ]
 
 
@@ -111,7 +113,8 @@ def select_args(probs: torch.Tensor, top_p: float, *, indices: Optional[torch.Te
                 counts: torch.Tensor, thresholds: Optional[torch.Tensor] = None,
                 row_flags: Optional[torch.Tensor] = None, seq_lens: Optional[torch.Tensor] = None,
                 page_table: Optional[torch.Tensor] = None, page_size: int = 0,
-                emit_physical: bool = False) -> SelectArgs:
+                emit_physical: bool = False, block_counts: Optional[torch.Tensor] = None,
+                reuse_selection: bool = False) -> SelectArgs:
     """probs [B,H_kv,n] fp32 (last dim contiguous); indices [B*H_kv, cap] int32."""
     assert probs.dtype == torch.float32 and probs.dim() == 3 and probs.stride(2) == 1
     B, H, n = probs.shape
@@ -133,6 +136,10 @@ def select_args(probs: torch.Tensor, top_p: float, *, indices: Optional[torch.Te
         a.page_table = page_table.data_ptr()
         a.page_size, a.max_pages_per_seq = page_size, page_table.shape[1]
     a.emit_physical = int(emit_physical)
+    if block_counts is not None:
+        assert block_counts.dtype == torch.int32 and block_counts.is_contiguous()
+        a.block_counts = block_counts.data_ptr()
+    a.reuse_selection = int(reuse_selection)
     return a
 
 

@@ -52,12 +52,12 @@ specattn_status check_select(const specattn_select_args *s, bool fused)
 {
     if (!s) { set_error("select args are NULL"); return SPECATTN_EINVAL; }
     if (!s->probs || !s->counts) { set_error("probs and counts must not be NULL"); return SPECATTN_EINVAL; }
-    if (!fused && !s->indices) { set_error("indices must not be NULL"); return SPECATTN_EINVAL; }
+    if (!fused && !s->indices && !s->block_counts) { set_error("indices and block_counts must not both be NULL"); return SPECATTN_EINVAL; }
     if (s->B <= 0 || s->H_kv <= 0 || s->n_max <= 0) { set_error("B, H_kv and n_max must be positive"); return SPECATTN_EINVAL; }
     if (!(s->top_p > 0.0f && s->top_p <= 1.0f)) { set_error("top_p must lie in (0, 1]"); return SPECATTN_EINVAL; }
     if (s->n_max > SPECATTN_MAX_N) { set_error("n_max %d exceeds %d", s->n_max, SPECATTN_MAX_N); return SPECATTN_ESHAPE; }
     if ((int64_t)s->B * s->H_kv > (1 << 24)) { set_error("too many rows"); return SPECATTN_ESHAPE; }
-    if (s->indices) {
+    if (s->indices && !fused) {
         if (s->idx_capacity < 1) { set_error("idx_capacity must be at least 1"); return SPECATTN_ESHAPE; }
         if (s->idx_stride_row < s->idx_capacity) { set_error("idx_stride_row is smaller than idx_capacity"); return SPECATTN_ESHAPE; }
     }
@@ -127,8 +127,8 @@ SelectLaunch make_select(const specattn_select_args *s)
     l.page_shift = s->emit_physical ? log2i(s->page_size) : 0;
     l.max_pages = s->max_pages_per_seq;
     l.emit_physical = s->emit_physical;
-    l.block_counts = nullptr;
-    l.blocks_per_row = 0;
+    l.block_counts = s->block_counts;
+    l.blocks_per_row = (s->n_max + SEL_BLOCK - 1) / SEL_BLOCK;
     return l;
 }
 
@@ -194,9 +194,52 @@ specattn_status specattn_fused(const specattn_select_args *sel, const specattn_a
     if (st != SPECATTN_OK) return st;
     st = check_attn(attn, true);
     if (st != SPECATTN_OK) return st;
-    (void)stream;
-    set_error("the fused path is not built yet");
-    return SPECATTN_EUNSUPPORTED;
+    if (sel->B != attn->B || sel->H_kv != attn->H_kv || sel->n_max != attn->n_max) {
+        set_error("selection and attention arguments describe different rows");
+        return SPECATTN_ESHAPE;
+    }
+    if (sel->reuse_selection && (!sel->thresholds || !sel->block_counts)) {
+        set_error("reuse_selection needs thresholds and block_counts");
+        return SPECATTN_EINVAL;
+    }
+    AttnLaunch al = make_attn(attn);
+    if (!attn_mfma_supported(al) || attn->indices_are_physical) {
+        set_error("the fused path is built for bf16, d = 128, G*T <= 32, logical positions");
+        return SPECATTN_EUNSUPPORTED;
+    }
+    st = check_workspace(attn->workspace, attn->workspace_bytes, specattn_workspace_size(sel, attn));
+    if (st != SPECATTN_OK) return st;
+    const int rows = sel->B * sel->H_kv;
+    const int blocks = (sel->n_max + SEL_BLOCK - 1) / SEL_BLOCK;
+    // workspace: [attention partials][tau: rows floats][block counts: rows * blocks ints]
+    char *extra = static_cast<char *>(attn->workspace) +
+                  attn_workspace_bytes(rows, attn->H_q / attn->H_kv, attn->T, attn->d, attn->n_max);
+    float *tau = sel->thresholds ? sel->thresholds : reinterpret_cast<float *>(extra);
+    extra += ((size_t)rows * sizeof(float) + 255) & ~(size_t)255;
+    int32_t *bc = sel->block_counts ? sel->block_counts : reinterpret_cast<int32_t *>(extra);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (!sel->reuse_selection) {
+        SelectLaunch sl = make_select(sel);
+        sl.indices = nullptr;
+        sl.idx_capacity = 0;
+        sl.thresholds = tau;
+        sl.block_counts = bc;
+        sl.blocks_per_row = blocks;
+        st = launch_select(sl, s);
+        if (st != SPECATTN_OK) return st;
+    }
+    al.indices = nullptr;
+    al.counts = sel->counts;
+    al.idx_capacity = sel->n_max;
+    al.idx_stride = 0;
+    al.probs = sel->probs;
+    al.probs_stride_b = sel->probs_stride_b;
+    al.probs_stride_h = sel->probs_stride_h;
+    al.seq_lens = sel->seq_lens;
+    al.tau = tau;
+    al.block_counts = bc;
+    al.blocks_per_row = blocks;
+    return launch_attn_mfma(al, s);
 }
 
 size_t specattn_workspace_size(const specattn_select_args *sel, const specattn_attn_args *attn)
@@ -208,7 +251,13 @@ size_t specattn_workspace_size(const specattn_select_args *sel, const specattn_a
     const int rows = attn->B * attn->H_kv;
     const int cap = sel ? attn->n_max : attn->idx_capacity;
     if (cap <= 0) return 0;
-    return attn_workspace_bytes(rows, attn->H_q / attn->H_kv, attn->T, attn->d, cap);
+    size_t bytes = attn_workspace_bytes(rows, attn->H_q / attn->H_kv, attn->T, attn->d, cap);
+    if (sel) {                                        // fused: room for tau and the block counts
+        const size_t blocks = ((size_t)attn->n_max + SEL_BLOCK - 1) / SEL_BLOCK;
+        bytes += ((size_t)rows * sizeof(float) + 255) & ~(size_t)255;
+        bytes += ((size_t)rows * blocks * sizeof(int32_t) + 255) & ~(size_t)255;
+    }
+    return bytes;
 }
 
 const char *specattn_last_error(void) { return g_error; }

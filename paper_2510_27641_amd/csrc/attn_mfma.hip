@@ -41,6 +41,7 @@ constexpr int TILE_BYTES = TILE * ROW_BYTES;          // 8 KiB per tensor
 constexpr int WAVE_LDS = 2 * TILE_BYTES;              // K buffer, V buffer
 constexpr int MAX_ROWS = 2048;        // rows whose tile prefix fits the LDS table
 constexpr int CHUNK_TILES = 64;       // tiles whose row offsets are staged in LDS at a time
+constexpr int MAX_BLOCKS = SPECATTN_MAX_N / SEL_BLOCK;   // selection blocks per row, at most
 constexpr int SEG_COST = 10;          // cost of starting a row segment, in tiles
 constexpr float RESCALE_SLACK = 8.0f; // log2 units the running max may exceed the reference by
 
@@ -205,7 +206,7 @@ struct Merge {
     }
 };
 
-template <int NQT, int LAYOUT>
+template <int NQT, int LAYOUT, bool FUSED>
 __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan plan)
 {
     extern __shared__ __attribute__((aligned(1024))) char smem[];
@@ -218,6 +219,8 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
     int *tile_ctr = wsum + NW;                                          // tiles of the current chunk claimed so far
     uint32_t *ent_lds = reinterpret_cast<uint32_t *>(tile_ctr + 1);       // [CHUNK_TILES * TILE] row offsets / 16 B
     float *ml_lds = reinterpret_cast<float *>(ent_lds);                 // wave merge: [NW][2][32], same space
+    int *blk_pre = reinterpret_cast<int *>(ent_lds + CHUNK_TILES * TILE);   // fused: [MAX_BLOCKS + 1] kept before block
+    int *scan_ws = blk_pre + MAX_BLOCKS + 1;                            // fused: [2][NW + 1] scan scratch
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l16 = lane & 15, g = lane >> 4;
@@ -327,12 +330,107 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
             if (j < n) ent_lds[j] = in[k];
         }
     };
+    // ---- fused path: the list is never read from memory; it is rebuilt from the draft row ----------
+    // blk_pre[b] = number of kept positions of row rr before block b (blocks of SEL_BLOCK positions)
+    auto fused_prepare_row = [&](int rr) {
+        __syncthreads();
+        const int32_t *bc = a.block_counts + (int64_t)rr * a.blocks_per_row;
+        if (wave == 0) {
+            int running = 0;
+            for (int base = 0; base < a.blocks_per_row; base += 64) {
+                const int c = (base + lane < a.blocks_per_row) ? bc[base + lane] : 0;
+                int inc = c;
+#pragma unroll
+                for (int off = 1; off < 64; off <<= 1) {
+                    const int o = __shfl_up(inc, off, 64);
+                    if (lane >= off) inc += o;
+                }
+                if (base + lane < a.blocks_per_row) blk_pre[base + lane + 1] = running + inc;
+                running += __shfl(inc, 63, 64);
+            }
+            if (lane == 0) blk_pre[0] = 0;
+        }
+        __syncthreads();
+    };
+    // ent_lds[0 .. n) <- row offsets of the kept positions of rank first .. first + n - 1 of row rr:
+    // scan the draft probabilities against tau* from the block that holds rank `first`, 8 positions
+    // per thread and pass, and number the kept ones by a workgroup-wide prefix sum.
+    auto fused_stage = [&](int rr, int first, int n) {
+        const int b = rr / a.H_kv, h = rr - b * a.H_kv;
+        const KvMap map = make_map<LAYOUT>(a, b, h);
+        const float *row = a.probs + (int64_t)b * a.probs_stride_b + (int64_t)h * a.probs_stride_h;
+        const bool aligned = (reinterpret_cast<uintptr_t>(row) & 15) == 0;
+        int len = a.seq_lens ? a.seq_lens[b] : a.n_max;
+        len = len < 0 ? 0 : (len > a.n_max ? a.n_max : len);
+        const uint32_t tau_bits = __float_as_uint(a.tau[rr]);
+        const int count = cnt_lds[rr];
+        const int last = (first + n) < count ? (first + n) : count;      // ranks [first, last) exist
+        int b0;
+        {
+            int lo = 0, hi = a.blocks_per_row;                           // blk_pre[b0] <= first < blk_pre[b0 + 1]
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if (blk_pre[mid] <= first) lo = mid; else hi = mid;
+            }
+            b0 = lo;
+        }
+        int pos = b0 * SEL_BLOCK, rank_base = blk_pre[b0], pass = 0;
+        while (rank_base < last) {                                       // uniform
+            const int p0 = pos + tid * 8;
+            uint32_t u[8];
+            if (aligned && p0 + 7 < len) {
+                const uint4 x = *reinterpret_cast<const uint4 *>(row + p0);
+                const uint4 y = *reinterpret_cast<const uint4 *>(row + p0 + 4);
+                u[0] = x.x; u[1] = x.y; u[2] = x.z; u[3] = x.w; u[4] = y.x; u[5] = y.y; u[6] = y.z; u[7] = y.w;
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) u[i] = (p0 + i < len) ? __float_as_uint(row[p0 + i]) : 0u;
+            }
+            int c = 0;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                if (u[i] == 0x80000000u) u[i] = 0u;                      // -0.0 is zero, as in the selection
+                c += u[i] >= tau_bits ? 1 : 0;
+            }
+            int inc = c;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const int o = __shfl_up(inc, off, 64);
+                if (lane >= off) inc += o;
+            }
+            int *ws = scan_ws + (pass & 1) * (NW + 1);
+            if (lane == 63) ws[wave] = inc;
+            __syncthreads();
+            int before = 0, all = 0;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) {
+                const int t = ws[w];
+                if (w < wave) before += t;
+                all += t;
+            }
+            int rk = rank_base + before + inc - c;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                if (u[i] >= tau_bits) {
+                    if (rk >= first && rk < last) ent_lds[rk - first] = (uint32_t)(map.rel<LAYOUT>(p0 + i) >> 3);
+                    ++rk;
+                }
+            }
+            rank_base += all;
+            pos += THREADS * 8;
+            ++pass;
+        }
+        __syncthreads();
+        // ranks past the end of the list repeat the last kept position (their scores are masked)
+        for (int j = last - first + tid; j < n; j += THREADS) ent_lds[j] = ent_lds[last - first - 1];
+    };
+
     {
         int lb, le;
         seg_range(r, lb, le);
         fetch_q(r);
         const int n0 = ((le - lb) < CHUNK_TILES ? (le - lb) : CHUNK_TILES) * TILE;
-        fetch_entries(r, lb * TILE, n0, ent_pf);
+        if (!FUSED) fetch_entries(r, lb * TILE, n0, ent_pf);
     }
 
     while (r < rows) {
@@ -371,9 +469,14 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
         for (int ch_begin = lt_begin; ch_begin < lt_end; ch_begin += CHUNK_TILES) {
             const int ch_end = (ch_begin + CHUNK_TILES) < lt_end ? (ch_begin + CHUNK_TILES) : lt_end;
             // ---- stage this chunk's row offsets in LDS (the first chunk's were fetched ahead) ----------
-            if (ch_begin != lt_begin) fetch_entries(r, ch_begin * TILE, (ch_end - ch_begin) * TILE, ent_pf);
-            __syncthreads();                                           // previous users of ent_lds are done
-            store_entries((ch_end - ch_begin) * TILE, ent_pf);
+            if (FUSED) {
+                if (ch_begin == lt_begin) fused_prepare_row(r); else __syncthreads();
+                fused_stage(r, ch_begin * TILE, (ch_end - ch_begin) * TILE);
+            } else {
+                if (ch_begin != lt_begin) fetch_entries(r, ch_begin * TILE, (ch_end - ch_begin) * TILE, ent_pf);
+                __syncthreads();                                       // previous users of ent_lds are done
+                store_entries((ch_end - ch_begin) * TILE, ent_pf);
+            }
             if (tid == 0) *tile_ctr = 0;
             __syncthreads();
             // Touch the Q fragments here, so that the compiler's wait for their loads sits outside the
@@ -496,7 +599,7 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
             seg_range(r_next, lb, le);
             fetch_q(r_next);
             const int n0 = ((le - lb) < CHUNK_TILES ? (le - lb) : CHUNK_TILES) * TILE;
-            fetch_entries(r_next, lb * TILE, n0, ent_pf);
+            if (!FUSED) fetch_entries(r_next, lb * TILE, n0, ent_pf);
         }
 
         // ---- combine the waves of this workgroup -------------------------------------------------------
@@ -626,13 +729,23 @@ specattn_status launch_attn_mfma(const AttnLaunch &a, hipStream_t stream)
     ws += (((size_t)rows + 1) * sizeof(int32_t) + 255) & ~(size_t)255;
     plan.part_ml = reinterpret_cast<float *>(ws);
     plan.part_o = plan.part_ml + slots * qtp * 2;
-    const size_t lds = (size_t)NW * WAVE_LDS + (2 * MAX_ROWS + 1 + NW + 1 + CHUNK_TILES * TILE) * sizeof(int);
+    const size_t lds = (size_t)NW * WAVE_LDS +
+                       (2 * MAX_ROWS + 1 + NW + 1 + CHUNK_TILES * TILE + MAX_BLOCKS + 1 + 2 * (NW + 1)) * sizeof(int);
     const int layout = a.indices_are_physical ? PHYSICAL : (a.page_table ? PAGE_TABLE : CONTIGUOUS);
     const void *fn = nullptr;
-#define PICK(NQT, LAY) if (qtp == 16 * NQT && layout == LAY) fn = reinterpret_cast<const void *>(&attn_mfma_kernel<NQT, LAY>);
-    PICK(1, CONTIGUOUS) PICK(1, PAGE_TABLE) PICK(1, PHYSICAL) PICK(2, CONTIGUOUS) PICK(2, PAGE_TABLE) PICK(2, PHYSICAL)
+    const bool fused = a.probs != nullptr;
+#define PICK(NQT, LAY)                                                                                           \
+    if (qtp == 16 * NQT && layout == LAY)                                                                        \
+        fn = fused ? reinterpret_cast<const void *>(&attn_mfma_kernel<NQT, LAY, true>)                           \
+                   : reinterpret_cast<const void *>(&attn_mfma_kernel<NQT, LAY, false>);
+    PICK(1, CONTIGUOUS) PICK(1, PAGE_TABLE) PICK(2, CONTIGUOUS) PICK(2, PAGE_TABLE)
+    if (!fused) {
+        if (qtp == 16 && layout == PHYSICAL) fn = reinterpret_cast<const void *>(&attn_mfma_kernel<1, PHYSICAL, false>);
+        if (qtp == 32 && layout == PHYSICAL) fn = reinterpret_cast<const void *>(&attn_mfma_kernel<2, PHYSICAL, false>);
+    }
+    if (!fn) { set_error("the fused path takes logical positions, not pool slots"); return SPECATTN_EUNSUPPORTED; }
 #undef PICK
-    static const void *configured[8] = {nullptr};
+    static const void *configured[16] = {nullptr};
     bool seen = false;
     for (const void *c : configured) seen = seen || c == fn;
     if (!seen) {

@@ -1,0 +1,122 @@
+"""GPU parity of specattn_fused (selection + attention without an index list in HBM) against
+oracle selection followed by oracle masked attention."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2510_27641_amd import binding as sa
+from paper_2510_27641_amd import workloads as W
+from helpers import TOL, dev, kv_tensors, oracle_attention, row_rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+def _fused(w, *, reuse=False, give_state=False, want_lse=True):
+    """Run specattn_fused on workload w; returns (out, lse, counts, tau)."""
+    q, k, v = kv_tensors(w)
+    probs = dev(w.probs)
+    R = w.B * w.H_kv
+    counts = torch.full((R,), -7, dtype=torch.int32, device="cuda")
+    sl = None if w.seq_lens is None else dev(w.seq_lens.astype(np.int32))
+    pt = None if w.page_table is None else dev(w.page_table)
+    nblk = (w.n + sa.SEL_BLOCK - 1) // sa.SEL_BLOCK
+    tau = torch.zeros((R,), dtype=torch.float32, device="cuda") if (give_state or reuse) else None
+    bc = torch.full((R, nblk), -1, dtype=torch.int32, device="cuda") if (give_state or reuse) else None
+    out = torch.full((w.B, w.H_q, w.T, w.d), float("nan"), dtype=torch.float32, device="cuda")
+    lse = torch.full((w.B, w.H_q, w.T), float("nan"), dtype=torch.float32, device="cuda") if want_lse else None
+    if reuse:      # the threshold phase as a separate (batchable) call that writes no index list
+        s0 = sa.select_args(probs, w.top_p, indices=None, counts=counts, thresholds=tau, seq_lens=sl,
+                            block_counts=bc)
+        sa.specattn_topp_select(s0)
+    sel = sa.select_args(probs, w.top_p, indices=None, counts=counts, thresholds=tau, seq_lens=sl,
+                         block_counts=bc, reuse_selection=reuse)
+    kw = dict(page_table=pt, page_size=W.PAGE_SIZE, n_max=w.n) if pt is not None else dict(n_max=w.n)
+    att = sa.attn_args(q, k, v, out=out, lse=lse, seq_lens=sl, **kw)
+    ws = sa.alloc_workspace(sa.specattn_workspace_size(sel, att))
+    att.workspace, att.workspace_bytes = ws.data_ptr(), ws.numel()
+    sa.specattn_fused(sel, att)
+    torch.cuda.synchronize()
+    return (out.cpu().numpy(), None if lse is None else lse.cpu().numpy(), counts.cpu().numpy(),
+            None if tau is None else tau.cpu().numpy())
+
+
+def _reference(w, which=None):
+    ref = oracle.topp_select(w.probs.reshape(-1, w.n), w.top_p, w.row_lens())
+    mask = ref.mask().reshape(w.B, w.H_kv, w.n)
+    o, lse = oracle_attention(w, mask, which=which)
+    return ref, o, lse
+
+
+def _check_counts(counts, ref):
+    clear = (ref.flags & oracle.ROW_NEAR_BOUNDARY) == 0
+    assert np.array_equal(counts[clear], ref.counts[clear])
+
+
+@pytest.mark.parametrize("mode", ["one_call", "state_given", "reuse"])
+def test_llama_layer_8k(mode):
+    w = W.llama8b_layer(seed=1)
+    out, lse, counts, tau = _fused(w, reuse=(mode == "reuse"), give_state=(mode == "state_given"))
+    ref, o, l = _reference(w)
+    _check_counts(counts, ref)
+    assert row_rel_err(out, o) <= TOL["bf16"]
+    assert np.abs(lse - l).max() <= 2e-3
+    if tau is not None:
+        clear = (ref.flags & oracle.ROW_NEAR_BOUNDARY) == 0
+        assert np.array_equal(tau[clear], ref.tau[clear])
+
+
+def test_batch_of_32k_rows_sampled():
+    w = W.llama8b_layer(seed=3, B=2, n=32768, top_p=0.9)
+    out, _, counts, _ = _fused(w)
+    rng = np.random.default_rng(1)
+    which = [(int(rng.integers(w.B)), int(rng.integers(w.H_q)), int(rng.integers(w.T))) for _ in range(48)]
+    ref, o, _ = _reference(w, which=which)
+    _check_counts(counts, ref)
+    got = np.stack([out[b, h, t] for b, h, t in which])
+    assert row_rel_err(got, o) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("n", [33, 1000, 1024, 1025, 5000, 70001])
+def test_row_lengths(n):
+    w = W.llama8b_layer(seed=20 + n % 7, B=2, n=n, H_q=8, H_kv=2, top_p=0.9)
+    out, _, counts, _ = _fused(w)
+    ref, o, _ = _reference(w)
+    _check_counts(counts, ref)
+    assert row_rel_err(out, o) <= TOL["bf16"]
+
+
+def test_paged_ragged_batch_through_page_table():
+    w = W.ragged_paged(seed=4, B=6, len_lo=50, len_hi=7000)
+    out, lse, counts, _ = _fused(w)
+    ref, o, l = _reference(w)
+    _check_counts(counts, ref)
+    assert row_rel_err(out, o) <= TOL["bf16"]
+
+
+def test_invalid_and_empty_rows_give_zero_output():
+    w = W.llama8b_layer(seed=5, n=3000, H_q=8, H_kv=4)
+    w.probs[0, 1, 17] = np.nan
+    w.probs[0, 2, :] = 0.0
+    out, lse, counts, _ = _fused(w)
+    ref, o, l = _reference(w)
+    assert counts[1] == 0 and counts[2] == 0
+    G = w.G
+    assert (out[0, 1 * G:(2 + 1) * G] == 0).all()
+    assert np.isneginf(lse[0, 1 * G:(2 + 1) * G]).all()
+    assert row_rel_err(out, o) <= TOL["bf16"]
+
+
+def test_top_p_one_selects_everything():
+    w = W.llama8b_layer(seed=6, n=2100, top_p=1.0, H_q=8, H_kv=2)
+    out, _, counts, _ = _fused(w)
+    ref, o, _ = _reference(w)
+    assert (counts == 2100).all()
+    assert row_rel_err(out, o) <= TOL["bf16"]
+
+
+def test_unsupported_shapes_fail_loudly():
+    w = W.tiny_f32()
+    with pytest.raises(sa.SpecAttnError) as e:
+        _fused(w)
+    assert e.value.status == sa.EUNSUPPORTED
