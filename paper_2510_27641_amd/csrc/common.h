@@ -41,6 +41,9 @@ struct SelectLaunch {
     int emit_physical;
     int32_t *block_counts;   // may be null; [rows][blocks_per_row]
     int blocks_per_row;
+#ifdef SPECATTN_TIMING
+    long long *timing;
+#endif
 };
 specattn_status launch_select(const SelectLaunch &a, hipStream_t stream);
 

@@ -16,6 +16,12 @@
 #include "common.h"
 
 namespace specattn {
+#ifdef SPECATTN_TIMING
+long long *g_select_timing = nullptr;   // [rows][8] wall-clock stamps (development builds only)
+#define SSTAMP(k) do { if (threadIdx.x == 0 && a.timing) a.timing[blockIdx.x * 8 + (k)] = wall_clock64(); } while (0)
+#else
+#define SSTAMP(k) do { } while (0)
+#endif
 namespace {
 
 constexpr int NB1 = 2048;                     // bins of pass 1
@@ -29,6 +35,8 @@ struct RowShared {
     double wave_m[16];
     unsigned wave_c[16];
     unsigned wave_tot[2][16];
+    unsigned wt[256];            // kept entries per (item, wave), then their exclusive prefix
+    int32_t wbuf[16][256];       // per wave: one item's kept entries, staged for contiguous stores
     double total_m;
     double m_above;
     unsigned c_above;
@@ -44,104 +52,118 @@ __device__ __forceinline__ unsigned long long packed_entry(uint32_t u)
     return CNT_ONE | sig;
 }
 
-// value of a significand sum whose entries all carry biased exponent field e: sum * 2^(max(e,1)-150)
+// value of a significand sum whose entries all carry biased exponent field e: sum * 2^(max(e,1)-150),
+// exact (the sum is below 2^44 and the scale is a power of two well inside the fp64 range)
 __device__ __forceinline__ double mass_of(unsigned long long packed, int e_field)
 {
-    const double s = (double)(long long)(packed & SIG_MASK);     // < 2^44: exact
-    return ldexp(s, (e_field > 0 ? e_field : 1) - 150);
-}
-
-// Suffix sums over threads (thread t gets the sum over threads > t) of a double and a count.
-template <int THREADS>
-__device__ __forceinline__ void suffix_scan(double lm, unsigned lc, RowShared &sh, double &excl_m,
-                                            unsigned &excl_c, double &total_m)
-{
-    constexpr int NW = THREADS / 64;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    double im = lm;
-    unsigned ic = lc;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const double om = __shfl_down(im, off, 64);
-        const unsigned oc = __shfl_down(ic, off, 64);
-        if (lane + off < 64) { im += om; ic += oc; }
-    }
-    if (lane == 0) { sh.wave_m[wave] = im; sh.wave_c[wave] = ic; }
-    const double nm = __shfl_down(im, 1, 64);          // inclusive sum of the lanes above
-    const unsigned nc = __shfl_down(ic, 1, 64);
-    __syncthreads();
-    double hm = 0.0;
-    unsigned hc = 0;
-    for (int w = NW - 1; w > wave; --w) { hm += sh.wave_m[w]; hc += sh.wave_c[w]; }
-    excl_m = (lane < 63 ? nm : 0.0) + hm;
-    excl_c = (lane < 63 ? nc : 0u) + hc;
-    double tot = 0.0;
-    for (int w = NW - 1; w >= 0; --w) tot += sh.wave_m[w];
-    total_m = tot;
-    __syncthreads();
+    const double s = (double)(long long)(packed & SIG_MASK);
+    const int e = (e_field > 0 ? e_field : 1) - 150;
+    return s * __hiloint2double((1023 + e) << 20, 0);
 }
 
 // One radix pass decision.  hist[0..NB) holds the packed counters of this pass.
 // On return (uniform over the block): bin = highest non-empty bin b with
 // m_above + mass(bins >= b) >= target (lowest non-empty bin if rounding leaves none),
 // and m_above / c_above advanced to cover the bins above it.
+// Two levels: every wave sums its own bins; all threads walk the few wave totals from the top to
+// find the wave that holds the boundary; only that wave looks at single bins.
 template <int THREADS, int NB, bool FIRST>
 __device__ __forceinline__ int locate_bin(RowShared &sh, int e_field_fixed, float top_p, double &target,
                                           double &m_above, unsigned &c_above,
                                           unsigned long long &bin_packed)
 {
+    constexpr int NW = THREADS / 64;
     constexpr int BPT = NB / THREADS;
     static_assert(BPT >= 1, "more threads than bins");
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int b0 = threadIdx.x * BPT;
     double lm = 0.0;
     unsigned lc = 0;
     double mass[BPT];
+    unsigned cnt[BPT];
 #pragma unroll
     for (int j = 0; j < BPT; ++j) {
         const unsigned long long h = sh.hist[b0 + j];
         const int e = FIRST ? ((b0 + j) >> 3) : e_field_fixed;
         mass[j] = mass_of(h, e);
+        cnt[j] = (unsigned)(h >> CNT_SHIFT);
         lm += mass[j];
-        lc += (unsigned)(h >> CNT_SHIFT);
+        lc += cnt[j];
     }
-    double excl_m, total;
-    unsigned excl_c;
-    if (threadIdx.x == 0) { sh.best = -1; sh.lowest = NB; }
-    suffix_scan<THREADS>(lm, lc, sh, excl_m, excl_c, total);
+    double wm = lm;
+    unsigned wc = lc;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {          // butterfly: every lane ends with the wave total
+        wm += __shfl_xor(wm, off, 64);
+        wc += __shfl_xor(wc, off, 64);
+    }
+    if (lane == 0) { sh.wave_m[wave] = wm; sh.wave_c[wave] = wc; }
+    __syncthreads();
+    double total = 0.0;
+#pragma unroll
+    for (int w = NW - 1; w >= 0; --w) total += sh.wave_m[w];
     if (FIRST) target = (double)top_p * total;     // Algorithm 2: M_target = p * sum a
     if (FIRST && !(total > 0.0)) return -1;        // no mass at all (uniform decision)
 
-    int mine = -1, low = NB;
-    double run = excl_m;
+    int wb = -1, wlow = -1;                        // wave holding the boundary; lowest non-empty wave
+    double run_w = 0.0, above_w = 0.0;
+    unsigned runc_w = 0, abovec_w = 0;
 #pragma unroll
-    for (int j = BPT - 1; j >= 0; --j) {
-        const bool nonempty = (sh.hist[b0 + j] >> CNT_SHIFT) != 0;
-        if (nonempty) {
-            low = b0 + j;
-            if (mine < 0 && (m_above + (run + mass[j])) >= target) mine = b0 + j;
+    for (int w = NW - 1; w >= 0; --w) {
+        const double m = sh.wave_m[w];
+        const unsigned c = sh.wave_c[w];
+        if (c) {
+            wlow = w;
+            if (wb < 0 && (m_above + (run_w + m)) >= target) { wb = w; above_w = run_w; abovec_w = runc_w; }
         }
-        run += mass[j];
+        if (wb < 0) { run_w += m; runc_w += c; }
     }
-    if (mine >= 0) atomicMax(&sh.best, mine);
-    if (low < NB) atomicMin(&sh.lowest, low);
-    __syncthreads();
-    const int bin = sh.best >= 0 ? sh.best : sh.lowest;
-    if (bin >= b0 && bin < b0 + BPT) {
-        double r = excl_m;
-        unsigned c = excl_c;
+    if (wb < 0) {                                  // rounding left no wave: take the lowest bins
+        wb = wlow;
+        above_w = run_w - sh.wave_m[wlow];
+        abovec_w = runc_w - sh.wave_c[wlow];
+    }
+    if (wave == wb) {
+        double im = lm;                            // suffix sums over the lanes of this wave
+        unsigned ic = lc;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const double om = __shfl_down(im, off, 64);
+            const unsigned oc = __shfl_down(ic, off, 64);
+            if (lane + off < 64) { im += om; ic += oc; }
+        }
+        const double nm = __shfl_down(im, 1, 64);
+        const unsigned nc = __shfl_down(ic, 1, 64);
+        const double excl_m = above_w + (lane < 63 ? nm : 0.0);
+        const unsigned excl_c = abovec_w + (lane < 63 ? nc : 0u);
+        int mine = -1, low = -1;
+        double run = excl_m, mine_above = 0.0, low_above = 0.0;
+        unsigned runc = excl_c, mine_c = 0, low_c = 0;
 #pragma unroll
         for (int j = BPT - 1; j >= 0; --j) {
-            if (b0 + j > bin) { r += mass[j]; c += (unsigned)(sh.hist[b0 + j] >> CNT_SHIFT); }
+            if (cnt[j]) {
+                low = b0 + j; low_above = run; low_c = runc;
+                if (mine < 0 && (m_above + (run + mass[j])) >= target) { mine = b0 + j; mine_above = run; mine_c = runc; }
+            }
+            run += mass[j];
+            runc += cnt[j];
         }
-        sh.m_above = m_above + r;
-        sh.c_above = c_above + c;
-        sh.bin_packed = sh.hist[bin];
+        const unsigned long long has_mine = __ballot(mine >= 0), has_low = __ballot(low >= 0);
+        // the boundary is in the highest lane that found one; else the lowest non-empty bin of the wave
+        const int owner = has_mine ? 63 - __clzll(has_mine) : __ffsll((unsigned long long)has_low) - 1;
+        if (lane == owner) {
+            const int bin = has_mine ? mine : low;
+            sh.best = bin;
+            sh.m_above = m_above + (has_mine ? mine_above : low_above);
+            sh.c_above = c_above + (has_mine ? mine_c : low_c);
+            sh.bin_packed = sh.hist[bin];
+        }
     }
     __syncthreads();
     m_above = sh.m_above;
     c_above = sh.c_above;
     bin_packed = sh.bin_packed;
-    return bin;
+    return sh.best;
 }
 
 template <int THREADS, int NB>
@@ -153,7 +175,7 @@ __device__ __forceinline__ void clear_hist(RowShared &sh)
 
 // THREADS threads per row; RESIDENT: the row sits in NV4 uint4 registers per thread.
 template <int THREADS, int NV4, bool RESIDENT>
-__global__ __launch_bounds__(THREADS) void topp_select_kernel(SelectLaunch a)
+__global__ __launch_bounds__(THREADS, 4) void topp_select_kernel(SelectLaunch a)
 {
     __shared__ RowShared sh;
     constexpr int NW = THREADS / 64;
@@ -167,6 +189,7 @@ __global__ __launch_bounds__(THREADS) void topp_select_kernel(SelectLaunch a)
     const bool aligned = (reinterpret_cast<uintptr_t>(row) & 15) == 0;
     const int n_items = (len + ITEM - 1) / ITEM;
 
+    SSTAMP(0);
     bool bad = false;
     auto load_item = [&](int i) -> uint4 {
         const int p = (i * THREADS + tid) * 4;
@@ -204,6 +227,7 @@ __global__ __launch_bounds__(THREADS) void topp_select_kernel(SelectLaunch a)
         }
     };
 
+    SSTAMP(1);
     // ---- pass 1: bits[30:20] -----------------------------------------------------------------
     clear_hist<THREADS, NB1>(sh);
     for_items([&](int, uint4 u) {
@@ -214,6 +238,7 @@ __global__ __launch_bounds__(THREADS) void topp_select_kernel(SelectLaunch a)
     });
     const bool any_bad = __syncthreads_or(bad ? 1 : 0) != 0;     // also orders the atomics
 
+    SSTAMP(2);
     double target = 0.0, m_above = 0.0;
     unsigned c_above = 0;
     unsigned long long bin_packed = 0;
@@ -231,29 +256,44 @@ __global__ __launch_bounds__(THREADS) void topp_select_kernel(SelectLaunch a)
     }
     const int e_field = b1 >> 3;
 
-    // ---- pass 2: bits[19:10] inside bin b1 ---------------------------------------------------
-    clear_hist<THREADS, NB2>(sh);
-    for_items([&](int, uint4 u) {
-        if ((u.x >> 20) == (uint32_t)b1 && u.x) atomicAdd(&sh.hist[(u.x >> 10) & 1023u], packed_entry(u.x));
-        if ((u.y >> 20) == (uint32_t)b1 && u.y) atomicAdd(&sh.hist[(u.y >> 10) & 1023u], packed_entry(u.y));
-        if ((u.z >> 20) == (uint32_t)b1 && u.z) atomicAdd(&sh.hist[(u.z >> 10) & 1023u], packed_entry(u.z));
-        if ((u.w >> 20) == (uint32_t)b1 && u.w) atomicAdd(&sh.hist[(u.w >> 10) & 1023u], packed_entry(u.w));
-    });
-    __syncthreads();
-    const int b2 = locate_bin<THREADS, NB2, false>(sh, e_field, a.top_p, target, m_above, c_above, bin_packed);
-
-    // ---- pass 3: bits[9:0] inside (b1, b2) ---------------------------------------------------
-    const uint32_t prefix = ((uint32_t)b1 << 10) | (uint32_t)b2;
-    clear_hist<THREADS, NB2>(sh);
-    for_items([&](int, uint4 u) {
-        if ((u.x >> 10) == prefix && u.x) atomicAdd(&sh.hist[u.x & 1023u], packed_entry(u.x));
-        if ((u.y >> 10) == prefix && u.y) atomicAdd(&sh.hist[u.y & 1023u], packed_entry(u.y));
-        if ((u.z >> 10) == prefix && u.z) atomicAdd(&sh.hist[u.z & 1023u], packed_entry(u.z));
-        if ((u.w >> 10) == prefix && u.w) atomicAdd(&sh.hist[u.w & 1023u], packed_entry(u.w));
-    });
-    __syncthreads();
-    const int b3 = locate_bin<THREADS, NB2, false>(sh, e_field, a.top_p, target, m_above, c_above, bin_packed);
-    const uint32_t tau_bits = (prefix << 10) | (uint32_t)b3;     // >= 1: zeros never enter a bin
+    SSTAMP(3);
+    // A boundary bin that holds a single entry pins tau*: the bin's significand sum is that entry's
+    // significand, and the exponent is the bin's.  Otherwise refine inside the bin.
+    auto single_entry_bits = [&](unsigned long long packed) -> uint32_t {
+        return ((uint32_t)e_field << 23) | ((uint32_t)packed & 0x7fffffu);
+    };
+    uint32_t tau_bits;
+    if ((bin_packed >> CNT_SHIFT) == 1) {
+        tau_bits = single_entry_bits(bin_packed);
+    } else {
+        // ---- pass 2: bits[19:10] inside bin b1 -----------------------------------------------
+        clear_hist<THREADS, NB2>(sh);
+        for_items([&](int, uint4 u) {
+            if ((u.x >> 20) == (uint32_t)b1 && u.x) atomicAdd(&sh.hist[(u.x >> 10) & 1023u], packed_entry(u.x));
+            if ((u.y >> 20) == (uint32_t)b1 && u.y) atomicAdd(&sh.hist[(u.y >> 10) & 1023u], packed_entry(u.y));
+            if ((u.z >> 20) == (uint32_t)b1 && u.z) atomicAdd(&sh.hist[(u.z >> 10) & 1023u], packed_entry(u.z));
+            if ((u.w >> 20) == (uint32_t)b1 && u.w) atomicAdd(&sh.hist[(u.w >> 10) & 1023u], packed_entry(u.w));
+        });
+        __syncthreads();
+        const int b2 = locate_bin<THREADS, NB2, false>(sh, e_field, a.top_p, target, m_above, c_above, bin_packed);
+        const uint32_t prefix = ((uint32_t)b1 << 10) | (uint32_t)b2;
+        if ((bin_packed >> CNT_SHIFT) == 1) {
+            tau_bits = single_entry_bits(bin_packed);
+        } else {
+            // ---- pass 3: bits[9:0] inside (b1, b2) -------------------------------------------
+            clear_hist<THREADS, NB2>(sh);
+            for_items([&](int, uint4 u) {
+                if ((u.x >> 10) == prefix && u.x) atomicAdd(&sh.hist[u.x & 1023u], packed_entry(u.x));
+                if ((u.y >> 10) == prefix && u.y) atomicAdd(&sh.hist[u.y & 1023u], packed_entry(u.y));
+                if ((u.z >> 10) == prefix && u.z) atomicAdd(&sh.hist[u.z & 1023u], packed_entry(u.z));
+                if ((u.w >> 10) == prefix && u.w) atomicAdd(&sh.hist[u.w & 1023u], packed_entry(u.w));
+            });
+            __syncthreads();
+            const int b3 = locate_bin<THREADS, NB2, false>(sh, e_field, a.top_p, target, m_above, c_above, bin_packed);
+            tau_bits = (prefix << 10) | (uint32_t)b3;             // >= 1: zeros never enter a bin
+        }
+    }
+    SSTAMP(4);
     const unsigned kept = c_above + (unsigned)(bin_packed >> CNT_SHIFT);
 
     if (tid == 0) {
@@ -322,10 +362,80 @@ __global__ __launch_bounds__(THREADS) void topp_select_kernel(SelectLaunch a)
         if (tid == 0) sh.running = base + all;                 // wave 0: base == running
         ++it;
     };
-    for_items(compact_item);
+    SSTAMP(5);
+    if (RESIDENT) {
+        // All items at once: every wave counts its kept entries per item, one workgroup-wide
+        // exclusive prefix over the (item, wave) counts gives every wave its place in the list.
+        constexpr int NE = NV4 * NW;
+        static_assert(NE <= 256 && NE <= THREADS, "prefix table too small");
+        unsigned before[NV4];
+        unsigned char fl[NV4];
+#pragma unroll
+        for (int i = 0; i < NV4; ++i) {
+            const uint4 u = data[i];
+            const bool f0 = u.x >= tau_bits, f1 = u.y >= tau_bits, f2 = u.z >= tau_bits, f3 = u.w >= tau_bits;
+            const unsigned long long m0 = __ballot(f0), m1 = __ballot(f1), m2 = __ballot(f2), m3 = __ballot(f3);
+            before[i] = __popcll(m0 & lt_mask) + __popcll(m1 & lt_mask) + __popcll(m2 & lt_mask) + __popcll(m3 & lt_mask);
+            fl[i] = (unsigned char)((f0 ? 1 : 0) | (f1 ? 2 : 0) | (f2 ? 4 : 0) | (f3 ? 8 : 0));
+            if (lane == 0) sh.wt[i * NW + wave] = __popcll(m0) + __popcll(m1) + __popcll(m2) + __popcll(m3);
+        }
+        __syncthreads();
+        if (a.block_counts) {
+            constexpr int BPI = ITEM / SEL_BLOCK;              // selection blocks per item
+            constexpr int WPB = NW / BPI;                      // waves per block
+            for (int blk = tid; blk < NV4 * BPI && blk < a.blocks_per_row; blk += THREADS) {
+                unsigned c = 0;
+                for (int w = 0; w < WPB; ++w) c += sh.wt[(blk / BPI) * NW + (blk % BPI) * WPB + w];
+                a.block_counts[(int64_t)r * a.blocks_per_row + blk] = (int32_t)c;
+            }
+        }
+        unsigned v = tid < NE ? sh.wt[tid] : 0u, inc = v;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const unsigned o = __shfl_up(inc, off, 64);
+            if (lane >= off) inc += o;
+        }
+        if (lane == 63) sh.wave_c[wave] = inc;
+        __syncthreads();
+        if (tid < NE) {
+            unsigned base = 0;
+            for (int w = 0; w < wave; ++w) base += sh.wave_c[w];
+            sh.wt[tid] = base + inc - v;
+        }
+        __syncthreads();
+        if (out) {
+            // Per item the wave's kept entries are consecutive in the list: gather them in LDS in
+            // list order, then store them with whole-wave contiguous writes.
+            int32_t *wb = sh.wbuf[wave];
+#pragma unroll
+            for (int i = 0; i < NV4; ++i) {
+                if (i < n_items) {
+                    unsigned o = before[i];
+                    const int p = (i * THREADS + tid) * 4;
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        if (fl[i] & (1 << c)) {
+                            const int pos = p + c;
+                            int32_t val = pos;
+                            if (ptab) val = (ptab[pos >> a.page_shift] << a.page_shift) | (pos & ((1 << a.page_shift) - 1));
+                            wb[o++] = val;
+                        }
+                    }
+                    const unsigned base = sh.wt[i * NW + wave];
+                    const unsigned next = (i * NW + wave + 1 < NE) ? sh.wt[i * NW + wave + 1] : kept;
+                    const unsigned cnt_w = next - base;            // wave-uniform, at most 256
+                    for (unsigned k = lane; k < cnt_w; k += 64)
+                        if (base + k < (unsigned)a.idx_capacity) out[base + k] = wb[k];
+                }
+            }
+        }
+    } else {
+        for_items(compact_item);
+    }
+    SSTAMP(6);
     if (a.block_counts) {                                      // blocks past the row's end
         constexpr int BPI = ITEM / SEL_BLOCK;
-        for (int k = n_items * BPI + tid; k < a.blocks_per_row; k += THREADS)
+        for (int k = (RESIDENT ? NV4 : n_items) * BPI + tid; k < a.blocks_per_row; k += THREADS)
             a.block_counts[(int64_t)r * a.blocks_per_row + k] = 0;
     }
 }
@@ -334,6 +444,12 @@ template <int THREADS, int NV4, bool RESIDENT>
 specattn_status launch_one(const SelectLaunch &a, hipStream_t stream)
 {
     const int rows = a.B * a.H_kv;
+#ifdef SPECATTN_TIMING
+    SelectLaunch b = a;
+    b.timing = g_select_timing;
+    hipLaunchKernelGGL((topp_select_kernel<THREADS, NV4, RESIDENT>), dim3(rows), dim3(THREADS), 0, stream, b);
+    return check_launch("topp_select_kernel");
+#endif
     hipLaunchKernelGGL((topp_select_kernel<THREADS, NV4, RESIDENT>), dim3(rows), dim3(THREADS), 0, stream, a);
     return check_launch("topp_select_kernel");
 }
@@ -343,13 +459,16 @@ specattn_status launch_one(const SelectLaunch &a, hipStream_t stream)
 specattn_status launch_select(const SelectLaunch &a, hipStream_t stream)
 {
     const int n = a.n_max;
+    // Many rows: small workgroups, several per CU, so that one row's load overlaps another row's
+    // passes.  Few rows: as many threads per row as its length allows, for latency.
+    const bool many = a.B * a.H_kv >= 2 * cu_count();
     // block counts are per 1024 positions, so every variant has THREADS*4 a multiple of 1024
     if (n <= 1024) return launch_one<256, 1, true>(a, stream);
     if (n <= 2048) return launch_one<256, 2, true>(a, stream);
     if (n <= 4096) return launch_one<256, 4, true>(a, stream);
-    if (n <= 8192) return launch_one<512, 4, true>(a, stream);
-    if (n <= 16384) return launch_one<1024, 4, true>(a, stream);
-    if (n <= 32768) return launch_one<1024, 8, true>(a, stream);
+    if (n <= 8192) return many ? launch_one<256, 8, true>(a, stream) : launch_one<512, 4, true>(a, stream);
+    if (n <= 16384) return many ? launch_one<256, 16, true>(a, stream) : launch_one<1024, 4, true>(a, stream);
+    if (n <= 32768) return many ? launch_one<512, 16, true>(a, stream) : launch_one<1024, 8, true>(a, stream);
     if (n <= 65536) return launch_one<1024, 16, true>(a, stream);
     return launch_one<1024, 1, false>(a, stream);
 }
