@@ -39,6 +39,8 @@ def parse():
     ap.add_argument("--top-p", type=float, default=0.9)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--path", choices=["both", "unfused", "fused"], default="both")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 1 GiB device copy (reference for rocprofv3 --pmc byte counters)")
     return ap.parse_args()
 
 
@@ -136,6 +138,12 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / steps          # ms per step
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     results = {}
     if args.path in ("both", "unfused"):
         results["unfused"] = timed(step_unfused, args.steps, args.warmup)
@@ -170,6 +178,12 @@ def main():
     best_name = [k for k in ("fused", "unfused") if results.get(k) == best][0]
     value = sel_bytes_step / (best * 1e-3) / 1e9
 
+    traffic = None                       # HBM bytes per launch from rocprofv3 --pmc, if a summary is committed
+    pmc = os.path.join(ROOT, "profiles", "sparse_decode_attn_config3_pmc.txt")
+    if os.path.exists(pmc):
+        for ln in open(pmc):
+            if ln.startswith("traffic_bytes_per_launch:"):
+                traffic = float(ln.split(":")[1])
     line = {
         "metric": "selected_kv_GBps_topp_select_plus_sparse_decode_attn_32k",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -185,9 +199,10 @@ def main():
         "paths": {k: {"ms_per_step": round(v, 4), "GBps": round(sel_bytes_step / (v * 1e-3) / 1e9, 1)}
                   for k, v in results.items() if k in ("unfused", "fused")},
         "kernels": {"select_all_layers_ms": round(ms_sel, 4), "attention_per_layer_ms": round(ms_attn, 5)},
-        "roofline": {"bound": "hbm", "kernel": "sparse_decode_attn (per layer launch sequence)",
+        "roofline": {"bound": "hbm", "kernel": "specattn_sparse_decode_attn = attn_mfma_kernel + merge_partials_kernel, one layer",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None},
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                     "algorithmic_bytes_per_launch": int(bytes_launch), "launch_us": round(ms_attn * 1e3, 2)},
         "input_generation_s": round(t_gen, 1),
     }
     if not fused_ok:
@@ -197,28 +212,33 @@ def main():
     if not args.no_cpu_baseline:
         import oracle
         cores = oracle.set_threads(0)
-        rows_s = probs_host[:B].reshape(R, n)                       # layer 0
-        t0 = time.time()
-        ref = oracle.topp_select(rows_s, top_p)
-        t_sel = time.time() - t0
-        mask = ref.mask().reshape(B, H_kv, n)[:1]                   # sequence 0 of layer 0
-        q0 = qs[0][:1].view(torch.int16).cpu().numpy().view(np.uint16)
-        k0 = ks[0][:1].view(torch.int16).cpu().numpy().view(np.uint16)
-        v0 = vs[0][:1].view(torch.int16).cpu().numpy().view(np.uint16)
-        t0 = time.time()
-        o_ref, _ = oracle.masked_attention(q0, k0, v0, mask, bf16=True)
-        t_att = time.time() - t0
-        samp_bytes = float(ref.counts[:H_kv].sum()) * 2 * d * 2
-        t_total = t_sel * (H_kv / R) + t_att                        # selection share of the sampled sequence
+        n_samp = min(2, L)                                          # whole layers 0 .. n_samp-1
+        t_sel = t_att = 0.0
+        samp_bytes = 0.0
+        worst = 0.0
+        for layer in range(n_samp):
+            rows_s = probs_host[layer * B:(layer + 1) * B].reshape(R, n)
+            t0 = time.time()
+            ref = oracle.topp_select(rows_s, top_p)
+            t_sel += time.time() - t0
+            mask = ref.mask().reshape(B, H_kv, n)
+            q0 = qs[layer].view(torch.int16).cpu().numpy().view(np.uint16)
+            k0 = ks[layer].view(torch.int16).cpu().numpy().view(np.uint16)
+            v0 = vs[layer].view(torch.int16).cpu().numpy().view(np.uint16)
+            t0 = time.time()
+            o_ref, _ = oracle.masked_attention(q0, k0, v0, mask, bf16=True)
+            t_att += time.time() - t0
+            samp_bytes += float(ref.counts.sum()) * 2 * d * 2
+            # the same sample doubles as a full-size check of the device result
+            got = (outs if "unfused" in results else outs_f)[layer].cpu().numpy()
+            err = np.abs(got - o_ref).max(axis=-1) / np.abs(o_ref).max(axis=-1)
+            worst = max(worst, float(err.max()))
         line["cpu_baseline"] = {
-            "value": round(samp_bytes / t_total / 1e9, 4), "unit": "GB/s", "cores": cores, "kind": "oracle",
-            "sample": f"layer 0: selection of its {R} rows ({t_sel:.2f} s) and masked dense attention of "
-                      f"sequence 0 (8 kv heads, 32x5 query rows, {t_att:.2f} s); rate = kept K/V bytes of "
-                      f"sequence 0 / (attention time + 1/{B} of the selection time)"}
-        # the same sample doubles as a full-size spot check of the device result
-        got = outs[0][:1].cpu().numpy() if "unfused" in results else outs_f[0][:1].cpu().numpy()
-        err = np.abs(got - o_ref).max(axis=-1) / np.abs(o_ref).max(axis=-1)
-        line["spot_check_row_rel_err"] = float(err.max())
+            "value": round(samp_bytes / (t_sel + t_att) / 1e9, 4), "unit": "GB/s", "cores": cores, "kind": "oracle",
+            "sample": f"layers 0..{n_samp - 1} of the step ({n_samp * R} selection rows, {n_samp * B * H_q * T} query rows): "
+                      f"oracle selection {t_sel:.2f} s + masked dense attention {t_att:.2f} s wall on {cores} threads; "
+                      f"rate = kept K/V bytes of the sample / that time"}
+        line["full_size_check_row_rel_err"] = worst
 
     print(json.dumps(line))
 

@@ -445,13 +445,8 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
 
         f32x4 o[NQT][8];                     // O^T[dv = 16t + 4g + i][q = l16]
         float m_ref[NQT], l_sum[NQT];        // reference max (log2 units) and sum of weights
-#pragma unroll
-        for (int qt = 0; qt < NQT; ++qt) {
-            m_ref[qt] = -INFINITY;
-            l_sum[qt] = 0.0f;
-#pragma unroll
-            for (int t = 0; t < 8; ++t) o[qt][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
-        }
+                                             // (zeroed once the first chunk is staged, which keeps the
+                                             //  registers free during the staging)
 
         // row offsets (in 16-byte units) of the 8 rows this lane helps to fetch for one tile
         auto read_entries = [&](int tile_in_chunk, uint32_t (&ent)[8]) {
@@ -486,6 +481,15 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
 #pragma unroll
                 for (int c = 0; c < 4; ++c) asm volatile("" :: "v"(qf[qt][c]));
             STAMP(2);
+            if (ch_begin == lt_begin) {
+#pragma unroll
+                for (int qt = 0; qt < NQT; ++qt) {
+                    m_ref[qt] = -INFINITY;
+                    l_sum[qt] = 0.0f;
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) o[qt][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+                }
+            }
 
             // The gathers are not tracked by the compiler's wait insertion; every wait on them is
             // written out.  Per wave the order of issue is K(t), V(t), K(t+1), V(t+1), ...
