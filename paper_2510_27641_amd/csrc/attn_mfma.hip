@@ -39,9 +39,14 @@ constexpr int D = 128;
 constexpr int ROW_BYTES = D * 2;      // one K or V row
 constexpr int TILE_BYTES = TILE * ROW_BYTES;          // 8 KiB per tensor
 constexpr int WAVE_LDS = 2 * TILE_BYTES;              // K buffer, V buffer
-constexpr int MAX_ROWS = 2048;        // rows whose tile prefix fits the LDS table
+constexpr int MAX_ROWS = 1536;        // rows whose cost prefix fits the LDS table
 constexpr int CHUNK_TILES = 64;       // tiles whose row offsets are staged in LDS at a time
 constexpr int MAX_BLOCKS = SPECATTN_MAX_N / SEL_BLOCK;   // selection blocks per row, at most
+// dynamic LDS: wave buffers, cost prefix, counts, wave sums, tile counter, list entries, block prefix,
+// scan scratch, and the Q tile (two 16-row tiles at most) at the end
+constexpr int LDS_BYTES = NW * WAVE_LDS +
+                          (2 * MAX_ROWS + 1 + NW + 1 + CHUNK_TILES * TILE + MAX_BLOCKS + 1 + 2 * (NW + 1)) * 4 + 48 +
+                          2 * 16 * ROW_BYTES;
 constexpr int SEG_COST = 10;          // cost of starting a row segment, in tiles
 constexpr float RESCALE_SLACK = 8.0f; // log2 units the running max may exceed the reference by
 
@@ -94,6 +99,26 @@ __device__ __forceinline__ void lds_read_k(KFrags &k, const uint32_t (&addr)[4])
           "=&v"(k.f[1][0]), "=&v"(k.f[1][1]), "=&v"(k.f[1][2]), "=&v"(k.f[1][3])
         : "v"(addr[0]), "v"(addr[1]), "v"(addr[2]), "v"(addr[3])
         : "memory");
+}
+// The Q fragments of one 16-row query tile (k-steps 0..3) from the Q tile staged in LDS.
+struct QFrags { u32x4 f[4]; };
+__device__ __forceinline__ void lds_read_q(QFrags &q, const uint32_t (&addr)[4], bool second_tile)
+{
+    if (!second_tile)
+        asm volatile(
+            "ds_read_b128 %0, %4\n ds_read_b128 %1, %5\n ds_read_b128 %2, %6\n ds_read_b128 %3, %7\n"
+            "s_waitcnt lgkmcnt(0)"
+            : "=&v"(q.f[0]), "=&v"(q.f[1]), "=&v"(q.f[2]), "=&v"(q.f[3])
+            : "v"(addr[0]), "v"(addr[1]), "v"(addr[2]), "v"(addr[3])
+            : "memory");
+    else
+        asm volatile(
+            "ds_read_b128 %0, %4 offset:4096\n ds_read_b128 %1, %5 offset:4096\n"
+            "ds_read_b128 %2, %6 offset:4096\n ds_read_b128 %3, %7 offset:4096\n"
+            "s_waitcnt lgkmcnt(0)"
+            : "=&v"(q.f[0]), "=&v"(q.f[1]), "=&v"(q.f[2]), "=&v"(q.f[3])
+            : "v"(addr[0]), "v"(addr[1]), "v"(addr[2]), "v"(addr[3])
+            : "memory");
 }
 // Transposing reads: within each group of 16 lanes, lane i receives element i%4 of the four 8-byte
 // rows addressed by lanes i/4, i/4+4, i/4+8 and i/4+12.  Four dv tiles, both halves of the tile.
@@ -221,6 +246,7 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
     float *ml_lds = reinterpret_cast<float *>(ent_lds);                 // wave merge: [NW][2][32], same space
     int *blk_pre = reinterpret_cast<int *>(ent_lds + CHUNK_TILES * TILE);   // fused: [MAX_BLOCKS + 1] kept before block
     int *scan_ws = blk_pre + MAX_BLOCKS + 1;                            // fused: [2][NW + 1] scan scratch
+    char *q_lds = smem + LDS_BYTES - NQT * 16 * ROW_BYTES;              // Q tile [NQT*16][256 B], chunks swizzled like K
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l16 = lane & 15, g = lane >> 4;
@@ -229,10 +255,15 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
     const uint32_t vs_addr = ks_addr + TILE_BYTES;
     const uint32_t ent_addr = (uint32_t)(uintptr_t)LDS_PTR(uint32_t, ent_lds);
     const uint32_t ctr_addr = (uint32_t)(uintptr_t)LDS_PTR(int, tile_ctr);
+    const uint32_t q_addr = (uint32_t)(uintptr_t)LDS_PTR(char, q_lds);
     // K fragment of k-step c: row l16 (+16 per position tile), 16-byte chunk 4c + g
     uint32_t k_off[4];
 #pragma unroll
     for (int c = 0; c < 4; ++c) k_off[c] = ks_addr + (uint32_t)(l16 * ROW_BYTES + (((4 * c + g) ^ swz(l16)) << 4));
+    // Q fragment of k-step c: same pattern on the Q tile (row = query row l16, +16 for the second tile)
+    uint32_t q_off[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) q_off[c] = q_addr + (k_off[c] - ks_addr);
     // V^T fragment of dv tile t: source lane points at row 4g + l16/4 (+16 per half), 4 values from
     // column 16t + 4*(l16%4)
     uint32_t v_off[8];
@@ -291,22 +322,25 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
     if (r >= rows) return;
 
     // ---- per-segment inputs that are fetched ahead of time -------------------------------------------
-    bf16x8 qf[NQT][4];                       // Q fragments: lane (q = l16, g) holds Q[q][32c + 8g .. +8)
+    // The Q tile of a segment goes through LDS: thread t fetches 16-byte chunk t%16 of query row t/16
+    // ahead of time and stores it (swizzled like a K row) when the segment is staged.
     uint32_t ent_pf[EPT];                    // this thread's entries of the segment's first chunk
+    u32x4 q_pf = (u32x4){0u, 0u, 0u, 0u};
     auto fetch_q = [&](int rr) {
         const int b = rr / a.H_kv, h = rr - b * a.H_kv;
-#pragma unroll
-        for (int qt = 0; qt < NQT; ++qt) {
-            const int qi = qt * 16 + l16;
+        const int qi = tid >> 4, ch = tid & 15;
+        q_pf = (u32x4){0u, 0u, 0u, 0u};
+        if (qi < QT) {
             const int gh = qi / a.T, tt = qi - gh * a.T;
             const uint16_t *qp = static_cast<const uint16_t *>(a.q) + (int64_t)b * a.q_stride_b +
                                  (int64_t)(h * G + gh) * a.q_stride_h + (int64_t)tt * a.q_stride_t;
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                if (qi < QT) qf[qt][c] = *reinterpret_cast<const bf16x8 *>(qp + 32 * c + 8 * g);
-                else qf[qt][c] = (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
-            }
+            q_pf = *reinterpret_cast<const u32x4 *>(qp + ch * 8);
         }
+    };
+    auto store_q = [&]() {
+        const int qi = tid >> 4, ch = tid & 15;
+        if (qi < NQT * 16)
+            *reinterpret_cast<u32x4 *>(q_lds + qi * ROW_BYTES + ((ch ^ swz(qi & 15)) << 4)) = q_pf;
     };
     // row offsets (16-byte units) of list entries [first, first + n) of row rr; entries past the end of
     // the list repeat the last kept position (their scores are masked), so every gather stays in bounds
@@ -466,20 +500,16 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
             // ---- stage this chunk's row offsets in LDS (the first chunk's were fetched ahead) ----------
             if (FUSED) {
                 if (ch_begin == lt_begin) fused_prepare_row(r); else __syncthreads();
+                if (ch_begin == lt_begin) store_q();
                 fused_stage(r, ch_begin * TILE, (ch_end - ch_begin) * TILE);
             } else {
                 if (ch_begin != lt_begin) fetch_entries(r, ch_begin * TILE, (ch_end - ch_begin) * TILE, ent_pf);
-                __syncthreads();                                       // previous users of ent_lds are done
+                __syncthreads();                                       // previous users of ent_lds / q_lds are done
                 store_entries((ch_end - ch_begin) * TILE, ent_pf);
+                if (ch_begin == lt_begin) store_q();
             }
             if (tid == 0) *tile_ctr = 0;
             __syncthreads();
-            // Touch the Q fragments here, so that the compiler's wait for their loads sits outside the
-            // tile loop (inside it, it would also wait for the gathers of the next tile).
-#pragma unroll
-            for (int qt = 0; qt < NQT; ++qt)
-#pragma unroll
-                for (int c = 0; c < 4; ++c) asm volatile("" :: "v"(qf[qt][c]));
             STAMP(2);
             if (ch_begin == lt_begin) {
 #pragma unroll
@@ -519,16 +549,19 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
                         issue(kbh, wave_lds, ent);
                     }
 #pragma unroll
-                    for (int pt = 0; pt < 2; ++pt)
+                    for (int qt = 0; qt < NQT; ++qt) {
+                        QFrags qf;
+                        lds_read_q(qf, q_off, qt == 1);
 #pragma unroll
-                        for (int qt = 0; qt < NQT; ++qt) {
+                        for (int pt = 0; pt < 2; ++pt) {
                             f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                             for (int c = 0; c < 4; ++c)
                                 acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf.f[pt][c]),
-                                                                              qf[qt][c], acc, 0, 0, 0);
+                                                                              __builtin_bit_cast(bf16x8, qf.f[c]), acc, 0, 0, 0);
                             s[qt][pt] = acc;
                         }
+                    }
                 }
 
                 // ---- softmax weights; lane (q = l16, g) holds positions 16pt + 4g + i ---------------
@@ -733,8 +766,7 @@ specattn_status launch_attn_mfma(const AttnLaunch &a, hipStream_t stream)
     ws += (((size_t)rows + 1) * sizeof(int32_t) + 255) & ~(size_t)255;
     plan.part_ml = reinterpret_cast<float *>(ws);
     plan.part_o = plan.part_ml + slots * qtp * 2;
-    const size_t lds = (size_t)NW * WAVE_LDS +
-                       (2 * MAX_ROWS + 1 + NW + 1 + CHUNK_TILES * TILE + MAX_BLOCKS + 1 + 2 * (NW + 1)) * sizeof(int);
+    const size_t lds = LDS_BYTES;
     const int layout = a.indices_are_physical ? PHYSICAL : (a.page_table ? PAGE_TABLE : CONTIGUOUS);
     const void *fn = nullptr;
     const bool fused = a.probs != nullptr;
