@@ -738,13 +738,14 @@ __global__ void merge_partials_kernel(AttnLaunch a, Plan plan, int qtp)
 bool attn_mfma_supported(const AttnLaunch &a)
 {
     const int G = a.H_q / a.H_kv;
-    return a.dtype == SPECATTN_BF16 && a.d == 128 && G * a.T <= 32 && a.B * a.H_kv <= MAX_ROWS;
+    return a.dtype == SPECATTN_BF16 && a.d == 128 && G * a.T <= 32 && a.H_kv <= MAX_ROWS;
 }
 
 int attn_mfma_workgroups() { return cu_count(); }
 
 size_t attn_mfma_workspace_bytes(int rows, int G, int T)
 {
+    if (rows > MAX_ROWS) rows = MAX_ROWS;                 // larger batches run as several launches
     const size_t qtp = (G * T <= 16) ? 16 : 32;
     const size_t slots = (size_t)attn_mfma_workgroups() + rows;
     size_t bytes = (((size_t)rows + 1) * sizeof(int32_t) + 255) & ~(size_t)255;        // cost prefix
@@ -752,7 +753,7 @@ size_t attn_mfma_workspace_bytes(int rows, int G, int T)
     return (bytes + 255) & ~(size_t)255;
 }
 
-specattn_status launch_attn_mfma(const AttnLaunch &a, hipStream_t stream)
+static specattn_status launch_chunk(const AttnLaunch &a, hipStream_t stream)
 {
     const int rows = a.B * a.H_kv;
     const int G = a.H_q / a.H_kv;
@@ -805,6 +806,42 @@ specattn_status launch_attn_mfma(const AttnLaunch &a, hipStream_t stream)
     if (st != SPECATTN_OK) return st;
     hipLaunchKernelGGL(merge_partials_kernel, dim3(rows * QT), dim3(D), 0, stream, a, plan, qtp);
     return check_launch("merge_partials_kernel");
+}
+
+// Batches with more rows than the kernel's LDS tables hold go out as several launches over
+// consecutive sequences (rows are independent; the workspace is reused, the stream orders them).
+specattn_status launch_attn_mfma(const AttnLaunch &a, hipStream_t stream)
+{
+    const int b_max = MAX_ROWS / a.H_kv;
+    if (a.B <= b_max) return launch_chunk(a, stream);
+    const int es = 2;                                       // bf16
+    const int G = a.H_q / a.H_kv;
+    for (int b0 = 0; b0 < a.B; b0 += b_max) {
+        AttnLaunch c = a;
+        c.B = (a.B - b0) < b_max ? (a.B - b0) : b_max;
+        const int64_t r0 = (int64_t)b0 * a.H_kv;
+        c.q = static_cast<const char *>(a.q) + (int64_t)b0 * a.q_stride_b * es;
+        const bool paged = a.page_table != nullptr || a.indices_are_physical;
+        if (!paged) {
+            c.k = static_cast<const char *>(a.k) + (int64_t)b0 * a.kv_stride_b * es;
+            c.v = static_cast<const char *>(a.v) + (int64_t)b0 * a.kv_stride_b * es;
+        }
+        if (a.page_table) c.page_table = a.page_table + (int64_t)b0 * a.max_pages;
+        if (a.indices) c.indices = a.indices + r0 * a.idx_stride;
+        c.counts = a.counts + r0;
+        c.out = a.out + (int64_t)b0 * a.H_q * a.T * a.d;
+        if (a.lse) c.lse = a.lse + (int64_t)b0 * a.H_q * a.T;
+        if (a.seq_lens) c.seq_lens = a.seq_lens + b0;
+        if (a.probs) {
+            c.probs = a.probs + (int64_t)b0 * a.probs_stride_b;
+            c.tau = a.tau + r0;
+            c.block_counts = a.block_counts + r0 * a.blocks_per_row;
+        }
+        (void)G;
+        const specattn_status st = launch_chunk(c, stream);
+        if (st != SPECATTN_OK) return st;
+    }
+    return SPECATTN_OK;
 }
 
 }  // namespace specattn

@@ -109,6 +109,12 @@ def test_other_shapes_and_dtypes(shape):
     _run_and_compare(w, _oracle_selection_mask(w))
 
 
+def test_more_rows_than_one_launch_holds():
+    # 2048 rows: the matrix-core variant runs them as two launches over consecutive sequences
+    w = W.llama8b_layer(seed=12, B=256, n=256, H_q=16, H_kv=8, T=2, top_p=0.7)
+    _run_and_compare(w, _oracle_selection_mask(w))
+
+
 def test_one_selected_position_returns_its_value_row():
     w = W.llama8b_layer(seed=7, n=512)
     mask = np.zeros((w.B, w.H_kv, w.n), dtype=np.uint8)
