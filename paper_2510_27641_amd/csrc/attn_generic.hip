@@ -11,6 +11,8 @@
 
 #include <hip/hip_bf16.h>
 
+#include <mutex>
+
 namespace specattn {
 namespace {
 
@@ -193,14 +195,18 @@ specattn_status run_generic(const AttnLaunch &a, int rows, int n_splits, float *
                             hipStream_t stream)
 {
     const size_t lds = sizeof(float) * (MAX_QT * D + GEN_TILE * (D + 1) + GEN_TILE * D + MAX_QT * (GEN_TILE + 1) + 3 * MAX_QT);
-    static bool configured = false;
-    if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_generic_kernel<T, D>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
-            set_error("cannot reserve %zu bytes of LDS", lds);
-            return SPECATTN_EHIP;
+    {
+        static std::mutex mu;
+        static bool configured = false;
+        std::lock_guard<std::mutex> lock(mu);
+        if (!configured) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_generic_kernel<T, D>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+                set_error("cannot reserve %zu bytes of LDS", lds);
+                return SPECATTN_EHIP;
+            }
+            configured = true;
         }
-        configured = true;
     }
     hipLaunchKernelGGL((attn_generic_kernel<T, D>), dim3(rows * n_splits), dim3(GEN_THREADS), lds, stream, a,
                        n_splits, part_o, part_ml);

@@ -19,6 +19,8 @@
 // accumulators of that row never leave the lane.
 #include "common.h"
 
+#include <mutex>
+
 namespace specattn {
 namespace {
 
@@ -465,7 +467,33 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
         fetch_q(r);
         const int n0 = ((le - lb) < CHUNK_TILES ? (le - lb) : CHUNK_TILES) * TILE;
         if (!FUSED) fetch_entries(r, lb * TILE, n0, ent_pf);
+        // Head start: wave w fetches the indices of tile w of the first chunk itself and requests that
+        // tile's rows at once, instead of waiting until the whole chunk's list is staged in LDS.
+        if (!FUSED && wave < n0 / TILE) {
+            const int b = r / a.H_kv, h = r - b * a.H_kv;
+            const KvMap map = make_map<LAYOUT>(a, b, h);
+            const int32_t *idx = a.indices + (int64_t)r * a.idx_stride;
+            const int count = cnt_lds[r];
+            uint32_t e[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                int jj = (lb + wave) * TILE + 4 * i + g;
+                jj = jj < count ? jj : count - 1;
+                e[i] = (uint32_t)(map.rel<LAYOUT>(idx[jj]) >> 3);
+            }
+            const char *kb0 = static_cast<const char *>(a.k) + map.base * 2;
+            const char *vb0 = static_cast<const char *>(a.v) + map.base * 2;
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                __builtin_amdgcn_global_load_lds(GLOBAL_PTR(kb0 + ((int64_t)e[i] << 4) + lane_chunk[i & 3]),
+                                                 LDS_PTR(void, wave_lds + i * 1024), 16, 0, 0);
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                __builtin_amdgcn_global_load_lds(GLOBAL_PTR(vb0 + ((int64_t)e[i] << 4) + lane_chunk[i & 3]),
+                                                 LDS_PTR(void, wave_lds + TILE_BYTES + i * 1024), 16, 0, 0);
+        }
     }
+    bool head_start = !FUSED;                 // true until the first chunk of the first segment has begun
 
     while (r < rows) {
         int lt_begin, lt_end;
@@ -508,7 +536,7 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
                 store_entries((ch_end - ch_begin) * TILE, ent_pf);
                 if (ch_begin == lt_begin) store_q();
             }
-            if (tid == 0) *tile_ctr = 0;
+            if (tid == 0) *tile_ctr = head_start ? ((ch_end - ch_begin) < NW ? (ch_end - ch_begin) : NW) : 0;
             __syncthreads();
             STAMP(2);
             if (ch_begin == lt_begin) {
@@ -527,12 +555,18 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
             // simply takes fewer), one claim ahead of the tile whose gathers are being issued.
             uint32_t ent[8];
             const int n_ch = ch_end - ch_begin;
-            int cur = lds_claim(ctr_addr, lane);
-            if (cur < n_ch) {
-                read_entries(cur, ent);
-                issue(kbh, wave_lds, ent);
-                issue(vbh, wave_lds + TILE_BYTES, ent);
+            int cur;
+            if (head_start && wave < n_ch) {
+                cur = wave;                                            // already requested above
+            } else {
+                cur = lds_claim(ctr_addr, lane);
+                if (cur < n_ch) {
+                    read_entries(cur, ent);
+                    issue(kbh, wave_lds, ent);
+                    issue(vbh, wave_lds + TILE_BYTES, ent);
+                }
             }
+            head_start = false;
             int nxt = lds_claim(ctr_addr, lane);
             while (cur < n_ch) {
                 const int lt = ch_begin + cur;
@@ -782,20 +816,21 @@ static specattn_status launch_chunk(const AttnLaunch &a, hipStream_t stream)
     }
     if (!fn) { set_error("the fused path takes logical positions, not pool slots"); return SPECATTN_EUNSUPPORTED; }
 #undef PICK
-    static const void *configured[16] = {nullptr};
-    bool seen = false;
-    for (const void *c : configured) seen = seen || c == fn;
-    if (!seen) {
-        if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
-            set_error("cannot reserve %zu bytes of LDS", lds);
-            return SPECATTN_EHIP;
+    {
+        // the kernels use more LDS than the default limit; raise it once per kernel (any thread may call)
+        static std::mutex mu;
+        static const void *configured[16] = {nullptr};
+        std::lock_guard<std::mutex> lock(mu);
+        bool seen = false;
+        for (const void *c : configured) seen = seen || c == fn;
+        if (!seen) {
+            if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+                set_error("cannot reserve %zu bytes of LDS", lds);
+                return SPECATTN_EHIP;
+            }
+            for (const void *&c : configured) if (!c) { c = fn; break; }
         }
-        for (const void *&c : configured) if (!c) { c = fn; break; }
     }
-#ifdef SPECATTN_TIMING
-    extern long long *g_specattn_timing;
-    plan.timing = g_specattn_timing;
-#endif
     void *kargs[] = {const_cast<AttnLaunch *>(&a), &plan};
     if (hipLaunchKernel(fn, dim3(plan.n_wg), dim3(THREADS), kargs, lds, stream) != hipSuccess) {
         set_error("attn_mfma_kernel: launch failed");

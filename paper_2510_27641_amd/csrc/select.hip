@@ -223,7 +223,15 @@ __global__ __launch_bounds__(THREADS, 4) void topp_select_kernel(SelectLaunch a)
             for (int i = 0; i < NV4; ++i)
                 if (i < n_items) fn(i, data[i]);
         } else {
-            for (int i = 0; i < n_items; ++i) fn(i, load_item(i));
+            // rows too long for the registers: stream them, four loads in flight per thread
+            for (int i0 = 0; i0 < n_items; i0 += 4) {
+                uint4 u[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) u[k] = (i0 + k < n_items) ? load_item(i0 + k) : make_uint4(0, 0, 0, 0);
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    if (i0 + k < n_items) fn(i0 + k, u[k]);
+            }
         }
     };
 
