@@ -673,51 +673,77 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
             if (!FUSED) fetch_entries(r_next, lb * TILE, n0, ent_pf);
         }
 
-        // ---- combine the waves of this workgroup -------------------------------------------------------
+        // ---- combine the waves of this workgroup: a tree over the waves (partner = wave + stride), each
+        //      state handed over lane by lane through the partner's own, now idle, tile buffers ---------
         __syncthreads();                         // every wave is done with its buffers and with ent_lds
         STAMP(4);
-        float *dump = reinterpret_cast<float *>(wave_lds);     // [QTP][D], 4-float blocks XOR-swizzled by q
+        {
+            float *mlw = ml_lds;                 // [NW][64 lanes][2 * NQT]: m, l of every lane
 #pragma unroll
-        for (int qt = 0; qt < NQT; ++qt) {
-            float l = l_sum[qt];
-            l += __shfl_xor(l, 16, 64);
-            l += __shfl_xor(l, 32, 64);
-            const int q = qt * 16 + l16;
+            for (int stride = NW / 2; stride >= 1; stride >>= 1) {
+                if (wave >= stride && wave < 2 * stride) {
+                    float *dmp = reinterpret_cast<float *>(wave_lds);          // [NQT * 8][64 lanes] float4
 #pragma unroll
-            for (int t = 0; t < 8; ++t)
-                *reinterpret_cast<f32x4 *>(dump + q * D + (((4 * t + g) ^ (q & 31)) << 2)) = o[qt][t];
-            if (g == 0) { ml_lds[wave * 64 + q] = m_ref[qt]; ml_lds[wave * 64 + 32 + q] = l; }
-        }
-        __syncthreads();
-        STAMP(5);
-        // Workgroups w0..w1 share row r.  A row owned by one workgroup is finished here; otherwise the
-        // partial goes to slot w + r for the merge kernel.
-        const int w0 = (pre[r] + SEG_COST) / share, w1 = (pre[r + 1] - 1) / share;
-        const int slot = blockIdx.x + r;
-        float *po = plan.part_o + (int64_t)slot * QTP * D;
-        float *pml = plan.part_ml + (int64_t)slot * QTP * 2;
-        for (int e = tid; e < QT * D; e += THREADS) {
-            const int q = e >> 7, dv = e & (D - 1);
-            const int col = (((dv >> 2) ^ (q & 31)) << 2) | (dv & 3);
-            float m = -INFINITY;
+                    for (int qt = 0; qt < NQT; ++qt) {
 #pragma unroll
-            for (int w = 0; w < NW; ++w) m = fmaxf(m, ml_lds[w * 64 + q]);
-            float acc = 0.0f, l = 0.0f;
+                        for (int t = 0; t < 8; ++t)
+                            *reinterpret_cast<f32x4 *>(dmp + ((qt * 8 + t) * 64 + lane) * 4) = o[qt][t];
+                        mlw[(wave * 64 + lane) * 2 * NQT + 2 * qt] = m_ref[qt];
+                        mlw[(wave * 64 + lane) * 2 * NQT + 2 * qt + 1] = l_sum[qt];
+                    }
+                }
+                __syncthreads();
+                if (wave < stride) {
+                    const float *dmp = reinterpret_cast<const float *>(smem + (wave + stride) * WAVE_LDS);
 #pragma unroll
-            for (int w = 0; w < NW; ++w) {
-                const float mw = ml_lds[w * 64 + q];
-                const float f = (mw == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(mw - m);
-                acc += f * reinterpret_cast<const float *>(smem + w * WAVE_LDS)[q * D + col];
-                l += f * ml_lds[w * 64 + 32 + q];
+                    for (int qt = 0; qt < NQT; ++qt) {
+                        const float mb = mlw[((wave + stride) * 64 + lane) * 2 * NQT + 2 * qt];
+                        const float lb = mlw[((wave + stride) * 64 + lane) * 2 * NQT + 2 * qt + 1];
+                        const float mn = fmaxf(m_ref[qt], mb);
+                        const float fa = (m_ref[qt] == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(m_ref[qt] - mn);
+                        const float fb = (mb == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(mb - mn);
+                        l_sum[qt] = l_sum[qt] * fa + lb * fb;
+                        m_ref[qt] = mn;
+#pragma unroll
+                        for (int t = 0; t < 8; ++t) {
+                            const f32x4 ob = *reinterpret_cast<const f32x4 *>(dmp + ((qt * 8 + t) * 64 + lane) * 4);
+                            o[qt][t] = o[qt][t] * fa + ob * fb;
+                        }
+                    }
+                }
             }
-            if (w0 == w1) {
-                const int gh = q / a.T, tt = q - gh * a.T;
-                const int64_t orow = ((int64_t)b * a.H_q + (h * G + gh)) * a.T + tt;
-                a.out[orow * D + dv] = l > 0.0f ? acc / l : 0.0f;
-                if (a.lse && dv == 0) a.lse[orow] = l > 0.0f ? (m + log2f(l)) * 0.6931471805599453f : -INFINITY;
-            } else {
-                po[e] = acc;
-                if (dv == 0) { pml[2 * q] = m; pml[2 * q + 1] = l; }
+        }
+        STAMP(5);
+        // Wave 0 now holds the workgroup's state for row r.  Workgroups w0..w1 share the row: a row owned
+        // by one workgroup is finished here; otherwise the partial goes to slot w + r for the merge kernel.
+        const int w0 = (pre[r] + SEG_COST) / share, w1 = (pre[r + 1] - 1) / share;
+        if (wave == 0) {
+            const int slot = blockIdx.x + r;
+            float *po = plan.part_o + (int64_t)slot * QTP * D;
+            float *pml = plan.part_ml + (int64_t)slot * QTP * 2;
+#pragma unroll
+            for (int qt = 0; qt < NQT; ++qt) {
+                float l = l_sum[qt];
+                l += __shfl_xor(l, 16, 64);
+                l += __shfl_xor(l, 32, 64);
+                const int q = qt * 16 + l16;
+                if (q < QT) {
+                    if (w0 == w1) {
+                        const int gh = q / a.T, tt = q - gh * a.T;
+                        const int64_t orow = ((int64_t)b * a.H_q + (h * G + gh)) * a.T + tt;
+#pragma unroll
+                        for (int t = 0; t < 8; ++t)
+                            *reinterpret_cast<f32x4 *>(a.out + orow * D + 16 * t + 4 * g) =
+                                l > 0.0f ? o[qt][t] / l : (f32x4){0.f, 0.f, 0.f, 0.f};
+                        if (a.lse && g == 0)
+                            a.lse[orow] = l > 0.0f ? (m_ref[qt] + log2f(l)) * 0.6931471805599453f : -INFINITY;
+                    } else {
+#pragma unroll
+                        for (int t = 0; t < 8; ++t)
+                            *reinterpret_cast<f32x4 *>(po + q * D + 16 * t + 4 * g) = o[qt][t];
+                        if (g == 0) { pml[2 * q] = m_ref[qt]; pml[2 * q + 1] = l; }
+                    }
+                }
             }
         }
         STAMP(6);
