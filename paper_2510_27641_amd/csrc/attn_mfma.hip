@@ -673,57 +673,50 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
             if (!FUSED) fetch_entries(r_next, lb * TILE, n0, ent_pf);
         }
 
-        // ---- combine the waves of this workgroup: a tree over the waves (partner = wave + stride), each
-        //      state handed over lane by lane through the partner's own, now idle, tile buffers ---------
+        // ---- combine the waves of this workgroup: every wave hands its state over lane by lane through its
+        //      own, now idle, tile buffers; wave w then reduces and writes the (query tile, dv tile) blocks
+        //      k = w * KPW .. of all eight states ---------------------------------------------------------
         __syncthreads();                         // every wave is done with its buffers and with ent_lds
         STAMP(4);
+        float *mlw = ml_lds;                     // [NW][64 lanes][2 * NQT]: m, l of every lane
         {
-            float *mlw = ml_lds;                 // [NW][64 lanes][2 * NQT]: m, l of every lane
+            float *dmp = reinterpret_cast<float *>(wave_lds);                  // [NQT * 8][64 lanes] float4
 #pragma unroll
-            for (int stride = NW / 2; stride >= 1; stride >>= 1) {
-                if (wave >= stride && wave < 2 * stride) {
-                    float *dmp = reinterpret_cast<float *>(wave_lds);          // [NQT * 8][64 lanes] float4
+            for (int qt = 0; qt < NQT; ++qt) {
 #pragma unroll
-                    for (int qt = 0; qt < NQT; ++qt) {
-#pragma unroll
-                        for (int t = 0; t < 8; ++t)
-                            *reinterpret_cast<f32x4 *>(dmp + ((qt * 8 + t) * 64 + lane) * 4) = o[qt][t];
-                        mlw[(wave * 64 + lane) * 2 * NQT + 2 * qt] = m_ref[qt];
-                        mlw[(wave * 64 + lane) * 2 * NQT + 2 * qt + 1] = l_sum[qt];
-                    }
-                }
-                __syncthreads();
-                if (wave < stride) {
-                    const float *dmp = reinterpret_cast<const float *>(smem + (wave + stride) * WAVE_LDS);
-#pragma unroll
-                    for (int qt = 0; qt < NQT; ++qt) {
-                        const float mb = mlw[((wave + stride) * 64 + lane) * 2 * NQT + 2 * qt];
-                        const float lb = mlw[((wave + stride) * 64 + lane) * 2 * NQT + 2 * qt + 1];
-                        const float mn = fmaxf(m_ref[qt], mb);
-                        const float fa = (m_ref[qt] == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(m_ref[qt] - mn);
-                        const float fb = (mb == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(mb - mn);
-                        l_sum[qt] = l_sum[qt] * fa + lb * fb;
-                        m_ref[qt] = mn;
-#pragma unroll
-                        for (int t = 0; t < 8; ++t) {
-                            const f32x4 ob = *reinterpret_cast<const f32x4 *>(dmp + ((qt * 8 + t) * 64 + lane) * 4);
-                            o[qt][t] = o[qt][t] * fa + ob * fb;
-                        }
-                    }
-                }
+                for (int t = 0; t < 8; ++t)
+                    *reinterpret_cast<f32x4 *>(dmp + ((qt * 8 + t) * 64 + lane) * 4) = o[qt][t];
+                mlw[(wave * 64 + lane) * 2 * NQT + 2 * qt] = m_ref[qt];
+                mlw[(wave * 64 + lane) * 2 * NQT + 2 * qt + 1] = l_sum[qt];
             }
         }
+        __syncthreads();
         STAMP(5);
-        // Wave 0 now holds the workgroup's state for row r.  Workgroups w0..w1 share the row: a row owned
-        // by one workgroup is finished here; otherwise the partial goes to slot w + r for the merge kernel.
+        // Workgroups w0..w1 share row r: a row owned by one workgroup is finished here; otherwise the
+        // partial goes to slot w + r for the merge kernel.
         const int w0 = (pre[r] + SEG_COST) / share, w1 = (pre[r + 1] - 1) / share;
-        if (wave == 0) {
+        {
+            constexpr int KPW = NQT * 8 / NW;    // blocks per wave (2 or 1)
             const int slot = blockIdx.x + r;
             float *po = plan.part_o + (int64_t)slot * QTP * D;
             float *pml = plan.part_ml + (int64_t)slot * QTP * 2;
 #pragma unroll
-            for (int qt = 0; qt < NQT; ++qt) {
-                float l = l_sum[qt];
+            for (int kk = 0; kk < KPW; ++kk) {
+                const int k = wave * KPW + kk;   // uniform
+                const int qt = k >> 3, t = k & 7;
+                float m = -INFINITY;
+#pragma unroll
+                for (int w = 0; w < NW; ++w) m = fmaxf(m, mlw[(w * 64 + lane) * 2 * NQT + 2 * qt]);
+                f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
+                float l = 0.0f;
+#pragma unroll
+                for (int w = 0; w < NW; ++w) {
+                    const float mw = mlw[(w * 64 + lane) * 2 * NQT + 2 * qt];
+                    const float f = (mw == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(mw - m);
+                    l += f * mlw[(w * 64 + lane) * 2 * NQT + 2 * qt + 1];
+                    acc += f * *reinterpret_cast<const f32x4 *>(reinterpret_cast<const float *>(smem + w * WAVE_LDS) +
+                                                                (k * 64 + lane) * 4);
+                }
                 l += __shfl_xor(l, 16, 64);
                 l += __shfl_xor(l, 32, 64);
                 const int q = qt * 16 + l16;
@@ -731,17 +724,13 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
                     if (w0 == w1) {
                         const int gh = q / a.T, tt = q - gh * a.T;
                         const int64_t orow = ((int64_t)b * a.H_q + (h * G + gh)) * a.T + tt;
-#pragma unroll
-                        for (int t = 0; t < 8; ++t)
-                            *reinterpret_cast<f32x4 *>(a.out + orow * D + 16 * t + 4 * g) =
-                                l > 0.0f ? o[qt][t] / l : (f32x4){0.f, 0.f, 0.f, 0.f};
-                        if (a.lse && g == 0)
-                            a.lse[orow] = l > 0.0f ? (m_ref[qt] + log2f(l)) * 0.6931471805599453f : -INFINITY;
+                        *reinterpret_cast<f32x4 *>(a.out + orow * D + 16 * t + 4 * g) =
+                            l > 0.0f ? acc / l : (f32x4){0.f, 0.f, 0.f, 0.f};
+                        if (a.lse && g == 0 && t == 0)
+                            a.lse[orow] = l > 0.0f ? (m + log2f(l)) * 0.6931471805599453f : -INFINITY;
                     } else {
-#pragma unroll
-                        for (int t = 0; t < 8; ++t)
-                            *reinterpret_cast<f32x4 *>(po + q * D + 16 * t + 4 * g) = o[qt][t];
-                        if (g == 0) { pml[2 * q] = m_ref[qt]; pml[2 * q + 1] = l; }
+                        *reinterpret_cast<f32x4 *>(po + q * D + 16 * t + 4 * g) = acc;
+                        if (g == 0 && t == 0) { pml[2 * q] = m; pml[2 * q + 1] = l; }
                     }
                 }
             }
@@ -857,6 +846,11 @@ static specattn_status launch_chunk(const AttnLaunch &a, hipStream_t stream)
             for (const void *&c : configured) if (!c) { c = fn; break; }
         }
     }
+#ifdef SPECATTN_TIMING
+    extern long long *g_specattn_timing;      // development builds: set by the timing harness
+    plan.timing = g_specattn_timing;
+    if (!plan.timing) { set_error("timing build without a timing buffer"); return SPECATTN_EINVAL; }
+#endif
     void *kargs[] = {const_cast<AttnLaunch *>(&a), &plan};
     if (hipLaunchKernel(fn, dim3(plan.n_wg), dim3(THREADS), kargs, lds, stream) != hipSuccess) {
         set_error("attn_mfma_kernel: launch failed");
