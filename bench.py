@@ -196,6 +196,16 @@ def main():
         for ab, _ in batched:
             sa.specattn_sparse_decode_attn(ab)
     ms_batched = timed(attn_batched, max(args.steps // 2, 3), 1)
+    # ceiling of this machine: a plain 16 B per lane read over distinct 4 GiB pieces of the K cache
+    piece = max(1, (4 << 30) // (k_all[0].numel() * 2))
+    pieces = [k_all[i * piece:(i + 1) * piece] for i in range(min(3, k_all.shape[0] // piece))]
+    state = {"i": 0}
+
+    def stream_read():
+        sa.specattn_stream_read(pieces[state["i"] % len(pieces)])
+        state["i"] += 1
+    ms_read = timed(stream_read, 6, 2)
+    stream_gbps = pieces[0].numel() * 2 / (ms_read * 1e-3) / 1e9
     bytes_launch = sel_bytes_step / L
     achieved = bytes_launch / (ms_attn * 1e-3) / 1e9
 
@@ -219,6 +229,7 @@ def main():
                    "path": best_name, "selected_fraction": round(sel_frac, 4),
                    "selected_kv_bytes_per_step": int(sel_bytes_step)},
         "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
+        "stream_read_GBps": round(stream_gbps, 1), "pct_of_stream_read": round(100.0 * value / stream_gbps, 2),
         "verify_steps_per_s": round(1e3 / best, 2),
         "selection_rows_per_s": round(L * R / (best * 1e-3), 1),
         "paths": {k: {"ms_per_step": round(v, 4), "GBps": round(sel_bytes_step / (v * 1e-3) / 1e9, 1)}
@@ -230,7 +241,8 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "specattn_sparse_decode_attn = attn_mfma_kernel + merge_partials_kernel, one layer",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
-                     "algorithmic_bytes_per_launch": int(bytes_launch), "launch_us": round(ms_attn * 1e3, 2)},
+                     "algorithmic_bytes_per_launch": int(bytes_launch), "launch_us": round(ms_attn * 1e3, 2),
+                     "frac_of_stream_read": round(achieved / stream_gbps, 4)},
         "input_generation_s": round(t_gen, 1),
     }
     if not fused_ok:
@@ -240,7 +252,7 @@ def main():
     if not args.no_cpu_baseline:
         import oracle
         cores = oracle.set_threads(0)
-        n_samp = min(2, L)                                          # whole layers 0 .. n_samp-1
+        n_samp = min(4, L)                                          # whole layers 0 .. n_samp-1
         t_sel = t_att = 0.0
         samp_bytes = 0.0
         worst = 0.0

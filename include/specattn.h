@@ -149,6 +149,15 @@ specattn_status specattn_fused(const specattn_select_args *sel, const specattn_a
    fused call (both).  0 is returned for invalid arguments. */
 size_t specattn_workspace_size(const specattn_select_args *sel, const specattn_attn_args *attn);
 
+/*
+ * Measurement aid, not a step of the method: reads `bytes` of device memory at `src` once with plain
+ * 16-byte-per-lane loads and discards them (`sink`, optional, is a device word that is almost never
+ * written; it only keeps the loads alive).  Timed by the caller, it gives the read rate this machine
+ * reaches, which is what the gather of selected K/V rows (Section 3.5) is compared against.
+ * src and bytes must be multiples of 16: SPECATTN_EALIGN otherwise; NULL or 0: SPECATTN_EINVAL.
+ */
+specattn_status specattn_stream_read(const void *src, size_t bytes, uint32_t *sink, void *stream);
+
 /* Text of the calling thread's last error ("" if none).  Never NULL. */
 const char *specattn_last_error(void);
 

@@ -21,7 +21,7 @@ SEL_BLOCK = 1024
 F32, BF16 = 0, 1
 
 EXPORTS = ("specattn_topp_select", "specattn_sparse_decode_attn", "specattn_fused",
-           "specattn_workspace_size", "specattn_last_error", "specattn_version")
+           "specattn_workspace_size", "specattn_stream_read", "specattn_last_error", "specattn_version")
 
 
 class SelectArgs(C.Structure):
@@ -79,6 +79,8 @@ def load() -> C.CDLL:
         lib.specattn_fused.argtypes = [C.POINTER(SelectArgs), C.POINTER(AttnArgs), C.c_void_p]
         lib.specattn_workspace_size.restype = C.c_size_t
         lib.specattn_workspace_size.argtypes = [C.POINTER(SelectArgs), C.POINTER(AttnArgs)]
+        lib.specattn_stream_read.restype = C.c_int
+        lib.specattn_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         lib.specattn_last_error.restype = C.c_char_p
         lib.specattn_last_error.argtypes = []
         lib.specattn_version.restype = C.c_int
@@ -208,6 +210,12 @@ def specattn_sparse_decode_attn(attn: AttnArgs, stream=None) -> None:
 
 def specattn_fused(sel: SelectArgs, attn: AttnArgs, stream=None) -> None:
     _check(load().specattn_fused(C.byref(sel), C.byref(attn), _stream(stream)))
+
+
+def specattn_stream_read(src: torch.Tensor, sink: Optional[torch.Tensor] = None, stream=None) -> None:
+    """Plain read of every byte of `src` (contiguous); the caller times it."""
+    assert src.is_contiguous()
+    _check(load().specattn_stream_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink), _stream(stream)))
 
 
 def alloc_workspace(nbytes: int, device="cuda") -> torch.Tensor:

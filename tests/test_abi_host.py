@@ -89,3 +89,12 @@ def test_workspace_size_is_monotone_and_zero_for_selection():
     assert 0 < small <= big
     assert small % 256 == 0
     assert sa.specattn_workspace_size(None, _attn(H_q=30)) == 0
+
+
+def test_stream_read_rejects_bad_arguments():
+    lib = sa.load()
+    assert lib.specattn_stream_read(None, 1024, None, None) == sa.EINVAL
+    assert lib.specattn_stream_read(0x1000, 0, None, None) == sa.EINVAL
+    assert lib.specattn_stream_read(0x1008, 1024, None, None) == sa.EALIGN
+    assert lib.specattn_stream_read(0x1000, 1000, None, None) == sa.EALIGN
+    assert "16" in sa.last_error()
