@@ -96,6 +96,11 @@ typedef struct specattn_select_args {
  * All T queries of all G query heads of a kv head share that head's list.
  * A row with count 0 gives out = 0 and lse = -inf.  Accumulation is fp32;
  * `out` is fp32 whatever the input dtype.
+ *
+ * Dense layers (Section 4 keeps the first layers of the verifier dense): with
+ * indices == NULL and counts == NULL every position below seq_lens[b] (n_max
+ * when seq_lens is NULL) is attended to, through the same kernels, without
+ * any list in memory.  idx_stride_row / idx_capacity are then ignored.
  */
 typedef struct specattn_attn_args {
     const void *q;               /* [B][H_q][T][d] */
@@ -112,8 +117,9 @@ typedef struct specattn_attn_args {
     int64_t kv_stride_page;      /* paged: elements between pages; kv_stride_h / kv_stride_n then
                                     address head and in-page token */
 
-    const int32_t *seq_lens;     /* [B] or NULL; only used by specattn_fused (selection side) */
-    const int32_t *indices;      /* [B*H_kv][idx_stride_row], as written by specattn_topp_select */
+    const int32_t *seq_lens;     /* [B] or NULL; used by specattn_fused (selection side) and by dense calls */
+    const int32_t *indices;      /* [B*H_kv][idx_stride_row], as written by specattn_topp_select; NULL together
+                                    with counts = dense */
     int64_t idx_stride_row;
     const int32_t *counts;       /* [B*H_kv]; values above idx_capacity are clamped to it */
     int32_t idx_capacity;

@@ -74,15 +74,17 @@ specattn_status check_attn(const specattn_attn_args *a, bool fused)
 {
     if (!a) { set_error("attention args are NULL"); return SPECATTN_EINVAL; }
     if (!a->q || !a->k || !a->v || !a->out) { set_error("q, k, v and out must not be NULL"); return SPECATTN_EINVAL; }
-    if (!fused && (!a->indices || !a->counts)) { set_error("indices and counts must not be NULL"); return SPECATTN_EINVAL; }
+    const bool dense = !fused && !a->indices && !a->counts;     // no list: attend to every position
+    if (!fused && !dense && (!a->indices || !a->counts)) { set_error("indices and counts must both be given, or both be NULL (dense)"); return SPECATTN_EINVAL; }
+    if (dense && a->indices_are_physical) { set_error("indices_are_physical without an index list"); return SPECATTN_EINVAL; }
     if (a->B <= 0 || a->H_q <= 0 || a->H_kv <= 0 || a->T <= 0 || a->d <= 0 || a->n_max <= 0) { set_error("sizes must be positive"); return SPECATTN_EINVAL; }
     if (a->dtype != SPECATTN_F32 && a->dtype != SPECATTN_BF16) { set_error("unknown dtype %d", (int)a->dtype); return SPECATTN_EUNSUPPORTED; }
     if (a->H_q % a->H_kv) { set_error("H_q is not a multiple of H_kv"); return SPECATTN_ESHAPE; }
     if (a->T > SPECATTN_MAX_T) { set_error("T exceeds %d", SPECATTN_MAX_T); return SPECATTN_ESHAPE; }
     if (a->d != 64 && a->d != 128) { set_error("d must be 64 or 128"); return SPECATTN_ESHAPE; }
     if ((a->H_q / a->H_kv) * a->T > 64) { set_error("G*T exceeds 64 query rows per kv head"); return SPECATTN_ESHAPE; }
-    if (!fused && a->idx_capacity < 1) { set_error("idx_capacity must be at least 1"); return SPECATTN_ESHAPE; }
-    if (!fused && a->idx_stride_row < a->idx_capacity) { set_error("idx_stride_row is smaller than idx_capacity"); return SPECATTN_ESHAPE; }
+    if (!fused && !dense && a->idx_capacity < 1) { set_error("idx_capacity must be at least 1"); return SPECATTN_ESHAPE; }
+    if (!fused && !dense && a->idx_stride_row < a->idx_capacity) { set_error("idx_stride_row is smaller than idx_capacity"); return SPECATTN_ESHAPE; }
     const bool paged = a->page_table != nullptr || a->indices_are_physical;
     if (paged) {
         if (!is_pow2(a->page_size)) { set_error("page_size must be a power of two"); return SPECATTN_ESHAPE; }
@@ -151,6 +153,8 @@ AttnLaunch make_attn(const specattn_attn_args *a)
     l.counts = a->counts;
     l.idx_capacity = a->idx_capacity;
     l.indices_are_physical = a->indices_are_physical;
+    l.dense = (!a->indices && !a->counts) ? 1 : 0;          // the fused call overwrites counts afterwards
+    if (l.dense) l.idx_capacity = a->n_max;
     l.out = a->out;
     l.lse = a->lse;
     l.workspace = a->workspace;
@@ -229,6 +233,7 @@ specattn_status specattn_fused(const specattn_select_args *sel, const specattn_a
         if (st != SPECATTN_OK) return st;
     }
     al.indices = nullptr;
+    al.dense = 0;
     al.counts = sel->counts;
     al.idx_capacity = sel->n_max;
     al.idx_stride = 0;
@@ -249,7 +254,8 @@ size_t specattn_workspace_size(const specattn_select_args *sel, const specattn_a
     if (attn->B <= 0 || attn->H_kv <= 0 || attn->H_q <= 0 || attn->T <= 0 || attn->d <= 0) return 0;
     if (attn->H_q % attn->H_kv) return 0;
     const int rows = attn->B * attn->H_kv;
-    const int cap = sel ? attn->n_max : attn->idx_capacity;
+    const bool dense = !attn->indices && !attn->counts;
+    const int cap = (sel || dense) ? attn->n_max : attn->idx_capacity;
     if (cap <= 0) return 0;
     size_t bytes = attn_workspace_bytes(rows, attn->H_q / attn->H_kv, attn->T, attn->d, cap);
     if (sel) {                                        // fused: room for tau and the block counts

@@ -78,14 +78,13 @@ __global__ __launch_bounds__(GEN_THREADS) void attn_generic_kernel(AttnLaunch a,
     const int b = r / a.H_kv, h = r - b * a.H_kv;
     const int G = a.H_q / a.H_kv;
     const int tid = threadIdx.x;
-    int count = a.counts[r];
-    count = count < 0 ? 0 : (count > a.idx_capacity ? a.idx_capacity : count);
+    const int count = attn_row_count(a, r);
     const int tiles = (count + GEN_TILE - 1) / GEN_TILE;
     const int tiles_per_split = (tiles + n_splits - 1) / n_splits;
     const int j_begin = s * tiles_per_split * GEN_TILE;
     int j_end = j_begin + tiles_per_split * GEN_TILE;
     j_end = j_end > count ? count : j_end;
-    const int32_t *idx = a.indices + (int64_t)r * a.idx_stride;
+    const int32_t *idx = a.dense ? nullptr : a.indices + (int64_t)r * a.idx_stride;
     const KvMap map = make_map(a, b, h);
     const float scale = a.sm_scale;
 
@@ -108,7 +107,7 @@ __global__ __launch_bounds__(GEN_THREADS) void attn_generic_kernel(AttnLaunch a,
             const int p = e / D, dd = e - p * D;
             float kv = 0.0f, vv = 0.0f;
             if (p < np) {
-                const int64_t o = map.off(idx[j0 + p]) + dd;
+                const int64_t o = map.off(idx ? idx[j0 + p] : j0 + p) + dd;
                 kv = Elem<T>::ld(a.k, o);
                 vv = Elem<T>::ld(a.v, o);
             }

@@ -176,8 +176,6 @@ struct Plan {
 #define STAMP(k) do { } while (0)
 #endif
 
-__device__ __forceinline__ int clamp_count(int c, int cap) { return c < 0 ? 0 : (c > cap ? cap : c); }
-
 // Cost of a row on the line the workgroups share out: its tiles, plus SEG_COST for picking the row up
 // (fresh Q, pipeline refill, partial write) so that workgroups crossing a row boundary get fewer tiles.
 __device__ __forceinline__ int row_cost(int count) { return count > 0 ? (count + TILE - 1) / TILE + SEG_COST : 0; }
@@ -192,7 +190,7 @@ __device__ __forceinline__ void cost_prefix(const AttnLaunch &a, int rows, int *
     for (int k = 0; k < per; ++k) {
         const int r = r0 + k;
         if (r < rows) {
-            const int c = clamp_count(a.counts[r], a.idx_capacity);
+            const int c = attn_row_count(a, r);
             cnt[r] = c;
             local += row_cost(c);
         }
@@ -356,7 +354,7 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
             const int j = tid + k * THREADS;
             int jj = first + j;
             jj = jj < count ? jj : count - 1;
-            out[k] = j < n ? (uint32_t)(map.rel<LAYOUT>(idx[jj]) >> 3) : 0u;
+            out[k] = j < n ? (uint32_t)(map.rel<LAYOUT>(a.dense ? jj : idx[jj]) >> 3) : 0u;
         }
     };
     auto store_entries = [&](int n, const uint32_t (&in)[EPT]) {
@@ -479,7 +477,7 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
             for (int i = 0; i < 8; ++i) {
                 int jj = (lb + wave) * TILE + 4 * i + g;
                 jj = jj < count ? jj : count - 1;
-                e[i] = (uint32_t)(map.rel<LAYOUT>(idx[jj]) >> 3);
+                e[i] = (uint32_t)(map.rel<LAYOUT>(a.dense ? jj : idx[jj]) >> 3);
             }
             const char *kb0 = static_cast<const char *>(a.k) + map.base * 2;
             const char *vb0 = static_cast<const char *>(a.v) + map.base * 2;
@@ -883,7 +881,7 @@ specattn_status launch_attn_mfma(const AttnLaunch &a, hipStream_t stream)
         }
         if (a.page_table) c.page_table = a.page_table + (int64_t)b0 * a.max_pages;
         if (a.indices) c.indices = a.indices + r0 * a.idx_stride;
-        c.counts = a.counts + r0;
+        if (a.counts) c.counts = a.counts + r0;
         c.out = a.out + (int64_t)b0 * a.H_q * a.T * a.d;
         if (a.lse) c.lse = a.lse + (int64_t)b0 * a.H_q * a.T;
         if (a.seq_lens) c.seq_lens = a.seq_lens + b0;

@@ -63,6 +63,7 @@ struct AttnLaunch {
     const int32_t *counts;
     int idx_capacity;
     int indices_are_physical;
+    int dense;               // 1: no list; every position below the sequence length is attended to
     float *out;
     float *lse;              // may be null
     void *workspace;
@@ -75,6 +76,18 @@ struct AttnLaunch {
     const int32_t *block_counts;
     int blocks_per_row;
 };
+// Number of positions row r attends to: the kept count (clamped to the list capacity), or the
+// sequence length when there is no list.
+__device__ __forceinline__ int attn_row_count(const AttnLaunch &a, int r)
+{
+    if (a.dense) {
+        const int len = a.seq_lens ? a.seq_lens[r / a.H_kv] : a.n_max;
+        return len < 0 ? 0 : (len > a.n_max ? a.n_max : len);
+    }
+    const int c = a.counts[r];
+    return c < 0 ? 0 : (c > a.idx_capacity ? a.idx_capacity : c);
+}
+
 // number of splits per row the attention launch will use for this shape
 int attn_num_splits(int rows, int idx_capacity);
 size_t attn_workspace_bytes(int rows, int G, int T, int d, int idx_capacity);

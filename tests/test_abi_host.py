@@ -72,6 +72,9 @@ def test_select_argument_errors(kw, status):
     (dict(page_table=0x9000, page_size=10, max_pages_per_seq=1000, kv_stride_page=8 * 16 * 128), sa.ESHAPE),
     (dict(page_table=0x9000, page_size=16, max_pages_per_seq=1000, kv_stride_page=0), sa.ESHAPE),
     (dict(), sa.EWORKSPACE),                                      # valid arguments but no workspace
+    (dict(counts=None), sa.EINVAL),                               # a list without counts
+    (dict(indices=None, counts=None), sa.EWORKSPACE),             # dense call: valid, but no workspace
+    (dict(indices=None, counts=None, indices_are_physical=1, page_size=16, kv_stride_page=8 * 16 * 128), sa.EINVAL),
     (dict(workspace=0x10040, workspace_bytes=1 << 30), sa.EWORKSPACE),   # misaligned workspace
     (dict(workspace=0x10000, workspace_bytes=16), sa.EWORKSPACE),        # too small
 ])
