@@ -36,6 +36,11 @@ def _load():
                                                 C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
                                                 C.c_void_p, C.c_void_p, C.c_double,
                                                 C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
+        lib.oracle_masked_attention_tail.restype = C.c_int
+        lib.oracle_masked_attention_tail.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
+                                                     C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_double,
+                                                     C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
         _lib = lib
     return _lib
 
@@ -97,11 +102,14 @@ def nucleus_bisection(row: np.ndarray, p: float, iters: int):
 def masked_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, mask: np.ndarray,
                      *, bf16: bool = False, lens: Optional[np.ndarray] = None,
                      sm_scale: Optional[float] = None,
-                     which: Optional[Sequence[Sequence[int]]] = None):
+                     which: Optional[Sequence[Sequence[int]]] = None,
+                     k_new: Optional[np.ndarray] = None, v_new: Optional[np.ndarray] = None):
     """Masked dense attention in fp64.
 
     q [B,H_q,T,d], k/v [B,H_kv,n,d]: float32 arrays, or uint16 bf16 bit
     patterns when bf16=True.  mask [B,H_kv,n] (nonzero = selected).
+    k_new/v_new [B,H_kv,T,d] (optional): the new tokens' keys and values;
+    query t also attends to new tokens 0..t, whatever the mask says.
     which: optional list of (b, h_q, t) rows; default all, returned as
     out [B,H_q,T,d] / lse [B,H_q,T].  With `which`, out is [len(which), d].
     """
@@ -111,6 +119,11 @@ def masked_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, mask: np.ndarr
     B, H_q, T, d = q.shape
     _, H_kv, n, _ = k.shape
     assert k.shape == v.shape == (B, H_kv, n, d)
+    assert (k_new is None) == (v_new is None)
+    if k_new is not None:
+        k_new, v_new = np.ascontiguousarray(k_new), np.ascontiguousarray(v_new)
+        assert k_new.dtype == want and v_new.dtype == want
+        assert k_new.shape == v_new.shape == (B, H_kv, T, d)
     mask = np.ascontiguousarray(mask, dtype=np.uint8)
     assert mask.shape == (B, H_kv, n)
     lens = (np.full(B, n, dtype=np.int32) if lens is None
@@ -125,12 +138,14 @@ def masked_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, mask: np.ndarr
     rows = which_a.shape[0]
     out = np.zeros((rows, d), dtype=np.float64)
     lse = np.zeros(rows, dtype=np.float64)
-    rc = _load().oracle_masked_attention(q.ctypes.data, k.ctypes.data, v.ctypes.data, int(bf16),
-                                         B, H_q, H_kv, T, d, n, mask.ctypes.data,
-                                         lens.ctypes.data, scale, which_a.ctypes.data, rows,
-                                         out.ctypes.data, lse.ctypes.data)
+    rc = _load().oracle_masked_attention_tail(q.ctypes.data, k.ctypes.data, v.ctypes.data, int(bf16),
+                                              B, H_q, H_kv, T, d, n, mask.ctypes.data, lens.ctypes.data,
+                                              None if k_new is None else k_new.ctypes.data,
+                                              None if v_new is None else v_new.ctypes.data,
+                                              scale, which_a.ctypes.data, rows,
+                                              out.ctypes.data, lse.ctypes.data)
     if rc != 0:
-        raise ValueError(f"oracle_masked_attention failed with {rc}")
+        raise ValueError(f"oracle_masked_attention_tail failed with {rc}")
     if full:
         return out.reshape(B, H_q, T, d), lse.reshape(B, H_q, T)
     return out, lse

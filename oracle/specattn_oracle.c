@@ -16,6 +16,9 @@
  *   oracle_nucleus_bisection Algorithm 2 itself (value-space bisection), with
  *                            an iteration count instead of the epsilon test,
  *                            as the footnote in Section 3.4 describes.
+ *   oracle_masked_attention_tail  the same with the keys/values of the tokens being
+ *                            verified appended causally (Algorithm 1, verification
+ *                            step: gamma + 1 tokens go through the verifier at once).
  *   oracle_masked_attention  Section 3.1, Eq. 1-3: scores over ALL positions,
  *                            unselected ones masked out, softmax, times V.
  *                            The softmax is taken over the selected set (the
@@ -29,6 +32,10 @@
  *                            rows, invariants, Algorithm 2 run to convergence.
  *   oracle_nucleus_bisection feasibility / superset / bracket-width bounds
  *                            that follow from the algorithm's invariant.
+ *   oracle_masked_attention_tail  a library attention routine with an explicit
+ *                            per-query boolean mask over cache + new tokens; with an
+ *                            empty cache and one new token the output is that token's
+ *                            value row.
  *   oracle_masked_attention  a library attention routine (with and without a
  *                            boolean mask), one-hot selections, constant keys,
  *                            the log-sum-exp merge identity, Appendix A's
@@ -170,34 +177,42 @@ static inline double load_elem(const void *base, int64_t i, int is_bf16)
 }
 
 /*
- * Masked dense attention for a list of output rows.
+ * Masked dense attention for a list of output rows, optionally with the verifier's own new tokens.
  *
  * q      [B][H_q][T][d], k/v [B][H_kv][n][d]   (fp32, or bf16 bit patterns when is_bf16)
  * mask   [B][H_kv][n] uint8, 1 = position selected for that kv head
  * lens   [B] valid context length per sequence (positions >= lens[b] never attend)
+ * k_new, v_new  [B][H_kv][T][d] or NULL: keys and values of the T tokens being verified (Algorithm 1
+ *        feeds the gamma draft tokens and the last accepted one through the verifier together).  They
+ *        sit behind the cache, are never subject to the mask, and are seen causally: query t attends
+ *        to new tokens 0..t.
  * which  [n_rows][3] = (b, h_q, t) of each requested output row
  * out    [n_rows][d] fp64, lse [n_rows] fp64 (log-sum-exp of the kept scaled scores)
  * Query head h_q reads kv head h_q / (H_q / H_kv).
- * A row with no selected position gives out = 0 and lse = -inf.
+ * A row with no position to attend to gives out = 0 and lse = -inf.
  */
-int oracle_masked_attention(const void *q, const void *k, const void *v, int is_bf16,
-                            int B, int H_q, int H_kv, int T, int d, int n,
-                            const uint8_t *mask, const int32_t *lens, double sm_scale,
-                            const int32_t *which, int n_rows, double *out, double *lse)
+int oracle_masked_attention_tail(const void *q, const void *k, const void *v, int is_bf16,
+                                 int B, int H_q, int H_kv, int T, int d, int n,
+                                 const uint8_t *mask, const int32_t *lens,
+                                 const void *k_new, const void *v_new, double sm_scale,
+                                 const int32_t *which, int n_rows, double *out, double *lse)
 {
     if (H_q % H_kv) return -1;
+    if ((k_new == NULL) != (v_new == NULL)) return -2;
     const int G = H_q / H_kv;
     (void)B;
 #pragma omp parallel for schedule(dynamic, 1)
     for (int w = 0; w < n_rows; ++w) {
         const int b = which[3 * w], hq = which[3 * w + 1], t = which[3 * w + 2];
         const int hk = hq / G;
-        const int L = lens[b];
+        const int L = lens[b] > 0 ? lens[b] : 0;
+        const int n_tail = k_new ? t + 1 : 0;    /* causal among the new tokens */
         const int64_t qoff = (((int64_t)b * H_q + hq) * T + t) * d;
         const int64_t kvoff = ((int64_t)b * H_kv + hk) * (int64_t)n * d;
+        const int64_t newoff = ((int64_t)b * H_kv + hk) * (int64_t)T * d;
         const uint8_t *m = mask + ((int64_t)b * H_kv + hk) * (int64_t)n;
         double *o = out + (int64_t)w * d;
-        double *score = (double *)malloc(sizeof(double) * (size_t)(L > 0 ? L : 1));
+        double *score = (double *)malloc(sizeof(double) * (size_t)(L + n_tail + 1));
         double mx = -INFINITY;
         for (int j = 0; j < L; ++j) {            /* Eq. 1: Q K^T / sqrt(d), every position */
             double acc = 0.0;
@@ -206,18 +221,40 @@ int oracle_masked_attention(const void *q, const void *k, const void *v, int is_
             score[j] = m[j] ? acc * sm_scale : -INFINITY;   /* Eq. 3: unselected positions drop out */
             if (score[j] > mx) mx = score[j];
         }
+        for (int p = 0; p < n_tail; ++p) {       /* the new tokens, position L + p */
+            double acc = 0.0;
+            for (int e = 0; e < d; ++e)
+                acc += load_elem(q, qoff + e, is_bf16) * load_elem(k_new, newoff + (int64_t)p * d + e, is_bf16);
+            score[L + p] = acc * sm_scale;
+            if (score[L + p] > mx) mx = score[L + p];
+        }
         for (int e = 0; e < d; ++e) o[e] = 0.0;
         if (mx == -INFINITY) { lse[w] = -INFINITY; free(score); continue; }
         double denom = 0.0;
-        for (int j = 0; j < L; ++j) denom += exp(score[j] - mx);
+        for (int j = 0; j < L + n_tail; ++j) denom += exp(score[j] - mx);
         for (int j = 0; j < L; ++j) {            /* Eq. 2: weights times V */
             if (!m[j]) continue;
             const double wj = exp(score[j] - mx) / denom;
             for (int e = 0; e < d; ++e)
                 o[e] += wj * load_elem(v, kvoff + (int64_t)j * d + e, is_bf16);
         }
+        for (int p = 0; p < n_tail; ++p) {
+            const double wj = exp(score[L + p] - mx) / denom;
+            for (int e = 0; e < d; ++e)
+                o[e] += wj * load_elem(v_new, newoff + (int64_t)p * d + e, is_bf16);
+        }
         lse[w] = mx + log(denom);
         free(score);
     }
     return 0;
+}
+
+/* The cache alone (no new tokens). */
+int oracle_masked_attention(const void *q, const void *k, const void *v, int is_bf16,
+                            int B, int H_q, int H_kv, int T, int d, int n,
+                            const uint8_t *mask, const int32_t *lens, double sm_scale,
+                            const int32_t *which, int n_rows, double *out, double *lse)
+{
+    return oracle_masked_attention_tail(q, k, v, is_bf16, B, H_q, H_kv, T, d, n, mask, lens, NULL, NULL,
+                                        sm_scale, which, n_rows, out, lse);
 }

@@ -156,3 +156,72 @@ def test_custom_scale():
     o, _ = oracle.masked_attention(q, k, v, mask, sm_scale=0.5)
     o_ref = _sdpa(q * np.float32(0.5 * np.sqrt(q.shape[-1])), k, v, mask)
     np.testing.assert_allclose(o, o_ref, rtol=1e-6, atol=1e-8)
+
+
+# ---- the verifier's own new tokens behind the cache (causal tail) --------------------------------
+def _tail(seed, B, H_kv, T, d):
+    rng = np.random.default_rng(seed)
+    return (rng.standard_normal((B, H_kv, T, d), dtype=np.float32),
+            rng.standard_normal((B, H_kv, T, d), dtype=np.float32))
+
+
+def _sdpa_tail(q, k, v, mask, k_new, v_new, lens=None):
+    """Library route: one explicit boolean mask per query over [cache | new tokens]."""
+    B, H_q, T, d = q.shape
+    H_kv, n = k.shape[1], k.shape[2]
+    G = H_q // H_kv
+    tq = torch.from_numpy(q).double()
+    tk = torch.from_numpy(np.concatenate([k, k_new], axis=2)).double().repeat_interleave(G, dim=1)
+    tv = torch.from_numpy(np.concatenate([v, v_new], axis=2)).double().repeat_interleave(G, dim=1)
+    am = np.zeros((B, H_kv, T, n + T), dtype=bool)
+    for b in range(B):
+        L = n if lens is None else int(lens[b])
+        am[b, :, :, :L] = mask[b, :, None, :L].astype(bool)
+        for t in range(T):
+            am[b, :, t, n:n + t + 1] = True
+    am = torch.from_numpy(am).repeat_interleave(G, dim=1)
+    return torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, attn_mask=am).numpy()
+
+
+@pytest.mark.parametrize("shape", [dict(), dict(B=1, H_q=4, H_kv=4, T=5, d=64, n=130),
+                                   dict(B=3, H_q=6, H_kv=3, T=1, d=8, n=33)])
+def test_tail_equals_library_attention_with_per_query_mask(shape):
+    q, k, v, mask = _rand(11, **shape)
+    k_new, v_new = _tail(12, q.shape[0], k.shape[1], q.shape[2], q.shape[3])
+    o, _ = oracle.masked_attention(q, k, v, mask, k_new=k_new, v_new=v_new)
+    np.testing.assert_allclose(o, _sdpa_tail(q, k, v, mask, k_new, v_new), rtol=1e-10, atol=1e-12)
+
+
+def test_tail_with_sequence_lengths_and_row_subset():
+    q, k, v, mask = _rand(13, B=3, H_q=4, H_kv=2, T=4, d=16, n=50)
+    lens = np.array([50, 0, 17], dtype=np.int32)
+    k_new, v_new = _tail(14, 3, 2, 4, 16)
+    o, _ = oracle.masked_attention(q, k, v, mask, lens=lens, k_new=k_new, v_new=v_new)
+    np.testing.assert_allclose(o, _sdpa_tail(q, k, v, mask, k_new, v_new, lens), rtol=1e-10, atol=1e-12)
+    which = [(2, 3, 1), (0, 0, 3), (1, 2, 0)]
+    o_s, _ = oracle.masked_attention(q, k, v, mask, lens=lens, k_new=k_new, v_new=v_new, which=which)
+    for i, (b, h, t) in enumerate(which):
+        np.testing.assert_array_equal(o_s[i], o[b, h, t])
+
+
+def test_tail_alone_first_query_returns_first_new_value_row():
+    # empty cache: query 0 sees only new token 0, so its output is that token's value row and lse = its score
+    q, k, v, _ = _rand(15, B=1, H_q=4, H_kv=2, T=3, d=16, n=9)
+    k_new, v_new = _tail(16, 1, 2, 3, 16)
+    none = np.zeros(k.shape[:3], dtype=np.uint8)
+    o, lse = oracle.masked_attention(q, k, v, none, k_new=k_new, v_new=v_new)
+    for h in range(4):
+        np.testing.assert_allclose(o[0, h, 0], v_new[0, h // 2, 0], rtol=1e-12)
+        s = float(q[0, h, 0].astype(np.float64) @ k_new[0, h // 2, 0].astype(np.float64)) / 4.0
+        assert abs(lse[0, h, 0] - s) < 1e-12
+
+
+def test_tail_is_causal_later_new_tokens_do_not_matter():
+    q, k, v, mask = _rand(17, B=1, H_q=2, H_kv=1, T=4, d=8, n=20)
+    k_new, v_new = _tail(18, 1, 1, 4, 8)
+    o1, _ = oracle.masked_attention(q, k, v, mask, k_new=k_new, v_new=v_new)
+    k2, v2 = k_new.copy(), v_new.copy()
+    k2[:, :, 3], v2[:, :, 3] = 50.0, -9.0          # only query 3 may see new token 3
+    o2, _ = oracle.masked_attention(q, k, v, mask, k_new=k2, v_new=v2)
+    np.testing.assert_array_equal(o1[:, :, :3], o2[:, :, :3])
+    assert np.abs(o1[:, :, 3] - o2[:, :, 3]).max() > 1e-3
