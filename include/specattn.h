@@ -129,6 +129,12 @@ typedef struct specattn_attn_args {
     float *lse;                  /* [B][H_q][T] log-sum-exp of the kept scaled scores; optional */
     void *workspace;             /* split partials; 256-byte aligned */
     size_t workspace_bytes;
+
+    /* optional: keys and values of the T tokens being verified (Algorithm 1 feeds the gamma draft
+       tokens and the last accepted one through the verifier together).  [B][H_kv][T][d], contiguous,
+       same dtype as k/v, 16-byte aligned; both NULL = the cache alone.  They sit behind the cache, are
+       never subject to the selection, and are seen causally: query t also attends to new tokens 0..t. */
+    const void *k_new, *v_new;
 } specattn_attn_args;
 
 /* Selection alone.  `workspace` may be NULL when specattn_workspace_size(sel, NULL) is 0. */

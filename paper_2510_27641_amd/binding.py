@@ -51,6 +51,7 @@ class AttnArgs(C.Structure):
         ("idx_capacity", C.c_int32), ("indices_are_physical", C.c_int32),
         ("out", C.c_void_p), ("lse", C.c_void_p),
         ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
+        ("k_new", C.c_void_p), ("v_new", C.c_void_p),
     ]
 
 
@@ -150,8 +151,10 @@ def attn_args(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, *, out: torch.T
               lse: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
               n_max: Optional[int] = None, sm_scale: float = 0.0,
               page_table: Optional[torch.Tensor] = None, page_size: int = 0,
-              indices_are_physical: bool = False, seq_lens: Optional[torch.Tensor] = None) -> AttnArgs:
-    """q [B,H_q,T,d]; contiguous k/v [B,H_kv,n,d]; paged k/v pool [pages,H_kv,page_size,d]."""
+              indices_are_physical: bool = False, seq_lens: Optional[torch.Tensor] = None,
+              k_new: Optional[torch.Tensor] = None, v_new: Optional[torch.Tensor] = None) -> AttnArgs:
+    """q [B,H_q,T,d]; contiguous k/v [B,H_kv,n,d]; paged k/v pool [pages,H_kv,page_size,d];
+    k_new/v_new [B,H_kv,T,d] contiguous (the new tokens behind the cache), optional."""
     assert q.dim() == 4 and k.dim() == 4 and k.shape == v.shape and k.stride() == v.stride()
     assert q.dtype == k.dtype == v.dtype and q.dtype in (torch.float32, torch.bfloat16)
     assert q.stride(3) == 1 and k.stride(3) == 1
@@ -186,6 +189,11 @@ def attn_args(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, *, out: torch.T
     assert out.dtype == torch.float32 and out.is_contiguous() and tuple(out.shape) == (B, H_q, T, d)
     a.out = out.data_ptr()
     a.lse = None if lse is None else lse.data_ptr()
+    if k_new is not None:
+        assert v_new is not None and k_new.dtype == v_new.dtype == q.dtype
+        assert k_new.is_contiguous() and v_new.is_contiguous()
+        assert tuple(k_new.shape) == tuple(v_new.shape) == (B, a.H_kv, T, d)
+        a.k_new, a.v_new = k_new.data_ptr(), v_new.data_ptr()
     if workspace is not None:
         a.workspace, a.workspace_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
     return a

@@ -91,6 +91,8 @@ specattn_status check_attn(const specattn_attn_args *a, bool fused)
         if (a->page_table && (int64_t)a->max_pages_per_seq * a->page_size < a->n_max) { set_error("page table is shorter than n_max"); return SPECATTN_ESHAPE; }
         if (a->kv_stride_page <= 0) { set_error("kv_stride_page must be positive"); return SPECATTN_ESHAPE; }
     }
+    if ((a->k_new == nullptr) != (a->v_new == nullptr)) { set_error("k_new and v_new must both be given or both be NULL"); return SPECATTN_EINVAL; }
+    if (a->k_new && (!aligned(a->k_new, 16) || !aligned(a->v_new, 16))) { set_error("k_new and v_new must be 16-byte aligned"); return SPECATTN_EALIGN; }
     if (a->kv_stride_n < a->d) { set_error("kv_stride_n is smaller than d"); return SPECATTN_ESHAPE; }
     const size_t es = a->dtype == SPECATTN_BF16 ? 2 : 4;
     if (!aligned(a->q, 16) || !aligned(a->k, 16) || !aligned(a->v, 16) || !aligned(a->out, 16)) { set_error("q, k, v and out must be 16-byte aligned"); return SPECATTN_EALIGN; }
@@ -155,6 +157,8 @@ AttnLaunch make_attn(const specattn_attn_args *a)
     l.indices_are_physical = a->indices_are_physical;
     l.dense = (!a->indices && !a->counts) ? 1 : 0;          // the fused call overwrites counts afterwards
     if (l.dense) l.idx_capacity = a->n_max;
+    l.k_new = a->k_new;
+    l.v_new = a->v_new;
     l.out = a->out;
     l.lse = a->lse;
     l.workspace = a->workspace;
@@ -268,6 +272,6 @@ size_t specattn_workspace_size(const specattn_select_args *sel, const specattn_a
 
 const char *specattn_last_error(void) { return g_error; }
 
-int specattn_version(void) { return 1000; }
+int specattn_version(void) { return 1001; }
 
 }  // extern "C"

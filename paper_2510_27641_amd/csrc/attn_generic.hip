@@ -161,29 +161,47 @@ __global__ __launch_bounds__(GEN_THREADS) void attn_generic_kernel(AttnLaunch a,
     if (tid < QT) { pml[2 * tid] = m_run[tid]; pml[2 * tid + 1] = l_run[tid]; }
 }
 
-// One workgroup per (row, query row): combine the partials of all splits.
+// One workgroup per (row, query row): combine the partials of all splits, then the new tokens
+// behind the cache (query t sees new tokens 0..t), if the caller gave any.
 __global__ void merge_kernel(AttnLaunch a, int n_splits, const float *part_o, const float *part_ml)
 {
+    __shared__ float red[2 * SPECATTN_MAX_T];
     const int G = a.H_q / a.H_kv;
     const int QT = G * a.T;
     const int r = blockIdx.x / QT, qi = blockIdx.x - r * QT;
     const int b = r / a.H_kv, h = r - b * a.H_kv;
     const int g = qi / a.T, t = qi - g * a.T;
     const int D = a.d;
+    float dots[SPECATTN_MAX_T];
+    const int n_tail = a.k_new ? t + 1 : 0;
+    if (n_tail) tail_dots(a, b, h * G + g, t, red, dots);
     float m = -INFINITY;
     for (int s = 0; s < n_splits; ++s) m = fmaxf(m, part_ml[(((int64_t)r * n_splits + s) * QT + qi) * 2]);
+#pragma unroll
+    for (int p = 0; p < SPECATTN_MAX_T; ++p)
+        if (p < n_tail) m = fmaxf(m, dots[p] * a.sm_scale);
     float l = 0.0f;
     for (int s = 0; s < n_splits; ++s) {
         const float *p = part_ml + (((int64_t)r * n_splits + s) * QT + qi) * 2;
         if (p[0] != -INFINITY) l += __expf(p[0] - m) * p[1];
     }
+    float wt[SPECATTN_MAX_T];
+#pragma unroll
+    for (int p = 0; p < SPECATTN_MAX_T; ++p) {
+        wt[p] = p < n_tail ? __expf(dots[p] * a.sm_scale - m) : 0.0f;
+        l += wt[p];
+    }
     const int64_t orow = ((int64_t)b * a.H_q + (h * G + g)) * a.T + t;
+    const int64_t noff = ((int64_t)b * a.H_kv + h) * a.T * D;
     for (int dd = threadIdx.x; dd < D; dd += blockDim.x) {
         float o = 0.0f;
         for (int s = 0; s < n_splits; ++s) {
             const float ms = part_ml[(((int64_t)r * n_splits + s) * QT + qi) * 2];
             if (ms != -INFINITY) o += __expf(ms - m) * part_o[(((int64_t)r * n_splits + s) * QT + qi) * D + dd];
         }
+#pragma unroll
+        for (int p = 0; p < SPECATTN_MAX_T; ++p)
+            if (p < n_tail) o += wt[p] * ld_elem(a.v_new, noff + (int64_t)p * D + dd, a.dtype);
         a.out[orow * D + dd] = l > 0.0f ? o / l : 0.0f;
     }
     if (a.lse && threadIdx.x == 0) a.lse[orow] = l > 0.0f ? m + __logf(l) : -INFINITY;

@@ -719,7 +719,7 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
                 l += __shfl_xor(l, 32, 64);
                 const int q = qt * 16 + l16;
                 if (q < QT) {
-                    if (w0 == w1) {
+                    if (w0 == w1 && !a.k_new) {
                         const int gh = q / a.T, tt = q - gh * a.T;
                         const int64_t orow = ((int64_t)b * a.H_q + (h * G + gh)) * a.T + tt;
                         *reinterpret_cast<f32x4 *>(a.out + orow * D + 16 * t + 4 * g) =
@@ -740,9 +740,12 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
 }
 
 // After the main kernel, one workgroup per (row, query row): rows shared by several workgroups get
-// their partials (r, w) combined; rows without any kept position get out = 0, lse = -inf.
+// their partials (r, w) combined; rows without any kept position get out = 0, lse = -inf.  When the
+// caller gave the new tokens behind the cache, every row goes through here (the main kernel then
+// leaves partials only) and query t also attends to new tokens 0..t.
 __global__ void merge_partials_kernel(AttnLaunch a, Plan plan, int qtp)
 {
+    __shared__ float red[2 * SPECATTN_MAX_T];
     const int G = a.H_q / a.H_kv;
     const int QT = G * a.T;
     const int rows = a.B * a.H_kv;
@@ -751,29 +754,41 @@ __global__ void merge_partials_kernel(AttnLaunch a, Plan plan, int qtp)
     const int gh = q / a.T, t = q - gh * a.T;
     const int64_t orow = ((int64_t)b * a.H_q + (h * G + gh)) * a.T + t;
     const int dv = threadIdx.x;
+    const bool tail = a.k_new != nullptr;
     const int total = plan.cost_prefix[rows];
     const int p0 = plan.cost_prefix[r], p1 = plan.cost_prefix[r + 1];
-    if (p0 == p1) {
+    if (p0 == p1 && !tail) {
         a.out[orow * D + dv] = 0.0f;
         if (a.lse && dv == 0) a.lse[orow] = -INFINITY;
         return;
     }
-    const int share = (total + plan.n_wg - 1) / plan.n_wg;
-    const int w0 = (p0 + SEG_COST) / share, w1 = (p1 - 1) / share;
-    if (w0 == w1) return;                       // finished by its only workgroup
     Merge acc;
-    for (int wb = w0; wb <= w1; wb += 8) {      // eight partials per round trip
-        float mw[8], lw[8], ow[8];
+    if (p0 != p1) {
+        const int share = (total + plan.n_wg - 1) / plan.n_wg;
+        const int w0 = (p0 + SEG_COST) / share, w1 = (p1 - 1) / share;
+        if (w0 == w1 && !tail) return;              // finished by its only workgroup
+        for (int wb = w0; wb <= w1; wb += 8) {      // eight partials per round trip
+            float mw[8], lw[8], ow[8];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            const int64_t s = (int64_t)(wb + k + r) * qtp + q;
-            const bool ok = wb + k <= w1;
-            mw[k] = ok ? plan.part_ml[s * 2] : -INFINITY;
-            lw[k] = ok ? plan.part_ml[s * 2 + 1] : 0.0f;
-            ow[k] = ok ? plan.part_o[s * D + dv] : 0.0f;
+            for (int k = 0; k < 8; ++k) {
+                const int64_t s = (int64_t)(wb + k + r) * qtp + q;
+                const bool ok = wb + k <= w1;
+                mw[k] = ok ? plan.part_ml[s * 2] : -INFINITY;
+                lw[k] = ok ? plan.part_ml[s * 2 + 1] : 0.0f;
+                ow[k] = ok ? plan.part_o[s * D + dv] : 0.0f;
+            }
+#pragma unroll
+            for (int k = 0; k < 8; ++k) acc.add(mw[k], lw[k], ow[k]);
         }
+    }
+    if (tail) {
+        float dots[SPECATTN_MAX_T];
+        tail_dots(a, b, h * G + gh, t, red, dots);
+        const float scale2 = a.sm_scale * 1.4426950408889634f;       // m is in log2 units
+        const int64_t noff = ((int64_t)b * a.H_kv + h) * a.T * D;
 #pragma unroll
-        for (int k = 0; k < 8; ++k) acc.add(mw[k], lw[k], ow[k]);
+        for (int p = 0; p < SPECATTN_MAX_T; ++p)
+            if (p <= t) acc.add(dots[p] * scale2, 1.0f, ld_elem(a.v_new, noff + (int64_t)p * D + dv, a.dtype));
     }
     a.out[orow * D + dv] = acc.l > 0.0f ? acc.o / acc.l : 0.0f;
     // m is in log2 units of the scaled scores
@@ -885,6 +900,10 @@ specattn_status launch_attn_mfma(const AttnLaunch &a, hipStream_t stream)
         c.out = a.out + (int64_t)b0 * a.H_q * a.T * a.d;
         if (a.lse) c.lse = a.lse + (int64_t)b0 * a.H_q * a.T;
         if (a.seq_lens) c.seq_lens = a.seq_lens + b0;
+        if (a.k_new) {
+            c.k_new = static_cast<const char *>(a.k_new) + r0 * a.T * a.d * es;
+            c.v_new = static_cast<const char *>(a.v_new) + r0 * a.T * a.d * es;
+        }
         if (a.probs) {
             c.probs = a.probs + (int64_t)b0 * a.probs_stride_b;
             c.tau = a.tau + r0;

@@ -64,6 +64,7 @@ struct AttnLaunch {
     int idx_capacity;
     int indices_are_physical;
     int dense;               // 1: no list; every position below the sequence length is attended to
+    const void *k_new, *v_new;   // [B][H_kv][T][d] new tokens behind the cache, or null
     float *out;
     float *lse;              // may be null
     void *workspace;
@@ -86,6 +87,36 @@ __device__ __forceinline__ int attn_row_count(const AttnLaunch &a, int r)
     }
     const int c = a.counts[r];
     return c < 0 ? 0 : (c > a.idx_capacity ? a.idx_capacity : c);
+}
+
+__device__ __forceinline__ float ld_elem(const void *p, int64_t i, int dtype)
+{
+    if (dtype == SPECATTN_BF16) return __uint_as_float((uint32_t) static_cast<const uint16_t *>(p)[i] << 16);
+    return static_cast<const float *>(p)[i];
+}
+
+// Scores of query row (b, hq, t) against the keys of new tokens 0..t (unscaled dot products), computed
+// by all threads of a workgroup of blockDim.x = max(64, d) threads together; `red` is LDS scratch of
+// 2 * SPECATTN_MAX_T floats.  Every thread returns with all t + 1 values.  Contains a barrier.
+__device__ __forceinline__ void tail_dots(const AttnLaunch &a, int b, int hq, int t, float *red,
+                                          float (&dots)[SPECATTN_MAX_T])
+{
+    const int e = threadIdx.x, lane = e & 63, wave = e >> 6;
+    const int hk = hq / (a.H_q / a.H_kv);
+    const int64_t qoff = (int64_t)b * a.q_stride_b + (int64_t)hq * a.q_stride_h + (int64_t)t * a.q_stride_t;
+    const int64_t noff = ((int64_t)b * a.H_kv + hk) * a.T * a.d;
+    const float qe = e < a.d ? ld_elem(a.q, qoff + e, a.dtype) : 0.0f;
+#pragma unroll
+    for (int p = 0; p < SPECATTN_MAX_T; ++p) {
+        float x = (p <= t && e < a.d) ? qe * ld_elem(a.k_new, noff + (int64_t)p * a.d + e, a.dtype) : 0.0f;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off, 64);
+        if (lane == 0 && wave < 2) red[wave * SPECATTN_MAX_T + p] = x;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int p = 0; p < SPECATTN_MAX_T; ++p)
+        dots[p] = red[p] + (blockDim.x > 64 ? red[SPECATTN_MAX_T + p] : 0.0f);
 }
 
 // number of splits per row the attention launch will use for this shape

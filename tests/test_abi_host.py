@@ -73,6 +73,8 @@ def test_select_argument_errors(kw, status):
     (dict(page_table=0x9000, page_size=16, max_pages_per_seq=1000, kv_stride_page=0), sa.ESHAPE),
     (dict(), sa.EWORKSPACE),                                      # valid arguments but no workspace
     (dict(counts=None), sa.EINVAL),                               # a list without counts
+    (dict(k_new=0x7000), sa.EINVAL),                              # new keys without new values
+    (dict(k_new=0x7000, v_new=0x8004), sa.EALIGN),
     (dict(indices=None, counts=None), sa.EWORKSPACE),             # dense call: valid, but no workspace
     (dict(indices=None, counts=None, indices_are_physical=1, page_size=16, kv_stride_page=8 * 16 * 128), sa.EINVAL),
     (dict(workspace=0x10040, workspace_bytes=1 << 30), sa.EWORKSPACE),   # misaligned workspace
