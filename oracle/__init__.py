@@ -7,8 +7,10 @@ from .oracle import (  # noqa: F401
     ROW_INVALID,
     ROW_NEAR_BOUNDARY,
     SelectResult,
+    UnionResult,
     masked_attention,
     nucleus_bisection,
     set_threads,
     topp_select,
+    topp_select_union,
 )

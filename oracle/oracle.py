@@ -90,6 +90,62 @@ def topp_select(probs: np.ndarray, top_p: float, lens: Optional[np.ndarray] = No
     return SelectResult(idx, counts, tau, flags, diag)
 
 
+@dataclass
+class UnionResult:
+    indices: np.ndarray     # [B*H_kv, n] int32; row r valid on [:counts[r]], ascending
+    counts: np.ndarray      # [B*H_kv] int32
+    flags: np.ndarray       # [B*H_kv] uint32: INVALID if every member row is invalid, NEAR_BOUNDARY if any valid one is
+    members: SelectResult   # the per-(b, draft head, step) selections the union was taken over
+
+    def row_set(self, r: int) -> np.ndarray:
+        return self.indices[r, : self.counts[r]]
+
+    def mask(self) -> np.ndarray:
+        m = np.zeros(self.indices.shape, dtype=np.uint8)
+        for r in range(m.shape[0]):
+            m[r, self.row_set(r)] = 1
+        return m
+
+
+def topp_select_union(probs: np.ndarray, top_p: float, H_kv: int,
+                      lens: Optional[np.ndarray] = None) -> UnionResult:
+    """Algorithm 2 as a whole: top-p selection of every draft step's row, then the union of the sets.
+
+    probs [B, H_draft, S, n] float32: the draft attention row of every (sequence, draft head,
+    speculative step).  Draft heads h*H_draft/H_kv .. (h+1)*H_draft/H_kv - 1 feed kv head h, and the
+    union runs over their rows as well as over the S steps.  lens [B]: common valid length.
+    """
+    probs = np.ascontiguousarray(probs, dtype=np.float32)
+    assert probs.ndim == 4
+    B, H_d, S, n = probs.shape
+    assert H_d % H_kv == 0
+    per = H_d // H_kv
+    lens = np.full(B, n, dtype=np.int32) if lens is None else np.ascontiguousarray(lens, dtype=np.int32)
+    members = topp_select(probs.reshape(B * H_d * S, n), top_p, lens=np.repeat(lens, H_d * S))
+    R = B * H_kv
+    idx = np.full((R, max(n, 1)), -1, dtype=np.int32)
+    counts = np.zeros(R, dtype=np.int32)
+    flags = np.zeros(R, dtype=np.uint32)
+    for b in range(B):
+        for h in range(H_kv):
+            r = b * H_kv + h
+            kept = set()
+            all_invalid, any_near = True, False
+            for hd in range(h * per, (h + 1) * per):
+                for s in range(S):
+                    m = (b * H_d + hd) * S + s
+                    if members.flags[m] & ROW_INVALID:
+                        continue
+                    all_invalid = False
+                    any_near = any_near or bool(members.flags[m] & ROW_NEAR_BOUNDARY)
+                    kept.update(int(j) for j in members.row_set(m))     # T <- T u T_s
+            out = sorted(kept)
+            counts[r] = len(out)
+            idx[r, : len(out)] = out
+            flags[r] = (ROW_INVALID if all_invalid else 0) | (ROW_NEAR_BOUNDARY if any_near else 0)
+    return UnionResult(idx, counts, flags, members)
+
+
 def nucleus_bisection(row: np.ndarray, p: float, iters: int):
     """Algorithm 2's bisection on one row; returns (theta_low, theta_high, theta_mid)."""
     row = np.ascontiguousarray(row, dtype=np.float32)
