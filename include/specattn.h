@@ -137,6 +137,41 @@ typedef struct specattn_attn_args {
     const void *k_new, *v_new;
 } specattn_attn_args;
 
+/*
+ * Algorithm 2 as a whole (Section 3.4): top-p selection of the draft attention row of every
+ * speculative step, then the union of the kept sets.  Every draft head that feeds a kv head
+ * (draft heads h*H_draft/H_kv .. (h+1)*H_draft/H_kv - 1 feed kv head h) adds its rows to the same
+ * union, so one ascending list per (sequence, kv head) comes out, ready for
+ * specattn_sparse_decode_attn.  Each member row is cut at its own exact tau* (same rules as
+ * specattn_topp_select); member rows that are invalid contribute nothing.
+ */
+typedef struct specattn_union_args {
+    const float *probs;          /* [B][H_draft][S][n_max] fp32: row (b, h, s) starts at
+                                    b*probs_stride_b + (h*S + s)*probs_stride_row */
+    int64_t probs_stride_b;      /* elements */
+    int64_t probs_stride_row;    /* elements between consecutive (head, step) rows, >= n_max */
+    int32_t B, H_draft, S, H_kv, n_max;   /* S = gamma draft steps; H_draft % H_kv == 0 */
+    const int32_t *seq_lens;     /* [B] common valid length, or NULL for n_max */
+    float top_p;                 /* p in (0, 1] */
+
+    int32_t *indices;            /* out [B*H_kv][idx_stride_row] ascending positions of the union */
+    int64_t idx_stride_row;
+    int32_t idx_capacity;
+    int32_t *counts;             /* out [B*H_kv] TRUE size of the union, even when > idx_capacity */
+    uint32_t *row_flags;         /* out, optional: INVALID if every member row is invalid (count 0),
+                                    NEAR_BOUNDARY if any valid member row is, OVERFLOW as for the selection */
+    float *member_thresholds;    /* out, optional: [B*H_draft*S] tau* of every member row */
+    int32_t *member_counts;      /* out, optional: [B*H_draft*S] kept count of every member row */
+
+    const int32_t *page_table;   /* optional paged output, as in specattn_select_args */
+    int32_t page_size, max_pages_per_seq, emit_physical;
+} specattn_union_args;
+
+/* workspace: specattn_union_workspace_size(args) bytes, 256-byte aligned. */
+specattn_status specattn_topp_select_union(const specattn_union_args *args, void *workspace,
+                                           size_t workspace_bytes, void *stream);
+size_t specattn_union_workspace_size(const specattn_union_args *args);
+
 /* Selection alone.  `workspace` may be NULL when specattn_workspace_size(sel, NULL) is 0. */
 specattn_status specattn_topp_select(const specattn_select_args *sel, void *workspace,
                                      size_t workspace_bytes, void *stream);

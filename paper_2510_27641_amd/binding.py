@@ -20,7 +20,7 @@ ROW_INVALID, ROW_NEAR_BOUNDARY, ROW_OVERFLOW = 1, 2, 4
 SEL_BLOCK = 1024
 F32, BF16 = 0, 1
 
-EXPORTS = ("specattn_topp_select", "specattn_sparse_decode_attn", "specattn_fused",
+EXPORTS = ("specattn_topp_select", "specattn_topp_select_union", "specattn_union_workspace_size", "specattn_sparse_decode_attn", "specattn_fused",
            "specattn_workspace_size", "specattn_stream_read", "specattn_last_error", "specattn_version")
 
 
@@ -55,6 +55,19 @@ class AttnArgs(C.Structure):
     ]
 
 
+class UnionArgs(C.Structure):
+    _fields_ = [
+        ("probs", C.c_void_p), ("probs_stride_b", C.c_int64), ("probs_stride_row", C.c_int64),
+        ("B", C.c_int32), ("H_draft", C.c_int32), ("S", C.c_int32), ("H_kv", C.c_int32), ("n_max", C.c_int32),
+        ("seq_lens", C.c_void_p), ("top_p", C.c_float),
+        ("indices", C.c_void_p), ("idx_stride_row", C.c_int64), ("idx_capacity", C.c_int32),
+        ("counts", C.c_void_p), ("row_flags", C.c_void_p),
+        ("member_thresholds", C.c_void_p), ("member_counts", C.c_void_p),
+        ("page_table", C.c_void_p), ("page_size", C.c_int32), ("max_pages_per_seq", C.c_int32),
+        ("emit_physical", C.c_int32),
+    ]
+
+
 class SpecAttnError(RuntimeError):
     def __init__(self, status: int, text: str):
         super().__init__(f"specattn status {status}: {text}")
@@ -74,6 +87,10 @@ def load() -> C.CDLL:
         lib = C.CDLL(LIB_PATH)
         lib.specattn_topp_select.restype = C.c_int
         lib.specattn_topp_select.argtypes = [C.POINTER(SelectArgs), C.c_void_p, C.c_size_t, C.c_void_p]
+        lib.specattn_topp_select_union.restype = C.c_int
+        lib.specattn_topp_select_union.argtypes = [C.POINTER(UnionArgs), C.c_void_p, C.c_size_t, C.c_void_p]
+        lib.specattn_union_workspace_size.restype = C.c_size_t
+        lib.specattn_union_workspace_size.argtypes = [C.POINTER(UnionArgs)]
         lib.specattn_sparse_decode_attn.restype = C.c_int
         lib.specattn_sparse_decode_attn.argtypes = [C.POINTER(AttnArgs), C.c_void_p]
         lib.specattn_fused.restype = C.c_int
@@ -146,6 +163,36 @@ def select_args(probs: torch.Tensor, top_p: float, *, indices: Optional[torch.Te
     return a
 
 
+def union_args(probs: torch.Tensor, top_p: float, H_kv: int, *, indices: torch.Tensor, counts: torch.Tensor,
+               row_flags: Optional[torch.Tensor] = None, seq_lens: Optional[torch.Tensor] = None,
+               member_thresholds: Optional[torch.Tensor] = None, member_counts: Optional[torch.Tensor] = None,
+               page_table: Optional[torch.Tensor] = None, page_size: int = 0,
+               emit_physical: bool = False) -> UnionArgs:
+    """probs [B,H_draft,S,n] fp32 with the (head, step) rows evenly spaced; indices [B*H_kv, cap] int32."""
+    assert probs.dtype == torch.float32 and probs.dim() == 4 and probs.stride(3) == 1
+    B, H_d, S, n = probs.shape
+    assert probs.stride(1) == S * probs.stride(2), "rows (head, step) must be evenly spaced"
+    a = UnionArgs()
+    a.probs = probs.data_ptr()
+    a.probs_stride_b, a.probs_stride_row = probs.stride(0), probs.stride(2)
+    a.B, a.H_draft, a.S, a.H_kv, a.n_max = B, H_d, S, H_kv, n
+    a.seq_lens = None if seq_lens is None else seq_lens.data_ptr()
+    a.top_p = top_p
+    assert indices.dtype == torch.int32 and indices.dim() == 2 and indices.stride(1) == 1
+    a.indices = indices.data_ptr()
+    a.idx_stride_row, a.idx_capacity = indices.stride(0), indices.shape[1]
+    a.counts = counts.data_ptr()
+    a.row_flags = None if row_flags is None else row_flags.data_ptr()
+    a.member_thresholds = None if member_thresholds is None else member_thresholds.data_ptr()
+    a.member_counts = None if member_counts is None else member_counts.data_ptr()
+    if page_table is not None:
+        assert page_table.dtype == torch.int32 and page_table.is_contiguous()
+        a.page_table = page_table.data_ptr()
+        a.page_size, a.max_pages_per_seq = page_size, page_table.shape[1]
+    a.emit_physical = int(emit_physical)
+    return a
+
+
 def attn_args(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, *, out: torch.Tensor,
               indices: Optional[torch.Tensor] = None, counts: Optional[torch.Tensor] = None,
               lse: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
@@ -210,6 +257,15 @@ def specattn_workspace_size(sel: Optional[SelectArgs], attn: Optional[AttnArgs])
 def specattn_topp_select(sel: SelectArgs, workspace: Optional[torch.Tensor] = None, stream=None) -> None:
     nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(load().specattn_topp_select(C.byref(sel), _ptr(workspace), nbytes, _stream(stream)))
+
+
+def specattn_union_workspace_size(args: UnionArgs) -> int:
+    return int(load().specattn_union_workspace_size(C.byref(args)))
+
+
+def specattn_topp_select_union(args: UnionArgs, workspace: torch.Tensor, stream=None) -> None:
+    nbytes = workspace.numel() * workspace.element_size()
+    _check(load().specattn_topp_select_union(C.byref(args), _ptr(workspace), nbytes, _stream(stream)))
 
 
 def specattn_sparse_decode_attn(attn: AttnArgs, stream=None) -> None:

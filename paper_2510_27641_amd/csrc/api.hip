@@ -185,6 +185,43 @@ specattn_status specattn_topp_select(const specattn_select_args *sel, void *work
     return launch_select(make_select(sel), static_cast<hipStream_t>(stream));
 }
 
+static specattn_status check_union(const specattn_union_args *u)
+{
+    if (!u) { set_error("union args are NULL"); return SPECATTN_EINVAL; }
+    if (!u->probs || !u->counts || !u->indices) { set_error("probs, indices and counts must not be NULL"); return SPECATTN_EINVAL; }
+    if (!(u->top_p > 0.0f && u->top_p <= 1.0f)) { set_error("top_p must be in (0, 1]"); return SPECATTN_EINVAL; }
+    if (u->B <= 0 || u->H_draft <= 0 || u->S <= 0 || u->H_kv <= 0 || u->n_max <= 0) { set_error("sizes must be positive"); return SPECATTN_EINVAL; }
+    if (u->H_draft % u->H_kv) { set_error("H_draft is not a multiple of H_kv"); return SPECATTN_ESHAPE; }
+    if (u->n_max > SPECATTN_MAX_N) { set_error("n_max exceeds %d", SPECATTN_MAX_N); return SPECATTN_ESHAPE; }
+    if ((int64_t)u->B * u->H_draft * u->S > (1 << 24)) { set_error("too many rows"); return SPECATTN_ESHAPE; }
+    if (u->probs_stride_row < u->n_max) { set_error("probs_stride_row is smaller than n_max"); return SPECATTN_ESHAPE; }
+    if (u->idx_capacity < 1) { set_error("idx_capacity must be at least 1"); return SPECATTN_ESHAPE; }
+    if (u->idx_stride_row < u->idx_capacity) { set_error("idx_stride_row is smaller than idx_capacity"); return SPECATTN_ESHAPE; }
+    if (u->emit_physical && !u->page_table) { set_error("emit_physical needs a page table"); return SPECATTN_EINVAL; }
+    if (u->page_table) {
+        if (!is_pow2(u->page_size)) { set_error("page_size must be a power of two"); return SPECATTN_ESHAPE; }
+        if ((int64_t)u->max_pages_per_seq * u->page_size < u->n_max) { set_error("page table is shorter than n_max"); return SPECATTN_ESHAPE; }
+    }
+    return SPECATTN_OK;
+}
+
+size_t specattn_union_workspace_size(const specattn_union_args *u)
+{
+    if (!u || u->B <= 0 || u->H_draft <= 0 || u->S <= 0 || u->H_kv <= 0 || u->n_max <= 0 || u->H_draft % u->H_kv) return 0;
+    return union_workspace_bytes(u->B, u->H_kv, (u->H_draft / u->H_kv) * u->S, u->n_max);
+}
+
+specattn_status specattn_topp_select_union(const specattn_union_args *u, void *workspace, size_t workspace_bytes,
+                                           void *stream)
+{
+    clear_error();
+    specattn_status st = check_union(u);
+    if (st != SPECATTN_OK) return st;
+    st = check_workspace(workspace, workspace_bytes, specattn_union_workspace_size(u));
+    if (st != SPECATTN_OK) return st;
+    return launch_union(u, workspace, static_cast<hipStream_t>(stream));
+}
+
 specattn_status specattn_sparse_decode_attn(const specattn_attn_args *attn, void *stream)
 {
     clear_error();
@@ -272,6 +309,6 @@ size_t specattn_workspace_size(const specattn_select_args *sel, const specattn_a
 
 const char *specattn_last_error(void) { return g_error; }
 
-int specattn_version(void) { return 1001; }
+int specattn_version(void) { return 1002; }
 
 }  // extern "C"

@@ -47,6 +47,10 @@ struct SelectLaunch {
 };
 specattn_status launch_select(const SelectLaunch &a, hipStream_t stream);
 
+// union of the per-step selections (Algorithm 2 as a whole)
+size_t union_workspace_bytes(int B, int H_kv, int M, int n_max);
+specattn_status launch_union(const specattn_union_args *u, void *workspace, hipStream_t stream);
+
 // ---- attention -----------------------------------------------------------------------------
 struct AttnLaunch {
     const void *q, *k, *v;

@@ -93,6 +93,55 @@ def draft_probs(
     return out
 
 
+def draft_step_probs(
+    rng: np.random.Generator,
+    B: int,
+    H_draft: int,
+    S: int,
+    n: int,
+    *,
+    lens: Optional[np.ndarray] = None,
+    step_sigma: float = 0.7,
+    **kw,
+) -> np.ndarray:
+    """[B, H_draft, S, n] float32: the draft attention rows of S consecutive speculative steps.
+
+    The S rows of one (sequence, head) share their logits (drawn as in draft_probs) up to an
+    independent N(0, step_sigma^2) perturbation per step and position, so consecutive steps attend
+    to mostly, but not exactly, the same positions.  Positions >= lens[b] hold exactly 0 (the
+    draft's attention to its own speculative tokens is not part of the verifier's cache, so a
+    row's mass over the cache may be below 1).
+    """
+    sigma = kw.pop("sigma", 2.0)
+    sink = kw.pop("sink", 6.0)
+    recency_boost = kw.pop("recency_boost", 3.0)
+    recency_len = kw.pop("recency_len", 64)
+    spike_frac = kw.pop("spike_frac", 0.01)
+    spike_max = kw.pop("spike_max", 4.0)
+    spike_zipf = kw.pop("spike_zipf", 1.1)
+    assert not kw, f"unknown arguments {sorted(kw)}"
+    out = np.zeros((B, H_draft, S, n), dtype=np.float32)
+    for b in range(B):
+        ln = int(n if lens is None else lens[b])
+        if ln == 0:
+            continue
+        for h in range(H_draft):
+            base = sigma * rng.standard_normal(ln)
+            base[0] += sink
+            base[max(0, ln - recency_len):ln] += recency_boost
+            k = int(round(spike_frac * ln))
+            if k > 0 and spike_max > 0.0:
+                pos = rng.choice(ln, size=k, replace=False)
+                base[pos] += spike_max * np.arange(1, k + 1, dtype=np.float64) ** (-spike_zipf)
+            for s_ in range(S):
+                logit = base + step_sigma * rng.standard_normal(ln)
+                logit -= logit.max()
+                e = np.exp(logit)
+                # the step's own s_ speculative tokens take a little of the mass (not part of the cache)
+                out[b, h, s_, :ln] = (e / (e.sum() * (1.0 + 0.02 * s_))).astype(np.float32)
+    return out
+
+
 # --------------------------------------------------------------------------
 # workload container
 # --------------------------------------------------------------------------

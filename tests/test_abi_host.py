@@ -103,3 +103,37 @@ def test_stream_read_rejects_bad_arguments():
     assert lib.specattn_stream_read(0x1008, 1024, None, None) == sa.EALIGN
     assert lib.specattn_stream_read(0x1000, 1000, None, None) == sa.EALIGN
     assert "16" in sa.last_error()
+
+
+def _union(**kw):
+    a = sa.UnionArgs()
+    a.probs, a.counts, a.indices = 0x1000, 0x2000, 0x3000
+    a.B, a.H_draft, a.S, a.H_kv, a.n_max = 2, 8, 4, 4, 1024
+    a.probs_stride_b, a.probs_stride_row = 8 * 4 * 1024, 1024
+    a.top_p = 0.9
+    a.idx_stride_row, a.idx_capacity = 1024, 1024
+    for k, v in kw.items():
+        setattr(a, k, v)
+    return a
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(probs=None), sa.EINVAL), (dict(indices=None), sa.EINVAL), (dict(counts=None), sa.EINVAL),
+    (dict(top_p=0.0), sa.EINVAL), (dict(top_p=float("nan")), sa.EINVAL), (dict(S=0), sa.EINVAL),
+    (dict(H_kv=3), sa.ESHAPE), (dict(n_max=(1 << 19) + 1, probs_stride_row=1 << 20), sa.ESHAPE),
+    (dict(probs_stride_row=1000), sa.ESHAPE), (dict(idx_capacity=0), sa.ESHAPE),
+    (dict(emit_physical=1), sa.EINVAL), (dict(page_table=0x9000, page_size=12, max_pages_per_seq=100), sa.ESHAPE),
+    (dict(), sa.EWORKSPACE),
+])
+def test_union_argument_errors(kw, status):
+    lib = sa.load()
+    a = _union(**kw)
+    assert lib.specattn_topp_select_union(C.byref(a), None, 0, None) == status
+    assert sa.last_error() != ""
+
+
+def test_union_workspace_size():
+    small = sa.specattn_union_workspace_size(_union())
+    assert small > 0 and small % 256 == 0
+    assert sa.specattn_union_workspace_size(_union(S=8)) > small
+    assert sa.specattn_union_workspace_size(_union(H_kv=3)) == 0
