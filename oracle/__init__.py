@@ -8,9 +8,12 @@ from .oracle import (  # noqa: F401
     ROW_NEAR_BOUNDARY,
     SelectResult,
     UnionResult,
+    chunk_masses,
+    chunk_token_mask,
     masked_attention,
     nucleus_bisection,
     set_threads,
     topp_select,
+    topp_select_chunks,
     topp_select_union,
 )

@@ -41,6 +41,8 @@ def _load():
                                                      C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
                                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_double,
                                                      C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
+        lib.oracle_chunk_masses.restype = C.c_int
+        lib.oracle_chunk_masses.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_void_p]
         _lib = lib
     return _lib
 
@@ -88,6 +90,41 @@ def topp_select(probs: np.ndarray, top_p: float, lens: Optional[np.ndarray] = No
     if rc != 0:
         raise ValueError(f"oracle_topp_select failed with {rc} (top_p must be in (0, 1])")
     return SelectResult(idx, counts, tau, flags, diag)
+
+
+def chunk_masses(probs: np.ndarray, chunk: int, lens: Optional[np.ndarray] = None) -> np.ndarray:
+    """probs [rows, n] float32 -> [rows, ceil(n / chunk)] float32 chunk masses (fp64 sums, rounded once)."""
+    probs = np.ascontiguousarray(probs, dtype=np.float32)
+    rows, n = probs.shape
+    lens = np.full(rows, n, dtype=np.int32) if lens is None else np.ascontiguousarray(lens, dtype=np.int32)
+    nc = (n + chunk - 1) // chunk
+    mass = np.zeros((rows, nc), dtype=np.float32)
+    rc = _load().oracle_chunk_masses(probs.ctypes.data, n, rows, lens.ctypes.data, int(chunk), nc, mass.ctypes.data)
+    if rc != 0:
+        raise ValueError(f"oracle_chunk_masses failed with {rc}")
+    return mass
+
+
+def topp_select_chunks(probs: np.ndarray, top_p: float, chunk: int,
+                       lens: Optional[np.ndarray] = None) -> SelectResult:
+    """Chunk-granular selection: exact top-p over the row of chunk masses.  The result's indices are
+    chunk numbers; chunk c stands for positions [c*chunk, min((c+1)*chunk, len))."""
+    probs = np.ascontiguousarray(probs, dtype=np.float32)
+    rows, n = probs.shape
+    lens = np.full(rows, n, dtype=np.int32) if lens is None else np.ascontiguousarray(lens, dtype=np.int32)
+    mass = chunk_masses(probs, chunk, lens)
+    return topp_select(mass, top_p, lens=(lens + chunk - 1) // chunk)
+
+
+def chunk_token_mask(res: SelectResult, chunk: int, n: int, lens: Optional[np.ndarray] = None) -> np.ndarray:
+    """[rows, n] uint8: the positions the kept chunks stand for."""
+    rows = res.counts.shape[0]
+    lens = np.full(rows, n, dtype=np.int32) if lens is None else lens
+    m = np.zeros((rows, n), dtype=np.uint8)
+    for r in range(rows):
+        for c in res.row_set(r):
+            m[r, c * chunk: min((c + 1) * chunk, int(lens[r]))] = 1
+    return m
 
 
 @dataclass

@@ -13,6 +13,10 @@
  *                            sort the row, fp64 running sum, first prefix
  *                            that reaches p * (row sum), keep every value
  *                            that is >= the value found there.
+ *   oracle_chunk_masses      the per-chunk attention mass that chunk-granular selection
+ *                            (Section 4: chunks of 16 tokens) ranks instead of single
+ *                            positions; the selection itself is oracle_topp_select on
+ *                            the row of chunk masses.
  *   oracle_nucleus_bisection Algorithm 2 itself (value-space bisection), with
  *                            an iteration count instead of the epsilon test,
  *                            as the footnote in Section 3.4 describes.
@@ -30,6 +34,8 @@
  *   oracle_topp_select       brute force over all subsets, closed forms for
  *                            geometric and two-level rows, hand-worked tie
  *                            rows, invariants, Algorithm 2 run to convergence.
+ *   oracle_chunk_masses      hand-worked rows, exact rational sums, chunk = 1 is the
+ *                            identity, the masses add up to the row sum.
  *   oracle_nucleus_bisection feasibility / superset / bracket-width bounds
  *                            that follow from the algorithm's invariant.
  *   oracle_masked_attention_tail  a library attention routine with an explicit
@@ -164,6 +170,35 @@ int oracle_nucleus_bisection(const float *a, int L, double p, int iters,
         if (m < target) hi = mid; else lo = mid;
     }
     *theta_low = lo; *theta_high = hi; *theta_mid = mid;
+    return 0;
+}
+
+/*
+ * Chunk masses for chunk-granular selection (Section 4 evaluates with chunks of 16 tokens; the paper
+ * does not say how a chunk is scored - the reading here is the chunk's attention mass, which keeps
+ * the top-p guarantee: the kept chunks hold at least p of the row's mass).
+ *
+ * mass[r][c] = fp32( sum of probs[r][c*chunk .. min((c+1)*chunk, lens[r])) ), the sum taken in fp64 in
+ * ascending position order.  A chunk that holds a NaN, negative or infinite entry gets mass NaN, which
+ * makes the row invalid for the selection that follows.  Chunks past the row's end get mass 0.
+ */
+int oracle_chunk_masses(const float *probs, int64_t row_stride, int rows, const int32_t *lens,
+                        int chunk, int n_chunks, float *mass)
+{
+    if (chunk <= 0) return -1;
+    for (int r = 0; r < rows; ++r) {
+        const float *a = probs + (int64_t)r * row_stride;
+        const int L = lens[r] > 0 ? lens[r] : 0;
+        for (int c = 0; c < n_chunks; ++c) {
+            double sum = 0.0;
+            int bad = 0;
+            for (int j = c * chunk; j < (c + 1) * chunk && j < L; ++j) {
+                if (isnan(a[j]) || isinf(a[j]) || a[j] < 0.0f) bad = 1;
+                sum += (double)a[j];
+            }
+            mass[(int64_t)r * n_chunks + c] = bad ? NAN : (float)sum;
+        }
+    }
     return 0;
 }
 
