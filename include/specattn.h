@@ -86,6 +86,15 @@ typedef struct specattn_select_args {
     int32_t reuse_selection;     /* specattn_fused only: 1 = thresholds, counts and block_counts already hold the
                                     result of an earlier specattn_topp_select / specattn_fused call on these rows
                                     (e.g. one batched call for all layers); the threshold phase is skipped */
+
+    /* Chunk-granular selection (Section 4 evaluates with chunks of 16 tokens).  chunk_size 0 or 1: single
+       positions.  A power of two >= 2: the row is first reduced to chunk masses - the sum of the chunk's
+       entries, taken in fp64 in ascending position order and rounded once to fp32 - and the exact top-p
+       selection runs over those; `indices` then holds ascending chunk numbers (chunk c stands for positions
+       [c*chunk_size, min((c+1)*chunk_size, len))), idx_capacity and counts are in chunks, thresholds are
+       chunk masses.  Needs workspace (specattn_workspace_size(sel, NULL)); not available together with
+       emit_physical, block_counts or specattn_fused (SPECATTN_EUNSUPPORTED). */
+    int32_t chunk_size;
 } specattn_select_args;
 
 /*
@@ -135,6 +144,11 @@ typedef struct specattn_attn_args {
        same dtype as k/v, 16-byte aligned; both NULL = the cache alone.  They sit behind the cache, are
        never subject to the selection, and are seen causally: query t also attends to new tokens 0..t. */
     const void *k_new, *v_new;
+
+    /* 0 or 1: `indices` holds positions.  A power of two >= 2: `indices` holds chunk numbers as written by a
+       chunk-granular specattn_topp_select (counts and idx_capacity in chunks); positions past seq_lens[b]
+       in the last chunk are not attended to.  Not available with indices_are_physical or specattn_fused. */
+    int32_t chunk_size;
 } specattn_attn_args;
 
 /*

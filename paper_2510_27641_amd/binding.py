@@ -34,6 +34,7 @@ class SelectArgs(C.Structure):
         ("page_table", C.c_void_p), ("page_size", C.c_int32), ("max_pages_per_seq", C.c_int32),
         ("emit_physical", C.c_int32),
         ("block_counts", C.c_void_p), ("reuse_selection", C.c_int32),
+        ("chunk_size", C.c_int32),
     ]
 
 
@@ -52,6 +53,7 @@ class AttnArgs(C.Structure):
         ("out", C.c_void_p), ("lse", C.c_void_p),
         ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
         ("k_new", C.c_void_p), ("v_new", C.c_void_p),
+        ("chunk_size", C.c_int32),
     ]
 
 
@@ -134,7 +136,7 @@ def select_args(probs: torch.Tensor, top_p: float, *, indices: Optional[torch.Te
                 row_flags: Optional[torch.Tensor] = None, seq_lens: Optional[torch.Tensor] = None,
                 page_table: Optional[torch.Tensor] = None, page_size: int = 0,
                 emit_physical: bool = False, block_counts: Optional[torch.Tensor] = None,
-                reuse_selection: bool = False) -> SelectArgs:
+                reuse_selection: bool = False, chunk_size: int = 0) -> SelectArgs:
     """probs [B,H_kv,n] fp32 (last dim contiguous); indices [B*H_kv, cap] int32."""
     assert probs.dtype == torch.float32 and probs.dim() == 3 and probs.stride(2) == 1
     B, H, n = probs.shape
@@ -160,6 +162,7 @@ def select_args(probs: torch.Tensor, top_p: float, *, indices: Optional[torch.Te
         assert block_counts.dtype == torch.int32 and block_counts.is_contiguous()
         a.block_counts = block_counts.data_ptr()
     a.reuse_selection = int(reuse_selection)
+    a.chunk_size = chunk_size
     return a
 
 
@@ -199,7 +202,8 @@ def attn_args(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, *, out: torch.T
               n_max: Optional[int] = None, sm_scale: float = 0.0,
               page_table: Optional[torch.Tensor] = None, page_size: int = 0,
               indices_are_physical: bool = False, seq_lens: Optional[torch.Tensor] = None,
-              k_new: Optional[torch.Tensor] = None, v_new: Optional[torch.Tensor] = None) -> AttnArgs:
+              k_new: Optional[torch.Tensor] = None, v_new: Optional[torch.Tensor] = None,
+              chunk_size: int = 0) -> AttnArgs:
     """q [B,H_q,T,d]; contiguous k/v [B,H_kv,n,d]; paged k/v pool [pages,H_kv,page_size,d];
     k_new/v_new [B,H_kv,T,d] contiguous (the new tokens behind the cache), optional."""
     assert q.dim() == 4 and k.dim() == 4 and k.shape == v.shape and k.stride() == v.stride()
@@ -236,6 +240,7 @@ def attn_args(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, *, out: torch.T
     assert out.dtype == torch.float32 and out.is_contiguous() and tuple(out.shape) == (B, H_q, T, d)
     a.out = out.data_ptr()
     a.lse = None if lse is None else lse.data_ptr()
+    a.chunk_size = chunk_size
     if k_new is not None:
         assert v_new is not None and k_new.dtype == v_new.dtype == q.dtype
         assert k_new.is_contiguous() and v_new.is_contiguous()

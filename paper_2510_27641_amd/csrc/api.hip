@@ -61,6 +61,8 @@ specattn_status check_select(const specattn_select_args *s, bool fused)
         if (s->idx_capacity < 1) { set_error("idx_capacity must be at least 1"); return SPECATTN_ESHAPE; }
         if (s->idx_stride_row < s->idx_capacity) { set_error("idx_stride_row is smaller than idx_capacity"); return SPECATTN_ESHAPE; }
     }
+    if (s->chunk_size < 0 || (s->chunk_size > 1 && (!is_pow2(s->chunk_size) || s->chunk_size > 1024))) { set_error("chunk_size must be 0, 1 or a power of two up to 1024"); return SPECATTN_ESHAPE; }
+    if (s->chunk_size > 1 && (fused || s->emit_physical || s->block_counts)) { set_error("chunk-granular selection is not available with the fused call, emit_physical or block_counts"); return SPECATTN_EUNSUPPORTED; }
     if (s->probs_stride_h < s->n_max || s->probs_stride_b < s->n_max) { set_error("probs strides are smaller than n_max"); return SPECATTN_ESHAPE; }
     if (s->emit_physical) {
         if (!s->page_table) { set_error("emit_physical needs a page table"); return SPECATTN_EINVAL; }
@@ -91,6 +93,8 @@ specattn_status check_attn(const specattn_attn_args *a, bool fused)
         if (a->page_table && (int64_t)a->max_pages_per_seq * a->page_size < a->n_max) { set_error("page table is shorter than n_max"); return SPECATTN_ESHAPE; }
         if (a->kv_stride_page <= 0) { set_error("kv_stride_page must be positive"); return SPECATTN_ESHAPE; }
     }
+    if (a->chunk_size < 0 || (a->chunk_size > 1 && (!is_pow2(a->chunk_size) || a->chunk_size > 1024))) { set_error("chunk_size must be 0, 1 or a power of two up to 1024"); return SPECATTN_ESHAPE; }
+    if (a->chunk_size > 1 && (fused || dense || a->indices_are_physical)) { set_error("chunk lists are not available with the fused call, dense calls or physical indices"); return SPECATTN_EUNSUPPORTED; }
     if ((a->k_new == nullptr) != (a->v_new == nullptr)) { set_error("k_new and v_new must both be given or both be NULL"); return SPECATTN_EINVAL; }
     if (a->k_new && (!aligned(a->k_new, 16) || !aligned(a->v_new, 16))) { set_error("k_new and v_new must be 16-byte aligned"); return SPECATTN_EALIGN; }
     if (a->kv_stride_n < a->d) { set_error("kv_stride_n is smaller than d"); return SPECATTN_ESHAPE; }
@@ -133,6 +137,8 @@ SelectLaunch make_select(const specattn_select_args *s)
     l.emit_physical = s->emit_physical;
     l.block_counts = s->block_counts;
     l.blocks_per_row = (s->n_max + SEL_BLOCK - 1) / SEL_BLOCK;
+    l.n_tokens = s->n_max;
+    l.chunk_shift = 0;
     return l;
 }
 
@@ -155,6 +161,7 @@ AttnLaunch make_attn(const specattn_attn_args *a)
     l.counts = a->counts;
     l.idx_capacity = a->idx_capacity;
     l.indices_are_physical = a->indices_are_physical;
+    l.chunk_shift = a->chunk_size > 1 ? log2i(a->chunk_size) : 0;
     l.dense = (!a->indices && !a->counts) ? 1 : 0;          // the fused call overwrites counts afterwards
     if (l.dense) l.idx_capacity = a->n_max;
     l.k_new = a->k_new;
@@ -182,7 +189,22 @@ specattn_status specattn_topp_select(const specattn_select_args *sel, void *work
     if (st != SPECATTN_OK) return st;
     st = check_workspace(workspace, workspace_bytes, specattn_workspace_size(sel, nullptr));
     if (st != SPECATTN_OK) return st;
-    return launch_select(make_select(sel), static_cast<hipStream_t>(stream));
+    SelectLaunch l = make_select(sel);
+    if (sel->chunk_size > 1) {                      // reduce to chunk masses, then select over those
+        const int cs = log2i(sel->chunk_size);
+        const int nc = (sel->n_max + sel->chunk_size - 1) >> cs;
+        float *mass = static_cast<float *>(workspace);
+        st = launch_chunk_masses(sel->probs, sel->probs_stride_b, sel->probs_stride_h, sel->B, sel->H_kv, sel->n_max,
+                                 sel->seq_lens, cs, nc, mass, static_cast<hipStream_t>(stream));
+        if (st != SPECATTN_OK) return st;
+        l.probs = mass;
+        l.stride_b = (int64_t)sel->H_kv * nc;
+        l.stride_h = nc;
+        l.n_max = nc;
+        l.chunk_shift = cs;
+        l.blocks_per_row = (nc + SEL_BLOCK - 1) / SEL_BLOCK;
+    }
+    return launch_select(l, static_cast<hipStream_t>(stream));
 }
 
 static specattn_status check_union(const specattn_union_args *u)
@@ -291,12 +313,17 @@ specattn_status specattn_fused(const specattn_select_args *sel, const specattn_a
 size_t specattn_workspace_size(const specattn_select_args *sel, const specattn_attn_args *attn)
 {
     if (!sel && !attn) return 0;
-    if (sel && !attn) return 0;                       // selection keeps its state on chip
+    if (sel && !attn) {                               // token selection keeps its state on chip;
+        if (sel->chunk_size <= 1) return 0;           // chunk selection needs room for the chunk masses
+        if (sel->B <= 0 || sel->H_kv <= 0 || sel->n_max <= 0 || !is_pow2(sel->chunk_size)) return 0;
+        const size_t nc = ((size_t)sel->n_max + sel->chunk_size - 1) / sel->chunk_size;
+        return ((size_t)sel->B * sel->H_kv * nc * sizeof(float) + 255) & ~(size_t)255;
+    }
     if (attn->B <= 0 || attn->H_kv <= 0 || attn->H_q <= 0 || attn->T <= 0 || attn->d <= 0) return 0;
     if (attn->H_q % attn->H_kv) return 0;
     const int rows = attn->B * attn->H_kv;
     const bool dense = !attn->indices && !attn->counts;
-    const int cap = (sel || dense) ? attn->n_max : attn->idx_capacity;
+    const int cap = (sel || dense) ? attn->n_max : attn->idx_capacity * (attn->chunk_size > 1 ? attn->chunk_size : 1);
     if (cap <= 0) return 0;
     size_t bytes = attn_workspace_bytes(rows, attn->H_q / attn->H_kv, attn->T, attn->d, cap);
     if (sel) {                                        // fused: room for tau and the block counts
@@ -309,6 +336,6 @@ size_t specattn_workspace_size(const specattn_select_args *sel, const specattn_a
 
 const char *specattn_last_error(void) { return g_error; }
 
-int specattn_version(void) { return 1002; }
+int specattn_version(void) { return 1003; }
 
 }  // extern "C"

@@ -107,7 +107,7 @@ __global__ __launch_bounds__(GEN_THREADS) void attn_generic_kernel(AttnLaunch a,
             const int p = e / D, dd = e - p * D;
             float kv = 0.0f, vv = 0.0f;
             if (p < np) {
-                const int64_t o = map.off(idx ? idx[j0 + p] : j0 + p) + dd;
+                const int64_t o = map.off(attn_list_pos(a, idx, j0 + p)) + dd;
                 kv = Elem<T>::ld(a.k, o);
                 vv = Elem<T>::ld(a.v, o);
             }
@@ -262,7 +262,7 @@ specattn_status launch_attn(const AttnLaunch &a, hipStream_t stream)
     const int rows = a.B * a.H_kv;
     const int G = a.H_q / a.H_kv;
     const int QT = G * a.T;
-    const int ns = attn_num_splits(rows, a.idx_capacity);
+    const int ns = attn_num_splits(rows, a.idx_capacity << a.chunk_shift);
     float *part_o = static_cast<float *>(a.workspace);
     float *part_ml = part_o + (size_t)rows * ns * QT * a.d;
     specattn_status st;

@@ -354,7 +354,7 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
             const int j = tid + k * THREADS;
             int jj = first + j;
             jj = jj < count ? jj : count - 1;
-            out[k] = j < n ? (uint32_t)(map.rel<LAYOUT>(a.dense ? jj : idx[jj]) >> 3) : 0u;
+            out[k] = j < n ? (uint32_t)(map.rel<LAYOUT>(attn_list_pos(a, idx, jj)) >> 3) : 0u;
         }
     };
     auto store_entries = [&](int n, const uint32_t (&in)[EPT]) {
@@ -477,7 +477,7 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
             for (int i = 0; i < 8; ++i) {
                 int jj = (lb + wave) * TILE + 4 * i + g;
                 jj = jj < count ? jj : count - 1;
-                e[i] = (uint32_t)(map.rel<LAYOUT>(a.dense ? jj : idx[jj]) >> 3);
+                e[i] = (uint32_t)(map.rel<LAYOUT>(attn_list_pos(a, idx, jj)) >> 3);
             }
             const char *kb0 = static_cast<const char *>(a.k) + map.base * 2;
             const char *vb0 = static_cast<const char *>(a.v) + map.base * 2;

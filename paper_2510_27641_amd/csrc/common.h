@@ -41,11 +41,17 @@ struct SelectLaunch {
     int emit_physical;
     int32_t *block_counts;   // may be null; [rows][blocks_per_row]
     int blocks_per_row;
+    int n_tokens;            // positions behind a row: seq_lens counts these (n_max << chunk_shift at most)
+    int chunk_shift;         // log2 of the chunk size when the row holds chunk masses, else 0
 #ifdef SPECATTN_TIMING
     long long *timing;
 #endif
 };
 specattn_status launch_select(const SelectLaunch &a, hipStream_t stream);
+// mass[r][c] = fp32(sum in fp64 of the entries of chunk c of row r), NaN if the chunk holds an invalid entry
+specattn_status launch_chunk_masses(const float *probs, int64_t stride_b, int64_t stride_h, int B, int H, int n_tokens,
+                                    const int32_t *seq_lens, int chunk_shift, int n_chunks, float *mass,
+                                    hipStream_t stream);
 
 // union of the per-step selections (Algorithm 2 as a whole)
 size_t union_workspace_bytes(int B, int H_kv, int M, int n_max);
@@ -68,6 +74,7 @@ struct AttnLaunch {
     int idx_capacity;
     int indices_are_physical;
     int dense;               // 1: no list; every position below the sequence length is attended to
+    int chunk_shift;         // > 0: list entries are chunk numbers of 1 << chunk_shift positions each
     const void *k_new, *v_new;   // [B][H_kv][T][d] new tokens behind the cache, or null
     float *out;
     float *lse;              // may be null
@@ -82,15 +89,33 @@ struct AttnLaunch {
     int blocks_per_row;
 };
 // Number of positions row r attends to: the kept count (clamped to the list capacity), or the
-// sequence length when there is no list.
+// sequence length when there is no list.  With a chunk list: the kept chunks' positions, less the
+// part of the last kept chunk that lies past the sequence length (the list is ascending, so only
+// the last entry can be the partial chunk).
 __device__ __forceinline__ int attn_row_count(const AttnLaunch &a, int r)
 {
-    if (a.dense) {
-        const int len = a.seq_lens ? a.seq_lens[r / a.H_kv] : a.n_max;
-        return len < 0 ? 0 : (len > a.n_max ? a.n_max : len);
+    int len = a.n_max;
+    if (a.dense || a.chunk_shift) {
+        len = a.seq_lens ? a.seq_lens[r / a.H_kv] : a.n_max;
+        len = len < 0 ? 0 : (len > a.n_max ? a.n_max : len);
     }
-    const int c = a.counts[r];
-    return c < 0 ? 0 : (c > a.idx_capacity ? a.idx_capacity : c);
+    if (a.dense) return len;
+    int c = a.counts[r];
+    c = c < 0 ? 0 : (c > a.idx_capacity ? a.idx_capacity : c);
+    if (!a.chunk_shift || c == 0) return c;
+    const int last = a.indices[(int64_t)r * a.idx_stride + c - 1];
+    const int end = (last + 1) << a.chunk_shift;
+    int cut = end > len ? end - len : 0;
+    cut = cut > (1 << a.chunk_shift) ? (1 << a.chunk_shift) : cut;
+    return (c << a.chunk_shift) - cut;
+}
+
+// Position behind list rank jj of a row whose list starts at idx.
+__device__ __forceinline__ int attn_list_pos(const AttnLaunch &a, const int32_t *idx, int jj)
+{
+    if (a.dense) return jj;
+    if (a.chunk_shift) return (idx[jj >> a.chunk_shift] << a.chunk_shift) | (jj & ((1 << a.chunk_shift) - 1));
+    return idx[jj];
 }
 
 __device__ __forceinline__ float ld_elem(const void *p, int64_t i, int dtype)

@@ -183,8 +183,10 @@ __global__ __launch_bounds__(THREADS, 4) void topp_select_kernel(SelectLaunch a)
     const int r = blockIdx.x;
     const int b = r / a.H_kv, h = r - b * a.H_kv;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    int len = a.seq_lens ? a.seq_lens[b] : a.n_max;
-    len = len < 0 ? 0 : (len > a.n_max ? a.n_max : len);
+    int len = a.seq_lens ? a.seq_lens[b] : a.n_tokens;
+    len = len < 0 ? 0 : (len > a.n_tokens ? a.n_tokens : len);
+    len = (len + (1 << a.chunk_shift) - 1) >> a.chunk_shift;     // rows of chunk masses: length in chunks
+    len = len > a.n_max ? a.n_max : len;
     const float *row = a.probs + (int64_t)b * a.stride_b + (int64_t)h * a.stride_h;
     const bool aligned = (reinterpret_cast<uintptr_t>(row) & 15) == 0;
     const int n_items = (len + ITEM - 1) / ITEM;
@@ -462,7 +464,55 @@ specattn_status launch_one(const SelectLaunch &a, hipStream_t stream)
     return check_launch("topp_select_kernel");
 }
 
+// One thread per (row, chunk): the chunk's entries are added up in fp64 in ascending position order and
+// the sum is rounded once to fp32 (Section 4: chunk-granular selection; the score of a chunk is its mass).
+__global__ __launch_bounds__(256) void chunk_mass_kernel(const float *__restrict__ probs, int64_t stride_b,
+                                                         int64_t stride_h, int H, int n_tokens,
+                                                         const int32_t *__restrict__ seq_lens, int chunk_shift,
+                                                         int n_chunks, int64_t total, float *__restrict__ mass)
+{
+    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (gid >= total) return;
+    const int64_t r = gid / n_chunks;
+    const int c = (int)(gid - r * n_chunks);
+    const int b = (int)(r / H), h = (int)(r - (int64_t)b * H);
+    int len = seq_lens ? seq_lens[b] : n_tokens;
+    len = len < 0 ? 0 : (len > n_tokens ? n_tokens : len);
+    const float *row = probs + (int64_t)b * stride_b + (int64_t)h * stride_h;
+    const int chunk = 1 << chunk_shift;
+    const int p0 = c << chunk_shift;
+    int p1 = p0 + chunk;
+    p1 = p1 > len ? len : p1;
+    double sum = 0.0;
+    bool bad = false;
+    auto add = [&](float x) {
+        const uint32_t u = __float_as_uint(x);
+        if (u > 0x80000000u || (u & 0x7fffffffu) >= 0x7f800000u) bad = true;     // negative, infinite or NaN
+        sum += (double)x;
+    };
+    if (p1 == p0 + chunk && chunk >= 4 && (reinterpret_cast<uintptr_t>(row + p0) & 15) == 0) {
+        for (int p = p0; p < p1; p += 4) {
+            const float4 v = *reinterpret_cast<const float4 *>(row + p);
+            add(v.x); add(v.y); add(v.z); add(v.w);
+        }
+    } else {
+        for (int p = p0; p < p1; ++p) add(row[p]);
+    }
+    mass[gid] = bad ? __uint_as_float(0x7fc00000u) : (float)sum;
+}
+
 }  // namespace
+
+specattn_status launch_chunk_masses(const float *probs, int64_t stride_b, int64_t stride_h, int B, int H, int n_tokens,
+                                    const int32_t *seq_lens, int chunk_shift, int n_chunks, float *mass,
+                                    hipStream_t stream)
+{
+    const int64_t total = (int64_t)B * H * n_chunks;
+    const unsigned grid = (unsigned)((total + 255) / 256);
+    hipLaunchKernelGGL(chunk_mass_kernel, dim3(grid), dim3(256), 0, stream, probs, stride_b, stride_h, H, n_tokens,
+                       seq_lens, chunk_shift, n_chunks, total, mass);
+    return check_launch("chunk_mass_kernel");
+}
 
 specattn_status launch_select(const SelectLaunch &a, hipStream_t stream)
 {

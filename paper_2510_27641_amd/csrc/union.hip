@@ -199,6 +199,7 @@ specattn_status launch_union(const specattn_union_args *u, void *workspace, hipS
     s.B = u->B;
     s.H_kv = u->H_draft * u->S;
     s.n_max = u->n_max;
+    s.n_tokens = u->n_max;
     s.seq_lens = u->seq_lens;
     s.top_p = u->top_p;
     s.counts = mcounts;

@@ -50,6 +50,8 @@ def _attn(**kw):
 
 @pytest.mark.parametrize("kw,status", [
     (dict(probs=None), sa.EINVAL), (dict(counts=None), sa.EINVAL), (dict(indices=None), sa.EINVAL),
+    (dict(chunk_size=12), sa.ESHAPE), (dict(chunk_size=-1), sa.ESHAPE), (dict(chunk_size=16), sa.EWORKSPACE),
+    (dict(chunk_size=16, block_counts=0x7000), sa.EUNSUPPORTED),
     (dict(top_p=0.0), sa.EINVAL), (dict(top_p=1.5), sa.EINVAL), (dict(top_p=float("nan")), sa.EINVAL),
     (dict(B=0), sa.EINVAL), (dict(n_max=(1 << 20) + 1, probs_stride_h=1 << 21, probs_stride_b=1 << 23), sa.ESHAPE),
     (dict(idx_capacity=0), sa.ESHAPE), (dict(idx_stride_row=8), sa.ESHAPE), (dict(probs_stride_h=512), sa.ESHAPE),
@@ -74,6 +76,8 @@ def test_select_argument_errors(kw, status):
     (dict(), sa.EWORKSPACE),                                      # valid arguments but no workspace
     (dict(counts=None), sa.EINVAL),                               # a list without counts
     (dict(k_new=0x7000), sa.EINVAL),                              # new keys without new values
+    (dict(chunk_size=24), sa.ESHAPE), (dict(chunk_size=16, indices_are_physical=1, page_size=16, kv_stride_page=8 * 16 * 128), sa.EUNSUPPORTED),
+    (dict(chunk_size=16, indices=None, counts=None), sa.EUNSUPPORTED),
     (dict(k_new=0x7000, v_new=0x8004), sa.EALIGN),
     (dict(indices=None, counts=None), sa.EWORKSPACE),             # dense call: valid, but no workspace
     (dict(indices=None, counts=None, indices_are_physical=1, page_size=16, kv_stride_page=8 * 16 * 128), sa.EINVAL),
@@ -94,6 +98,11 @@ def test_workspace_size_is_monotone_and_zero_for_selection():
     assert 0 < small <= big
     assert small % 256 == 0
     assert sa.specattn_workspace_size(None, _attn(H_q=30)) == 0
+
+
+def test_chunk_selection_workspace_size():
+    assert sa.specattn_workspace_size(_sel(chunk_size=16), None) == 2 * 4 * 64 * 4
+    assert sa.specattn_workspace_size(_sel(chunk_size=16, n_max=1000, probs_stride_h=1024), None) == ((2 * 4 * 63 * 4 + 255) // 256) * 256
 
 
 def test_stream_read_rejects_bad_arguments():
