@@ -8,6 +8,7 @@ from .oracle import (  # noqa: F401
     ROW_NEAR_BOUNDARY,
     SelectResult,
     UnionResult,
+    bisection_select,
     chunk_masses,
     chunk_token_mask,
     masked_attention,

@@ -41,6 +41,9 @@ def _load():
                                                      C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
                                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_double,
                                                      C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
+        lib.oracle_bisection_select.restype = C.c_int
+        lib.oracle_bisection_select.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_void_p, C.c_float, C.c_int,
+                                                C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p]
         lib.oracle_chunk_masses.restype = C.c_int
         lib.oracle_chunk_masses.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_void_p]
         _lib = lib
@@ -90,6 +93,24 @@ def topp_select(probs: np.ndarray, top_p: float, lens: Optional[np.ndarray] = No
     if rc != 0:
         raise ValueError(f"oracle_topp_select failed with {rc} (top_p must be in (0, 1])")
     return SelectResult(idx, counts, tau, flags, diag)
+
+
+def bisection_select(probs: np.ndarray, top_p: float, iters: int,
+                     lens: Optional[np.ndarray] = None) -> SelectResult:
+    """Algorithm 2 with `iters` halvings per row (the paper's implementation: 10); set {a >= theta_low}."""
+    probs = np.ascontiguousarray(probs, dtype=np.float32)
+    rows, n = probs.shape
+    lens = np.full(rows, n, dtype=np.int32) if lens is None else np.ascontiguousarray(lens, dtype=np.int32)
+    idx = np.full((rows, max(n, 1)), -1, dtype=np.int32)
+    counts = np.zeros(rows, dtype=np.int32)
+    tau = np.zeros(rows, dtype=np.float32)
+    flags = np.zeros(rows, dtype=np.uint32)
+    rc = _load().oracle_bisection_select(probs.ctypes.data, n, rows, lens.ctypes.data, float(top_p), int(iters),
+                                         idx.ctypes.data, idx.shape[1], counts.ctypes.data, tau.ctypes.data,
+                                         flags.ctypes.data)
+    if rc != 0:
+        raise ValueError(f"oracle_bisection_select failed with {rc}")
+    return SelectResult(idx, counts, tau, flags, np.zeros((rows, 4)))
 
 
 def chunk_masses(probs: np.ndarray, chunk: int, lens: Optional[np.ndarray] = None) -> np.ndarray:

@@ -20,6 +20,8 @@
  *   oracle_nucleus_bisection Algorithm 2 itself (value-space bisection), with
  *                            an iteration count instead of the epsilon test,
  *                            as the footnote in Section 3.4 describes.
+ *   oracle_bisection_select  the same with a fixed number of halvings, as a selection
+ *                            (what the paper's implementation runs, 10 halvings).
  *   oracle_masked_attention_tail  the same with the keys/values of the tokens being
  *                            verified appended causally (Algorithm 1, verification
  *                            step: gamma + 1 tokens go through the verifier at once).
@@ -38,6 +40,8 @@
  *                            identity, the masses add up to the row sum.
  *   oracle_nucleus_bisection feasibility / superset / bracket-width bounds
  *                            that follow from the algorithm's invariant.
+ *   oracle_bisection_select  hand-worked rows, a separately written numpy loop, the exact
+ *                            selection as a subset, equality with it after 60 halvings.
  *   oracle_masked_attention_tail  a library attention routine with an explicit
  *                            per-query boolean mask over cache + new tokens; with an
  *                            empty cache and one new token the output is that token's
@@ -156,20 +160,70 @@ int oracle_topp_select(const float *probs, int64_t row_stride, int rows, const i
  * the last midpoint; the algorithm as printed selects with the last midpoint.
  * theta_low always keeps mass >= target (it starts at 0 and only moves to
  * midpoints that do), so {a >= theta_low} is the feasible choice.
+ * margin (optional): the smallest |M_current - M_target| met in any iteration - how close the
+ * closest of the algorithm's comparisons came to going the other way.
  */
-int oracle_nucleus_bisection(const float *a, int L, double p, int iters,
-                             double *theta_low, double *theta_high, double *theta_mid)
+static void bisect_row(const float *a, int L, double p, int iters,
+                       double *theta_low, double *theta_high, double *theta_mid, double *total_out, double *margin)
 {
-    double total = 0.0, hi = 0.0, lo = 0.0, mid = 0.0;
+    double total = 0.0, hi = 0.0, lo = 0.0, mid = 0.0, closest = INFINITY;
     for (int i = 0; i < L; ++i) { total += (double)a[i]; if ((double)a[i] > hi) hi = (double)a[i]; }
     const double target = p * total;
     for (int it = 0; it < iters; ++it) {
         mid = 0.5 * (hi + lo);
         double m = 0.0;
         for (int i = 0; i < L; ++i) if ((double)a[i] >= mid) m += (double)a[i];
+        if (fabs(m - target) < closest) closest = fabs(m - target);
         if (m < target) hi = mid; else lo = mid;
     }
     *theta_low = lo; *theta_high = hi; *theta_mid = mid;
+    if (total_out) *total_out = total;
+    if (margin) *margin = closest;
+}
+
+int oracle_nucleus_bisection(const float *a, int L, double p, int iters,
+                             double *theta_low, double *theta_high, double *theta_mid)
+{
+    bisect_row(a, L, p, iters, theta_low, theta_high, theta_mid, NULL, NULL);
+    return 0;
+}
+
+/*
+ * Algorithm 2 with a fixed number of halvings (the footnote in Section 3.4: the implementation
+ * uses 10), as a selection: per row the set {j : a_j >= theta_low} in ascending j.  theta_low = 0
+ * (never raised) keeps every position of the row, zeros included.
+ * tau[r] is the smallest fp32 value >= theta_low, so that {a >= tau} is the same set.
+ * flags: ORACLE_ROW_INVALID as for the exact selection; ORACLE_ROW_NEAR_BOUNDARY when one of the
+ * comparisons M_current < M_target was decided by less than 1e-6 of the row sum.
+ */
+int oracle_bisection_select(const float *probs, int64_t row_stride, int rows, const int32_t *lens,
+                            float top_p, int iters, int32_t *indices, int64_t idx_stride,
+                            int32_t *counts, float *tau, uint32_t *flags)
+{
+    if (!(top_p > 0.0f && top_p <= 1.0f) || iters < 1) return -1;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int r = 0; r < rows; ++r) {
+        const float *a = probs + (int64_t)r * row_stride;
+        const int L = lens[r];
+        int32_t *out = indices + (int64_t)r * idx_stride;
+        counts[r] = 0; tau[r] = 0.0f; flags[r] = 0;
+        int bad = (L <= 0);
+        for (int i = 0; i < L && !bad; ++i)
+            if (isnan(a[i]) || isinf(a[i]) || a[i] < 0.0f) bad = 1;
+        double lo, hi, mid, total, margin;
+        if (!bad) {
+            bisect_row(a, L, (double)top_p, iters, &lo, &hi, &mid, &total, &margin);
+            if (!(total > 0.0)) bad = 1;
+        }
+        if (bad) { flags[r] = ORACLE_ROW_INVALID; continue; }
+        int c = 0;
+        for (int i = 0; i < L; ++i) if ((double)a[i] >= lo) out[c++] = i;
+        counts[r] = c;
+        float t = (float)lo;
+        if ((double)t < lo) t = nextafterf(t, INFINITY);
+        tau[r] = t;
+        if (margin <= 1e-6 * total) flags[r] |= ORACLE_ROW_NEAR_BOUNDARY;
+    }
     return 0;
 }
 
