@@ -95,6 +95,14 @@ typedef struct specattn_select_args {
        chunk masses.  Needs workspace (specattn_workspace_size(sel, NULL)); not available together with
        emit_physical, block_counts or specattn_fused (SPECATTN_EUNSUPPORTED). */
     int32_t chunk_size;
+
+    /* 0: the exact tau*.  k >= 1: Algorithm 2's value-space bisection with k halvings of [0, max] instead
+       (the footnote of Section 3.4: the paper's implementation uses 10); the kept set is {a >= theta_low},
+       the bracket end that always keeps mass >= top_p * (row sum), and `thresholds` receives theta_low
+       rounded up to fp32.  theta_low = 0 keeps every position of the row.  ROW_NEAR_BOUNDARY then means
+       that one of the k comparisons was decided by less than 1e-6 of the row sum.  Needs workspace; not
+       available together with block_counts, chunk_size > 1 or specattn_fused (SPECATTN_EUNSUPPORTED). */
+    int32_t bisect_iters;
 } specattn_select_args;
 
 /*

@@ -34,7 +34,7 @@ class SelectArgs(C.Structure):
         ("page_table", C.c_void_p), ("page_size", C.c_int32), ("max_pages_per_seq", C.c_int32),
         ("emit_physical", C.c_int32),
         ("block_counts", C.c_void_p), ("reuse_selection", C.c_int32),
-        ("chunk_size", C.c_int32),
+        ("chunk_size", C.c_int32), ("bisect_iters", C.c_int32),
     ]
 
 
@@ -136,7 +136,8 @@ def select_args(probs: torch.Tensor, top_p: float, *, indices: Optional[torch.Te
                 row_flags: Optional[torch.Tensor] = None, seq_lens: Optional[torch.Tensor] = None,
                 page_table: Optional[torch.Tensor] = None, page_size: int = 0,
                 emit_physical: bool = False, block_counts: Optional[torch.Tensor] = None,
-                reuse_selection: bool = False, chunk_size: int = 0) -> SelectArgs:
+                reuse_selection: bool = False, chunk_size: int = 0,
+                bisect_iters: int = 0) -> SelectArgs:
     """probs [B,H_kv,n] fp32 (last dim contiguous); indices [B*H_kv, cap] int32."""
     assert probs.dtype == torch.float32 and probs.dim() == 3 and probs.stride(2) == 1
     B, H, n = probs.shape
@@ -163,6 +164,7 @@ def select_args(probs: torch.Tensor, top_p: float, *, indices: Optional[torch.Te
         a.block_counts = block_counts.data_ptr()
     a.reuse_selection = int(reuse_selection)
     a.chunk_size = chunk_size
+    a.bisect_iters = bisect_iters
     return a
 
 

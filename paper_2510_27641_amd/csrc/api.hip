@@ -63,6 +63,8 @@ specattn_status check_select(const specattn_select_args *s, bool fused)
     }
     if (s->chunk_size < 0 || (s->chunk_size > 1 && (!is_pow2(s->chunk_size) || s->chunk_size > 1024))) { set_error("chunk_size must be 0, 1 or a power of two up to 1024"); return SPECATTN_ESHAPE; }
     if (s->chunk_size > 1 && (fused || s->emit_physical || s->block_counts)) { set_error("chunk-granular selection is not available with the fused call, emit_physical or block_counts"); return SPECATTN_EUNSUPPORTED; }
+    if (s->bisect_iters < 0 || s->bisect_iters > 64) { set_error("bisect_iters must lie in 0..64"); return SPECATTN_ESHAPE; }
+    if (s->bisect_iters > 0 && (fused || s->block_counts || s->chunk_size > 1 || !s->indices)) { set_error("the bisection mode needs an index list and is not available with the fused call, block_counts or chunks"); return SPECATTN_EUNSUPPORTED; }
     if (s->probs_stride_h < s->n_max || s->probs_stride_b < s->n_max) { set_error("probs strides are smaller than n_max"); return SPECATTN_ESHAPE; }
     if (s->emit_physical) {
         if (!s->page_table) { set_error("emit_physical needs a page table"); return SPECATTN_EINVAL; }
@@ -190,6 +192,21 @@ specattn_status specattn_topp_select(const specattn_select_args *sel, void *work
     st = check_workspace(workspace, workspace_bytes, specattn_workspace_size(sel, nullptr));
     if (st != SPECATTN_OK) return st;
     SelectLaunch l = make_select(sel);
+    if (sel->bisect_iters > 0) {                    // Algorithm 2 as the paper runs it, then the mask and compaction passes
+        // workspace: [tau][valid][flags][block counts][ballots], the layout of the union with one member per row
+        const size_t rows = (size_t)sel->B * sel->H_kv, a256 = (rows * 4 + 255) & ~(size_t)255;
+        char *ws = static_cast<char *>(workspace);
+        float *tau = sel->thresholds ? sel->thresholds : reinterpret_cast<float *>(ws);
+        int32_t *valid = reinterpret_cast<int32_t *>(ws + a256);
+        uint32_t *mflags = reinterpret_cast<uint32_t *>(ws + 2 * a256);
+        hipStream_t hs = static_cast<hipStream_t>(stream);
+        st = launch_bisect_thresholds(l, sel->bisect_iters, tau, valid, mflags, hs);
+        if (st != SPECATTN_OK) return st;
+        return launch_threshold_union(sel->probs, sel->probs_stride_b, sel->probs_stride_h, sel->B, sel->H_kv, 1, sel->n_max,
+                                      sel->seq_lens, tau, valid, mflags, ws + 3 * a256, sel->indices, sel->idx_stride_row,
+                                      sel->idx_capacity, sel->counts, sel->row_flags, sel->page_table, sel->page_size,
+                                      sel->max_pages_per_seq, sel->emit_physical, hs);
+    }
     if (sel->chunk_size > 1) {                      // reduce to chunk masses, then select over those
         const int cs = log2i(sel->chunk_size);
         const int nc = (sel->n_max + sel->chunk_size - 1) >> cs;
@@ -314,6 +331,10 @@ size_t specattn_workspace_size(const specattn_select_args *sel, const specattn_a
 {
     if (!sel && !attn) return 0;
     if (sel && !attn) {                               // token selection keeps its state on chip;
+        if (sel->bisect_iters > 0) {
+            if (sel->B <= 0 || sel->H_kv <= 0 || sel->n_max <= 0) return 0;
+            return union_workspace_bytes(sel->B, sel->H_kv, 1, sel->n_max);
+        }
         if (sel->chunk_size <= 1) return 0;           // chunk selection needs room for the chunk masses
         if (sel->B <= 0 || sel->H_kv <= 0 || sel->n_max <= 0 || !is_pow2(sel->chunk_size)) return 0;
         const size_t nc = ((size_t)sel->n_max + sel->chunk_size - 1) / sel->chunk_size;
@@ -336,6 +357,6 @@ size_t specattn_workspace_size(const specattn_select_args *sel, const specattn_a
 
 const char *specattn_last_error(void) { return g_error; }
 
-int specattn_version(void) { return 1003; }
+int specattn_version(void) { return 1004; }
 
 }  // extern "C"

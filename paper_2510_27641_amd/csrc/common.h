@@ -56,6 +56,17 @@ specattn_status launch_chunk_masses(const float *probs, int64_t stride_b, int64_
 // union of the per-step selections (Algorithm 2 as a whole)
 size_t union_workspace_bytes(int B, int H_kv, int M, int n_max);
 specattn_status launch_union(const specattn_union_args *u, void *workspace, hipStream_t stream);
+// mask + compaction passes alone, for rows whose thresholds are already known; `scratch` holds the block
+// counts and ballots (the tail of union_workspace_bytes)
+specattn_status launch_threshold_union(const float *probs, int64_t stride_b, int64_t stride_m, int B, int H_kv, int M,
+                                       int n_max, const int32_t *seq_lens, const float *tau, const int32_t *mcounts,
+                                       const uint32_t *mflags, void *scratch, int32_t *indices, int64_t idx_stride,
+                                       int idx_capacity, int32_t *counts, uint32_t *row_flags,
+                                       const int32_t *page_table, int page_size, int max_pages, int emit_physical,
+                                       hipStream_t stream);
+// Algorithm 2's fixed-iteration bisection: tau[r] = theta_low rounded up to fp32, valid[r] = 0/1, flags[r]
+specattn_status launch_bisect_thresholds(const SelectLaunch &a, int iters, float *tau, int32_t *valid, uint32_t *flags,
+                                         hipStream_t stream);
 
 // ---- attention -----------------------------------------------------------------------------
 struct AttnLaunch {

@@ -60,7 +60,7 @@ __global__ __launch_bounds__(U_THREADS) void union_mask_kernel(UnionLaunch a)
 #pragma unroll
         for (int it = 0; it < U_ITERS; ++it) {
             const int p = blk * U_BLOCK + it * U_THREADS * 4 + tid * 4;
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            float4 v = make_float4(-1.f, -1.f, -1.f, -1.f);   // positions past the row's end: below any threshold
             if (p + 3 < len && aligned) {
                 v = *reinterpret_cast<const float4 *>(row + p);
             } else {
@@ -70,8 +70,9 @@ __global__ __launch_bounds__(U_THREADS) void union_mask_kernel(UnionLaunch a)
                 if (p + 3 < len) v.w = row[p + 3];
             }
             // compared as integers, like the selection itself: non-negative floats order like their bit
-            // patterns, and -0.0 (the only signed value a valid row can hold) stays below every threshold
-            const int x = __float_as_int(v.x), y = __float_as_int(v.y), z = __float_as_int(v.z), w = __float_as_int(v.w);
+            // patterns; -0.0 (the only signed value a valid row can hold) counts as zero
+            auto bits = [](float f) { const int i = __float_as_int(f); return i == (int)0x80000000 ? 0 : i; };
+            const int x = bits(v.x), y = bits(v.y), z = bits(v.z), w = bits(v.w);
             keep[it] |= (x >= t ? 1u : 0u) | (y >= t ? 2u : 0u) | (z >= t ? 4u : 0u) | (w >= t ? 8u : 0u);
         }
     }
@@ -177,10 +178,42 @@ size_t union_workspace_bytes(int B, int H_kv, int M, int n_max)
     return 3 * align256(members * 4) + align256(rows * blocks * 4) + align256(rows * blocks * U_WORDS * 8);
 }
 
+// The mask and compaction passes for rows whose member thresholds are known.
+specattn_status launch_threshold_union(const float *probs, int64_t stride_b, int64_t stride_m, int B, int H_kv, int M,
+                                       int n_max, const int32_t *seq_lens, const float *tau, const int32_t *mcounts,
+                                       const uint32_t *mflags, void *scratch, int32_t *indices, int64_t idx_stride,
+                                       int idx_capacity, int32_t *counts, uint32_t *row_flags,
+                                       const int32_t *page_table, int page_size, int max_pages, int emit_physical,
+                                       hipStream_t stream)
+{
+    const size_t rows = (size_t)B * H_kv, blocks = union_blocks(n_max);
+    char *ws = static_cast<char *>(scratch);
+    UnionLaunch a{};
+    a.probs = probs; a.stride_b = stride_b; a.stride_m = stride_m;
+    a.B = B; a.H_kv = H_kv; a.M = M; a.n_max = n_max;
+    a.seq_lens = seq_lens;
+    a.tau = tau; a.mcounts = mcounts; a.mflags = mflags;
+    a.block_counts = reinterpret_cast<int32_t *>(ws);
+    a.ballots = reinterpret_cast<unsigned long long *>(ws + align256(rows * blocks * 4));
+    a.blocks = (int)blocks;
+    a.indices = indices; a.idx_stride = idx_stride; a.idx_capacity = idx_capacity;
+    a.counts = counts; a.row_flags = row_flags;
+    a.page_table = page_table; a.max_pages = max_pages; a.emit_physical = emit_physical;
+    a.page_shift = 0;
+    if (page_table) while ((1 << a.page_shift) < page_size) ++a.page_shift;
+    const dim3 grid((unsigned)(blocks * rows));
+    hipLaunchKernelGGL(union_mask_kernel, grid, dim3(U_THREADS), 0, stream, a);
+    specattn_status st = check_launch("union_mask_kernel");
+    if (st != SPECATTN_OK) return st;
+    hipLaunchKernelGGL(union_compact_kernel, grid, dim3(U_THREADS), 0, stream, a);
+    return check_launch("union_compact_kernel");
+}
+
+// workspace: [member tau][member counts][member flags][block counts][ballots]
 specattn_status launch_union(const specattn_union_args *u, void *workspace, hipStream_t stream)
 {
     const int per = u->H_draft / u->H_kv, M = per * u->S;
-    const size_t rows = (size_t)u->B * u->H_kv, members = rows * M, blocks = union_blocks(u->n_max);
+    const size_t members = (size_t)u->B * u->H_kv * M;
     char *ws = static_cast<char *>(workspace);
     float *tau = u->member_thresholds ? u->member_thresholds : reinterpret_cast<float *>(ws);
     ws += align256(members * 4);
@@ -188,9 +221,6 @@ specattn_status launch_union(const specattn_union_args *u, void *workspace, hipS
     ws += align256(members * 4);
     uint32_t *mflags = reinterpret_cast<uint32_t *>(ws);
     ws += align256(members * 4);
-    int32_t *block_counts = reinterpret_cast<int32_t *>(ws);
-    ws += align256(rows * blocks * 4);
-    unsigned long long *ballots = reinterpret_cast<unsigned long long *>(ws);
 
     SelectLaunch s{};                                         // every member row on its own, thresholds only
     s.probs = u->probs;
@@ -205,30 +235,12 @@ specattn_status launch_union(const specattn_union_args *u, void *workspace, hipS
     s.counts = mcounts;
     s.thresholds = tau;
     s.row_flags = mflags;
-    specattn_status st = launch_select(s, stream);
+    const specattn_status st = launch_select(s, stream);
     if (st != SPECATTN_OK) return st;
-
-    UnionLaunch a{};
-    a.probs = u->probs;
-    a.stride_b = u->probs_stride_b;
-    a.stride_m = u->probs_stride_row;
-    a.B = u->B; a.H_kv = u->H_kv; a.M = M; a.n_max = u->n_max;
-    a.seq_lens = u->seq_lens;
-    a.tau = tau; a.mcounts = mcounts; a.mflags = mflags;
-    a.block_counts = block_counts; a.ballots = ballots; a.blocks = (int)blocks;
-    a.indices = u->indices; a.idx_stride = u->idx_stride_row; a.idx_capacity = u->idx_capacity;
-    a.counts = u->counts; a.row_flags = u->row_flags;
-    a.page_table = u->page_table;
-    a.max_pages = u->max_pages_per_seq;
-    a.emit_physical = u->emit_physical;
-    a.page_shift = 0;
-    if (u->page_table) while ((1 << a.page_shift) < u->page_size) ++a.page_shift;
-    const dim3 grid((unsigned)(blocks * rows));
-    hipLaunchKernelGGL(union_mask_kernel, grid, dim3(U_THREADS), 0, stream, a);
-    st = check_launch("union_mask_kernel");
-    if (st != SPECATTN_OK) return st;
-    hipLaunchKernelGGL(union_compact_kernel, grid, dim3(U_THREADS), 0, stream, a);
-    return check_launch("union_compact_kernel");
+    return launch_threshold_union(u->probs, u->probs_stride_b, u->probs_stride_row, u->B, u->H_kv, M, u->n_max,
+                                  u->seq_lens, tau, mcounts, mflags, ws, u->indices, u->idx_stride_row, u->idx_capacity,
+                                  u->counts, u->row_flags, u->page_table, u->page_size, u->max_pages_per_seq,
+                                  u->emit_physical, stream);
 }
 
 }  // namespace specattn

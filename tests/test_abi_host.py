@@ -52,6 +52,8 @@ def _attn(**kw):
     (dict(probs=None), sa.EINVAL), (dict(counts=None), sa.EINVAL), (dict(indices=None), sa.EINVAL),
     (dict(chunk_size=12), sa.ESHAPE), (dict(chunk_size=-1), sa.ESHAPE), (dict(chunk_size=16), sa.EWORKSPACE),
     (dict(chunk_size=16, block_counts=0x7000), sa.EUNSUPPORTED),
+    (dict(bisect_iters=65), sa.ESHAPE), (dict(bisect_iters=10), sa.EWORKSPACE),
+    (dict(bisect_iters=10, chunk_size=16), sa.EUNSUPPORTED), (dict(bisect_iters=10, block_counts=0x7000), sa.EUNSUPPORTED),
     (dict(top_p=0.0), sa.EINVAL), (dict(top_p=1.5), sa.EINVAL), (dict(top_p=float("nan")), sa.EINVAL),
     (dict(B=0), sa.EINVAL), (dict(n_max=(1 << 20) + 1, probs_stride_h=1 << 21, probs_stride_b=1 << 23), sa.ESHAPE),
     (dict(idx_capacity=0), sa.ESHAPE), (dict(idx_stride_row=8), sa.ESHAPE), (dict(probs_stride_h=512), sa.ESHAPE),
