@@ -194,7 +194,10 @@ specattn_status specattn_topp_select_union(const specattn_union_args *args, void
                                            size_t workspace_bytes, void *stream);
 size_t specattn_union_workspace_size(const specattn_union_args *args);
 
-/* Selection alone.  `workspace` may be NULL when specattn_workspace_size(sel, NULL) is 0. */
+/* Selection alone.  The plain selection (single positions, exact tau*) never needs a workspace: without one
+   every row is handled by one workgroup.  When specattn_workspace_size(sel, NULL) is not 0 for it (few, long
+   rows) and a workspace of that size is given, each row is split over many workgroups instead; the results
+   are the same.  The chunk and bisection modes need their workspace (SPECATTN_EWORKSPACE otherwise). */
 specattn_status specattn_topp_select(const specattn_select_args *sel, void *workspace,
                                      size_t workspace_bytes, void *stream);
 

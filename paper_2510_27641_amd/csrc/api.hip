@@ -189,9 +189,31 @@ specattn_status specattn_topp_select(const specattn_select_args *sel, void *work
     clear_error();
     specattn_status st = check_select(sel, false);
     if (st != SPECATTN_OK) return st;
-    st = check_workspace(workspace, workspace_bytes, specattn_workspace_size(sel, nullptr));
-    if (st != SPECATTN_OK) return st;
+    const bool plain = sel->bisect_iters == 0 && sel->chunk_size <= 1;
+    const size_t need = specattn_workspace_size(sel, nullptr);
+    // the plain selection works without a workspace; with one, few long rows are split over many workgroups
+    const bool split = plain && need > 0 && workspace && aligned(workspace, 256) && workspace_bytes >= need;
+    if (!plain) {
+        st = check_workspace(workspace, workspace_bytes, need);
+        if (st != SPECATTN_OK) return st;
+    }
     SelectLaunch l = make_select(sel);
+    if (split) {
+        // workspace: [tau][valid][flags][block counts][ballots] as for the union with one member per row, then the
+        // row histograms and locate states of the split passes
+        const size_t rows = (size_t)sel->B * sel->H_kv, a256 = (rows * 4 + 255) & ~(size_t)255;
+        char *ws = static_cast<char *>(workspace);
+        float *tau = sel->thresholds ? sel->thresholds : reinterpret_cast<float *>(ws);
+        int32_t *valid = reinterpret_cast<int32_t *>(ws + a256);
+        uint32_t *mflags = reinterpret_cast<uint32_t *>(ws + 2 * a256);
+        hipStream_t hs = static_cast<hipStream_t>(stream);
+        st = launch_select_multi_wg(l, ws + union_workspace_bytes(sel->B, sel->H_kv, 1, sel->n_max), tau, valid, mflags, hs);
+        if (st != SPECATTN_OK) return st;
+        return launch_threshold_union(sel->probs, sel->probs_stride_b, sel->probs_stride_h, sel->B, sel->H_kv, 1, sel->n_max,
+                                      sel->seq_lens, tau, valid, mflags, ws + 3 * a256, sel->indices, sel->idx_stride_row,
+                                      sel->idx_capacity, sel->counts, sel->row_flags, sel->page_table, sel->page_size,
+                                      sel->max_pages_per_seq, sel->emit_physical, hs);
+    }
     if (sel->bisect_iters > 0) {                    // Algorithm 2 as the paper runs it, then the mask and compaction passes
         // workspace: [tau][valid][flags][block counts][ballots], the layout of the union with one member per row
         const size_t rows = (size_t)sel->B * sel->H_kv, a256 = (rows * 4 + 255) & ~(size_t)255;
@@ -335,7 +357,11 @@ size_t specattn_workspace_size(const specattn_select_args *sel, const specattn_a
             if (sel->B <= 0 || sel->H_kv <= 0 || sel->n_max <= 0) return 0;
             return union_workspace_bytes(sel->B, sel->H_kv, 1, sel->n_max);
         }
-        if (sel->chunk_size <= 1) return 0;           // chunk selection needs room for the chunk masses
+        if (sel->chunk_size <= 1) {                   // optional: lets few long rows be split over many workgroups
+            if (sel->B <= 0 || sel->H_kv <= 0 || sel->n_max <= 0 || !sel->indices || sel->block_counts) return 0;
+            if (!select_multi_wg_preferred(sel->B * sel->H_kv, sel->n_max)) return 0;
+            return union_workspace_bytes(sel->B, sel->H_kv, 1, sel->n_max) + select_multi_wg_bytes(sel->B * sel->H_kv, sel->n_max);
+        }
         if (sel->B <= 0 || sel->H_kv <= 0 || sel->n_max <= 0 || !is_pow2(sel->chunk_size)) return 0;
         const size_t nc = ((size_t)sel->n_max + sel->chunk_size - 1) / sel->chunk_size;
         return ((size_t)sel->B * sel->H_kv * nc * sizeof(float) + 255) & ~(size_t)255;

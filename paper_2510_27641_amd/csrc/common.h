@@ -48,6 +48,12 @@ struct SelectLaunch {
 #endif
 };
 specattn_status launch_select(const SelectLaunch &a, hipStream_t stream);
+// Few long rows: each row split over many workgroups (thresholds only; the list comes from the mask and
+// compaction passes).  `scratch` holds select_multi_wg_bytes(rows, n_max).
+bool select_multi_wg_preferred(int rows, int n);
+size_t select_multi_wg_bytes(int rows, int n);
+specattn_status launch_select_multi_wg(const SelectLaunch &a, void *scratch, float *tau, int32_t *valid, uint32_t *flags,
+                                       hipStream_t stream);
 // mass[r][c] = fp32(sum in fp64 of the entries of chunk c of row r), NaN if the chunk holds an invalid entry
 specattn_status launch_chunk_masses(const float *probs, int64_t stride_b, int64_t stride_h, int B, int H, int n_tokens,
                                     const int32_t *seq_lens, int chunk_shift, int n_chunks, float *mass,

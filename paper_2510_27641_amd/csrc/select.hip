@@ -464,6 +464,172 @@ specattn_status launch_one(const SelectLaunch &a, hipStream_t stream)
     return check_launch("topp_select_kernel");
 }
 
+// ---- few long rows: one row split over many workgroups ------------------------------------------------
+// The same three radix passes, but every workgroup histograms one slice (a multiple of MW_SLICE positions,
+// chosen so that about two workgroups per CU are in flight) in LDS and
+// adds its non-empty bins to the row's histogram in memory (64-bit integer atomics: the sums stay exact and
+// independent of order).  Kernel boundaries separate the passes; at the start of the next pass every
+// workgroup of a row locates the boundary bin from the finished histogram by itself (identical code on
+// identical data), and slice 0 records the outcome for the kernels that follow.
+constexpr int MW_THREADS = 256;
+constexpr int MW_SLICE = 4096;
+
+struct MwStage {                     // outcome of one locate step
+    unsigned long long bin_packed;
+    double target, m_above;
+    unsigned c_above;
+    int bin;
+    int done;                        // the boundary bin held a single entry: tau_bits is final
+    uint32_t tau_bits;
+};
+struct MwState {
+    MwStage s1, s2;
+    int bad;                         // an entry was NaN, negative or infinite
+    int invalid;                     // no mass at all
+};
+struct MwLaunch {
+    SelectLaunch a;
+    unsigned long long *h1, *h2, *h3;    // [rows][NB1], [rows][NB2], [rows][NB2]
+    MwState *state;                      // [rows]
+    int slices, slice_len;               // workgroups per row; positions per workgroup (a multiple of MW_SLICE)
+    float *tau;                          // [rows] out
+    int32_t *valid;                      // [rows] out: 1 unless the row is invalid
+    uint32_t *flags;                     // [rows] out
+};
+
+__global__ void mw_clear_kernel(unsigned long long *p, size_t n)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0ull;
+}
+
+__device__ __forceinline__ int mw_row_len(const SelectLaunch &a, int b)
+{
+    int len = a.seq_lens ? a.seq_lens[b] : a.n_tokens;
+    len = len < 0 ? 0 : (len > a.n_tokens ? a.n_tokens : len);
+    return len > a.n_max ? a.n_max : len;
+}
+
+template <int PASS>
+__global__ __launch_bounds__(MW_THREADS) void mw_pass_kernel(MwLaunch w)
+{
+    __shared__ RowShared sh;
+    const SelectLaunch &a = w.a;
+    const int r = blockIdx.x / w.slices, sl = blockIdx.x - r * w.slices;
+    const int b = r / a.H_kv, h = r - b * a.H_kv;
+    const int tid = threadIdx.x;
+    const int len = mw_row_len(a, b);
+    MwState &st = w.state[r];
+    uint32_t want = 0;                 // PASS 2: bits[30:20] == want; PASS 3: bits[30:10] == want
+    if (PASS >= 2) {
+        if (st.bad || len == 0) return;
+        const unsigned long long *hg = PASS == 2 ? w.h1 + (size_t)r * NB1 : w.h2 + (size_t)r * NB2;
+        for (int k = tid; k < (PASS == 2 ? NB1 : NB2); k += MW_THREADS) sh.hist[k] = hg[k];
+        __syncthreads();
+        double target = 0.0, m_above = 0.0;
+        unsigned c_above = 0;
+        unsigned long long bin_packed = 0;
+        int bin, e_field;
+        if (PASS == 2) {
+            bin = locate_bin<MW_THREADS, NB1, true>(sh, 0, a.top_p, target, m_above, c_above, bin_packed);
+            if (bin < 0) {
+                if (sl == 0 && tid == 0) st.invalid = 1;
+                return;
+            }
+            e_field = bin >> 3;
+            want = (uint32_t)bin;
+        } else {
+            if (st.invalid || st.s1.done) return;
+            target = st.s1.target; m_above = st.s1.m_above; c_above = st.s1.c_above;
+            e_field = st.s1.bin >> 3;
+            bin = locate_bin<MW_THREADS, NB2, false>(sh, e_field, a.top_p, target, m_above, c_above, bin_packed);
+            want = ((uint32_t)st.s1.bin << 10) | (uint32_t)bin;
+        }
+        const bool single = (bin_packed >> CNT_SHIFT) == 1;
+        if (sl == 0 && tid == 0) {
+            MwStage &o = PASS == 2 ? st.s1 : st.s2;
+            o.bin_packed = bin_packed; o.target = target; o.m_above = m_above; o.c_above = c_above; o.bin = bin;
+            o.done = single ? 1 : 0;
+            o.tau_bits = ((uint32_t)e_field << 23) | ((uint32_t)bin_packed & 0x7fffffu);
+        }
+        if (single) return;
+        __syncthreads();               // locate_bin's readers of sh.hist are done
+    }
+    constexpr int NB = PASS == 1 ? NB1 : NB2;
+    for (int k = tid; k < NB; k += MW_THREADS) sh.hist[k] = 0ull;
+    __syncthreads();
+    const float *row = a.probs + (int64_t)b * a.stride_b + (int64_t)h * a.stride_h;
+    const bool aligned = (reinterpret_cast<uintptr_t>(row) & 15) == 0;
+    bool bad = false;
+    int p_end = (sl + 1) * w.slice_len;
+    p_end = p_end > len ? len : p_end;
+    for (int p = sl * w.slice_len + tid * 4; p < p_end; p += MW_THREADS * 4) {
+        uint4 u = make_uint4(0, 0, 0, 0);
+        if (p + 3 < len && aligned) {
+            u = *reinterpret_cast<const uint4 *>(row + p);
+        } else {
+            if (p < len) u.x = __float_as_uint(row[p]);
+            if (p + 1 < len) u.y = __float_as_uint(row[p + 1]);
+            if (p + 2 < len) u.z = __float_as_uint(row[p + 2]);
+            if (p + 3 < len) u.w = __float_as_uint(row[p + 3]);
+        }
+        auto visit = [&](uint32_t x) {
+            if (x == 0x80000000u) x = 0u;                               // -0.0 is zero
+            if (x >= 0x7f800000u) { bad = true; return; }               // negative, infinite, NaN
+            if (!x) return;
+            if (PASS == 1) atomicAdd(&sh.hist[x >> 20], packed_entry(x));
+            else if (PASS == 2) { if ((x >> 20) == want) atomicAdd(&sh.hist[(x >> 10) & 1023u], packed_entry(x)); }
+            else { if ((x >> 10) == want) atomicAdd(&sh.hist[x & 1023u], packed_entry(x)); }
+        };
+        visit(u.x); visit(u.y); visit(u.z); visit(u.w);
+    }
+    const bool any_bad = __syncthreads_or(bad ? 1 : 0) != 0;             // also orders the LDS atomics
+    if (PASS == 1 && any_bad && tid == 0) atomicOr(&st.bad, 1);
+    unsigned long long *hg = (PASS == 1 ? w.h1 + (size_t)r * NB1 : PASS == 2 ? w.h2 + (size_t)r * NB2 : w.h3 + (size_t)r * NB2);
+    for (int k = tid; k < NB; k += MW_THREADS) {
+        const unsigned long long v = sh.hist[k];
+        if (v) atomicAdd(&hg[k], v);
+    }
+}
+
+// One workgroup per row: the last locate step, tau*, validity and the boundary flag.
+__global__ __launch_bounds__(MW_THREADS) void mw_final_kernel(MwLaunch w)
+{
+    __shared__ RowShared sh;
+    const SelectLaunch &a = w.a;
+    const int r = blockIdx.x, b = r / a.H_kv, tid = threadIdx.x;
+    const int len = mw_row_len(a, b);
+    const MwState &st = w.state[r];
+    if (st.bad || st.invalid || len == 0) {
+        if (tid == 0) { w.tau[r] = 0.0f; w.valid[r] = 0; w.flags[r] = SPECATTN_ROW_INVALID; }
+        return;
+    }
+    const int e_field = st.s1.bin >> 3;
+    double target = st.s1.target, m_above;
+    unsigned long long bin_packed;
+    uint32_t tau_bits;
+    if (st.s1.done) {
+        tau_bits = st.s1.tau_bits; m_above = st.s1.m_above; bin_packed = st.s1.bin_packed;
+    } else if (st.s2.done) {
+        tau_bits = st.s2.tau_bits; m_above = st.s2.m_above; bin_packed = st.s2.bin_packed;
+    } else {
+        for (int k = tid; k < NB2; k += MW_THREADS) sh.hist[k] = w.h3[(size_t)r * NB2 + k];
+        __syncthreads();
+        m_above = st.s2.m_above;
+        unsigned c_above = st.s2.c_above;
+        const int b3 = locate_bin<MW_THREADS, NB2, false>(sh, e_field, a.top_p, target, m_above, c_above, bin_packed);
+        tau_bits = ((uint32_t)st.s1.bin << 20) | ((uint32_t)st.s2.bin << 10) | (uint32_t)b3;
+    }
+    if (tid == 0) {
+        const double row_sum = target / (double)a.top_p;
+        const double m_incl = m_above + mass_of(bin_packed, e_field), band = 1e-6 * row_sum;
+        w.tau[r] = __uint_as_float(tau_bits);
+        w.valid[r] = 1;
+        w.flags[r] = (fabs(m_incl - target) <= band || fabs(m_above - target) <= band) ? SPECATTN_ROW_NEAR_BOUNDARY : 0u;
+    }
+}
+
+inline size_t mw_align(size_t x) { return (x + 255) & ~(size_t)255; }
+
 // One thread per (row, chunk): the chunk's entries are added up in fp64 in ascending position order and
 // the sum is rounded once to fp32 (Section 4: chunk-granular selection; the score of a chunk is its mass).
 __global__ __launch_bounds__(256) void chunk_mass_kernel(const float *__restrict__ probs, int64_t stride_b,
@@ -512,6 +678,56 @@ specattn_status launch_chunk_masses(const float *probs, int64_t stride_b, int64_
     hipLaunchKernelGGL(chunk_mass_kernel, dim3(grid), dim3(256), 0, stream, probs, stride_b, stride_h, H, n_tokens,
                        seq_lens, chunk_shift, n_chunks, total, mass);
     return check_launch("chunk_mass_kernel");
+}
+
+bool select_multi_wg_preferred(int rows, int n)
+{
+    // One workgroup per row leaves most of the chip idle when there are few rows, and rows beyond 65536
+    // entries do not fit its registers; the split path costs six more launches and re-reads the rows from
+    // L2 in every pass.  Measured crossover: 32 rows at 65536 entries, 64 at 131072, 128 at 262144.
+    return n >= 65536 && (int64_t)rows * 2048 <= n;
+}
+
+size_t select_multi_wg_bytes(int rows, int n)
+{
+    const size_t R = (size_t)rows;
+    return mw_align(R * NB1 * 8) + 2 * mw_align(R * NB2 * 8) + mw_align(R * sizeof(MwState));
+}
+
+// tau / valid / flags of every row by the split path; `scratch` holds select_multi_wg_bytes
+specattn_status launch_select_multi_wg(const SelectLaunch &a, void *scratch, float *tau, int32_t *valid, uint32_t *flags,
+                                       hipStream_t stream)
+{
+    const int rows = a.B * a.H_kv;
+    const size_t R = (size_t)rows;
+    MwLaunch w;
+    w.a = a;
+    char *p = static_cast<char *>(scratch);
+    w.h1 = reinterpret_cast<unsigned long long *>(p); p += mw_align(R * NB1 * 8);
+    w.h2 = reinterpret_cast<unsigned long long *>(p); p += mw_align(R * NB2 * 8);
+    w.h3 = reinterpret_cast<unsigned long long *>(p); p += mw_align(R * NB2 * 8);
+    w.state = reinterpret_cast<MwState *>(p);
+    {
+        const int blocks = (a.n_max + MW_SLICE - 1) / MW_SLICE;
+        int k = (int)((R * blocks + 2 * cu_count() - 1) / (2 * cu_count()));      // blocks per workgroup
+        k = k < 1 ? 1 : (k > 16 ? 16 : k);
+        w.slice_len = k * MW_SLICE;
+        w.slices = (a.n_max + w.slice_len - 1) / w.slice_len;
+    }
+    w.tau = tau; w.valid = valid; w.flags = flags;
+    const size_t words = select_multi_wg_bytes(rows, a.n_max) / 8;
+    hipLaunchKernelGGL(mw_clear_kernel, dim3((unsigned)((words + 1023) / 1024 < 2048 ? (words + 1023) / 1024 : 2048)), dim3(256), 0,
+                       stream, w.h1, words);
+    specattn_status st = check_launch("mw_clear_kernel");
+    if (st != SPECATTN_OK) return st;
+    const dim3 grid((unsigned)(R * w.slices));
+    hipLaunchKernelGGL(mw_pass_kernel<1>, grid, dim3(MW_THREADS), 0, stream, w);
+    hipLaunchKernelGGL(mw_pass_kernel<2>, grid, dim3(MW_THREADS), 0, stream, w);
+    hipLaunchKernelGGL(mw_pass_kernel<3>, grid, dim3(MW_THREADS), 0, stream, w);
+    st = check_launch("mw_pass_kernel");
+    if (st != SPECATTN_OK) return st;
+    hipLaunchKernelGGL(mw_final_kernel, dim3(rows), dim3(MW_THREADS), 0, stream, w);
+    return check_launch("mw_final_kernel");
 }
 
 specattn_status launch_select(const SelectLaunch &a, hipStream_t stream)

@@ -34,8 +34,10 @@ def kv_tensors(w: W.Workload):
 
 
 def gpu_select(probs: np.ndarray, top_p: float, *, seq_lens=None, capacity=None, page_table=None,
-               page_size=0, emit_physical=False, probs_dev=None):
-    """Run specattn_topp_select; returns dict of numpy results (+ device tensors)."""
+               page_size=0, emit_physical=False, probs_dev=None, split=True):
+    """Run specattn_topp_select; returns dict of numpy results (+ device tensors).
+
+    split: hand over the optional workspace, with which few long rows are split over many workgroups."""
     p = dev(probs) if probs_dev is None else probs_dev
     B, H, n = p.shape
     R = B * H
@@ -48,11 +50,13 @@ def gpu_select(probs: np.ndarray, top_p: float, *, seq_lens=None, capacity=None,
     pt = None if page_table is None else dev(np.asarray(page_table, dtype=np.int32))
     args = sa.select_args(p, top_p, indices=idx, counts=counts, thresholds=tau, row_flags=flags,
                           seq_lens=sl, page_table=pt, page_size=page_size, emit_physical=emit_physical)
-    sa.specattn_topp_select(args)
+    need = sa.specattn_workspace_size(args, None) if split else 0
+    ws = sa.alloc_workspace(need) if need else None
+    sa.specattn_topp_select(args, ws)
     torch.cuda.synchronize()
     return dict(indices=idx.cpu().numpy(), counts=counts.cpu().numpy(), tau=tau.cpu().numpy(),
                 flags=flags.cpu().numpy().astype(np.uint32), d_indices=idx, d_counts=counts,
-                d_tau=tau, keep=(p, sl, pt))
+                d_tau=tau, keep=(p, sl, pt), split=bool(need))
 
 
 def compare_select(got: dict, ref: oracle.SelectResult, *, capacity=None, to_physical=None):

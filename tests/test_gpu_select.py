@@ -183,3 +183,54 @@ def test_near_boundary_flag_matches_oracle_on_clear_rows():
     row = np.array([0.5, 0.25, 0.125, 0.0625, 0.0625], dtype=np.float32).reshape(1, 1, 5)
     assert gpu_select(row, 0.5)["flags"][0] & sa.ROW_NEAR_BOUNDARY
     assert not gpu_select(row, 0.6)["flags"][0] & sa.ROW_NEAR_BOUNDARY
+
+
+# ---- few long rows: the split path (each row over many workgroups) against the oracle and the one-workgroup path
+@pytest.mark.parametrize("rows,n", [(1, 65536), (8, 66000), (3, 70001), (2, 200000), (32, 131072), (64, 131072)])
+def test_split_path_matches_oracle_and_single_path(rows, n):
+    rng = np.random.default_rng(rows * 7 + n)
+    probs = W.draft_probs(rng, rows, n).reshape(1, rows, n)
+    got = gpu_select(probs, 0.9)
+    assert got["split"], "this shape is expected to take the split path"
+    ref = oracle.topp_select(probs.reshape(rows, n), 0.9)
+    flagged, mism = compare_select(got, ref)
+    assert mism == 0
+    one = gpu_select(probs, 0.9, split=False)
+    assert np.array_equal(got["counts"], one["counts"]) and np.array_equal(got["tau"], one["tau"])
+    assert np.array_equal(got["flags"], one["flags"])
+    for r in range(rows):
+        assert np.array_equal(got["indices"][r, :got["counts"][r]], one["indices"][r, :one["counts"][r]])
+
+
+def test_split_path_edge_rows():
+    n = 66000
+    rng = np.random.default_rng(77)
+    probs = W.draft_probs(rng, 8, n).reshape(2, 4, n)
+    lens = np.array([n, 20001], dtype=np.int32)
+    probs[1] = W.draft_probs(rng, 4, n, lens=np.full(4, 20001))
+    probs[0, 0, :] = 0.0; probs[0, 0, 12345] = 1.0            # one entry holds everything (single-entry bins)
+    probs[0, 1, :] = np.float32(1.0 / n)                      # all tied: the boundary bin holds the whole row
+    probs[0, 2, 777] = np.nan                                 # invalid
+    probs[0, 3, :] = 0.0                                      # no mass
+    probs[1, 0, 5:15000] = 0.0                                # long run of zeros
+    probs[1, 1, 100] = -0.0
+    for p in (0.5, 0.9, 1.0):
+        got = gpu_select(probs, p, seq_lens=lens, capacity=50000)
+        assert got["split"]
+        ref = oracle.topp_select(probs.reshape(8, n), p, lens=np.repeat(lens, 4))
+        flagged, mism = compare_select(got, ref, capacity=50000)
+        assert mism == 0 or p == 1.0
+        assert got["counts"][0] == 1 and got["counts"][1] == n
+        assert got["flags"][2] & sa.ROW_INVALID and got["flags"][3] & sa.ROW_INVALID
+        assert got["flags"][1] & sa.ROW_OVERFLOW
+
+
+def test_split_path_paged_physical_output():
+    w = W.ragged_paged(seed=15, B=2, len_lo=70000, len_hi=90000, with_kv=False)
+    got = gpu_select(w.probs, 0.95, seq_lens=w.seq_lens, page_table=w.page_table, page_size=W.PAGE_SIZE, emit_physical=True)
+    assert got["split"]
+    B, H, n = w.probs.shape
+    ref = oracle.topp_select(w.probs.reshape(B * H, n), 0.95, lens=w.row_lens())
+    to_phys = lambda r, pos: w.page_table[r // H, pos // W.PAGE_SIZE] * W.PAGE_SIZE + pos % W.PAGE_SIZE
+    flagged, mism = compare_select(got, ref, to_physical=to_phys)
+    assert mism == 0
