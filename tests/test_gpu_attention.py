@@ -103,6 +103,9 @@ def test_ragged_list_lengths(count):
 @pytest.mark.parametrize("shape", [
     dict(H_q=8, H_kv=8, T=1, d=128), dict(H_q=16, H_kv=2, T=8, d=128), dict(H_q=8, H_kv=2, T=5, d=64),
     dict(H_q=4, H_kv=4, T=3, d=64, dtype="f32"), dict(H_q=8, H_kv=4, T=5, d=128, dtype="f32"),
+    # query rows per kv head at and around the matrix-core kernel's tile sizes (16 and 32)
+    dict(H_q=8, H_kv=2, T=8, d=128), dict(H_q=4, H_kv=2, T=8, d=128), dict(H_q=6, H_kv=2, T=7, d=128),
+    dict(H_q=2, H_kv=2, T=5, d=128), dict(H_q=34, H_kv=2, T=1, d=128), dict(H_q=22, H_kv=2, T=3, d=128),
 ])
 def test_other_shapes_and_dtypes(shape):
     w = W.llama8b_layer(seed=6, B=2, n=1300, **shape)
