@@ -30,8 +30,17 @@ constexpr int CNT_SHIFT = 44;                 // counter = count << 44 | sum of 
 constexpr unsigned long long CNT_ONE = 1ull << CNT_SHIFT;
 constexpr unsigned long long SIG_MASK = CNT_ONE - 1;
 
+struct LocSlot {                 // a candidate outcome of one locate step
+    unsigned long long packed;
+    double m_above;
+    unsigned c_above;
+    int bin;
+};
+
 struct RowShared {
     unsigned long long hist[NB1];
+    LocSlot loc[16], loc_low[16];
+    int loc_state[16];
     double wave_m[16];
     unsigned wave_c[16];
     unsigned wave_tot[2][16];
@@ -61,12 +70,37 @@ __device__ __forceinline__ double mass_of(unsigned long long packed, int e_field
     return s * __hiloint2double((1023 + e) << 20, 0);
 }
 
+// Cross-lane moves on the vector ALU (no LDS traffic): lanes without a source lane receive 0.
+template <int CTRL, int ROW_MASK> __device__ __forceinline__ int dpp_int(int v)
+{
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, ROW_MASK, 0xf, false);
+}
+template <int CTRL, int ROW_MASK> __device__ __forceinline__ double dpp_double(double v)
+{
+    return __hiloint2double(dpp_int<CTRL, ROW_MASK>(__double2hiint(v)), dpp_int<CTRL, ROW_MASK>(__double2loint(v)));
+}
+// Inclusive prefix sums over the 64 lanes of a wave: shifts by 1, 2, 4, 8 inside each row of 16 lanes, then
+// lane 15 of rows 0 and 2 into rows 1 and 3, then lane 31 into rows 2 and 3.
+__device__ __forceinline__ void wave_prefix(double &m, unsigned &c)
+{
+#define SPECATTN_SCAN_STEP(CTRL, RM) \
+    do { m += dpp_double<CTRL, RM>(m); c += (unsigned)dpp_int<CTRL, RM>((int)c); } while (0)
+    SPECATTN_SCAN_STEP(0x111, 0xf);    // row_shr:1
+    SPECATTN_SCAN_STEP(0x112, 0xf);    // row_shr:2
+    SPECATTN_SCAN_STEP(0x114, 0xf);    // row_shr:4
+    SPECATTN_SCAN_STEP(0x118, 0xf);    // row_shr:8
+    SPECATTN_SCAN_STEP(0x142, 0xa);    // row_bcast:15 into rows 1 and 3
+    SPECATTN_SCAN_STEP(0x143, 0xc);    // row_bcast:31 into rows 2 and 3
+#undef SPECATTN_SCAN_STEP
+}
+
 // One radix pass decision.  hist[0..NB) holds the packed counters of this pass.
 // On return (uniform over the block): bin = highest non-empty bin b with
 // m_above + mass(bins >= b) >= target (lowest non-empty bin if rounding leaves none),
 // and m_above / c_above advanced to cover the bins above it.
-// Two levels: every wave sums its own bins; all threads walk the few wave totals from the top to
-// find the wave that holds the boundary; only that wave looks at single bins.
+// Threads own bins from the top down (thread 0 the highest BPT bins), so "the bins above mine" is a
+// prefix over threads: a wave-wide scan, the wave totals through LDS, and every thread knows the mass
+// above its own bins; the one thread whose bins hold the boundary finds it among them.
 template <int THREADS, int NB, bool FIRST>
 __device__ __forceinline__ int locate_bin(RowShared &sh, int e_field_fixed, float top_p, double &target,
                                           double &m_above, unsigned &c_above,
@@ -76,94 +110,74 @@ __device__ __forceinline__ int locate_bin(RowShared &sh, int e_field_fixed, floa
     constexpr int BPT = NB / THREADS;
     static_assert(BPT >= 1, "more threads than bins");
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int b0 = threadIdx.x * BPT;
+    const int top = NB - 1 - (int)threadIdx.x * BPT;           // this thread's highest bin
     double lm = 0.0;
     unsigned lc = 0;
     double mass[BPT];
-    unsigned cnt[BPT];
+    unsigned long long h[BPT];
 #pragma unroll
     for (int j = 0; j < BPT; ++j) {
-        const unsigned long long h = sh.hist[b0 + j];
-        const int e = FIRST ? ((b0 + j) >> 3) : e_field_fixed;
-        mass[j] = mass_of(h, e);
-        cnt[j] = (unsigned)(h >> CNT_SHIFT);
+        h[j] = sh.hist[top - j];
+        const int e = FIRST ? ((top - j) >> 3) : e_field_fixed;
+        mass[j] = mass_of(h[j], e);
         lm += mass[j];
-        lc += cnt[j];
+        lc += (unsigned)(h[j] >> CNT_SHIFT);
     }
-    double wm = lm;
-    unsigned wc = lc;
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {          // butterfly: every lane ends with the wave total
-        wm += __shfl_xor(wm, off, 64);
-        wc += __shfl_xor(wc, off, 64);
-    }
-    if (lane == 0) { sh.wave_m[wave] = wm; sh.wave_c[wave] = wc; }
+    double incl_m = lm;
+    unsigned incl_c = lc;
+    wave_prefix(incl_m, incl_c);
+    if (lane == 63) { sh.wave_m[wave] = incl_m; sh.wave_c[wave] = incl_c; }
+    // mass and count of the lanes before this one (wave_shr:1)
+    double above = dpp_double<0x138, 0xf>(incl_m);
+    unsigned above_c = (unsigned)dpp_int<0x138, 0xf>((int)incl_c);
     __syncthreads();
     double total = 0.0;
 #pragma unroll
-    for (int w = NW - 1; w >= 0; --w) total += sh.wave_m[w];
+    for (int w = 0; w < NW; ++w) {
+        const double wm = sh.wave_m[w];
+        if (w < wave) { above += wm; above_c += sh.wave_c[w]; }
+        total += wm;
+    }
     if (FIRST) target = (double)top_p * total;     // Algorithm 2: M_target = p * sum a
     if (FIRST && !(total > 0.0)) return -1;        // no mass at all (uniform decision)
 
-    int wb = -1, wlow = -1;                        // wave holding the boundary; lowest non-empty wave
-    double run_w = 0.0, above_w = 0.0;
-    unsigned runc_w = 0, abovec_w = 0;
+    int mine = -1, low = -1;                       // boundary bin / lowest non-empty bin among this thread's
+    double run = above, mine_above = 0.0, low_above = 0.0;
+    unsigned runc = above_c, mine_c = 0, low_c = 0;
+    unsigned long long mine_h = 0, low_h = 0;
 #pragma unroll
-    for (int w = NW - 1; w >= 0; --w) {
-        const double m = sh.wave_m[w];
-        const unsigned c = sh.wave_c[w];
-        if (c) {
-            wlow = w;
-            if (wb < 0 && (m_above + (run_w + m)) >= target) { wb = w; above_w = run_w; abovec_w = runc_w; }
+    for (int j = 0; j < BPT; ++j) {
+        const unsigned cj = (unsigned)(h[j] >> CNT_SHIFT);
+        if (cj) {
+            low = top - j; low_above = run; low_c = runc; low_h = h[j];
+            if (mine < 0 && (m_above + (run + mass[j])) >= target) { mine = top - j; mine_above = run; mine_c = runc; mine_h = h[j]; }
         }
-        if (wb < 0) { run_w += m; runc_w += c; }
+        run += mass[j];
+        runc += cj;
     }
-    if (wb < 0) {                                  // rounding left no wave: take the lowest bins
-        wb = wlow;
-        above_w = run_w - sh.wave_m[wlow];
-        abovec_w = runc_w - sh.wave_c[wlow];
+    // per wave: the first lane (highest bins) that holds a boundary, and the last lane with any entry
+    const unsigned long long has_mine = __ballot(mine >= 0), has_low = __ballot(low >= 0);
+    if (has_mine && lane == __ffsll((unsigned long long)has_mine) - 1) {
+        sh.loc[wave].bin = mine; sh.loc[wave].m_above = mine_above; sh.loc[wave].c_above = mine_c; sh.loc[wave].packed = mine_h;
     }
-    if (wave == wb) {
-        double im = lm;                            // suffix sums over the lanes of this wave
-        unsigned ic = lc;
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            const double om = __shfl_down(im, off, 64);
-            const unsigned oc = __shfl_down(ic, off, 64);
-            if (lane + off < 64) { im += om; ic += oc; }
-        }
-        const double nm = __shfl_down(im, 1, 64);
-        const unsigned nc = __shfl_down(ic, 1, 64);
-        const double excl_m = above_w + (lane < 63 ? nm : 0.0);
-        const unsigned excl_c = abovec_w + (lane < 63 ? nc : 0u);
-        int mine = -1, low = -1;
-        double run = excl_m, mine_above = 0.0, low_above = 0.0;
-        unsigned runc = excl_c, mine_c = 0, low_c = 0;
-#pragma unroll
-        for (int j = BPT - 1; j >= 0; --j) {
-            if (cnt[j]) {
-                low = b0 + j; low_above = run; low_c = runc;
-                if (mine < 0 && (m_above + (run + mass[j])) >= target) { mine = b0 + j; mine_above = run; mine_c = runc; }
-            }
-            run += mass[j];
-            runc += cnt[j];
-        }
-        const unsigned long long has_mine = __ballot(mine >= 0), has_low = __ballot(low >= 0);
-        // the boundary is in the highest lane that found one; else the lowest non-empty bin of the wave
-        const int owner = has_mine ? 63 - __clzll(has_mine) : __ffsll((unsigned long long)has_low) - 1;
-        if (lane == owner) {
-            const int bin = has_mine ? mine : low;
-            sh.best = bin;
-            sh.m_above = m_above + (has_mine ? mine_above : low_above);
-            sh.c_above = c_above + (has_mine ? mine_c : low_c);
-            sh.bin_packed = sh.hist[bin];
-        }
+    if (has_low && lane == 63 - __clzll(has_low)) {
+        sh.loc_low[wave].bin = low; sh.loc_low[wave].m_above = low_above; sh.loc_low[wave].c_above = low_c; sh.loc_low[wave].packed = low_h;
     }
+    if (lane == 0) sh.loc_state[wave] = (has_mine ? 1 : 0) | (has_low ? 2 : 0);
     __syncthreads();
-    m_above = sh.m_above;
-    c_above = sh.c_above;
-    bin_packed = sh.bin_packed;
-    return sh.best;
+    int pick = -1, pick_low = -1;                  // first wave with a boundary; last wave with any entry
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+        const int st = sh.loc_state[w];
+        if (pick < 0 && (st & 1)) pick = w;
+        if (st & 2) pick_low = w;
+    }
+    const LocSlot &slot = pick >= 0 ? sh.loc[pick] : sh.loc_low[pick_low];
+    const int bin = slot.bin;
+    m_above += slot.m_above;
+    c_above += slot.c_above;
+    bin_packed = slot.packed;
+    return bin;
 }
 
 template <int THREADS, int NB>
