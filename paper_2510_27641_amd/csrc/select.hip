@@ -39,7 +39,7 @@ struct LocSlot {                 // a candidate outcome of one locate step
 
 struct RowShared {
     unsigned long long hist[NB1];
-    LocSlot loc[16], loc_low[16];
+    LocSlot loc[16];
     int loc_state[16];
     double wave_m[16];
     unsigned wave_c[16];
@@ -141,38 +141,61 @@ __device__ __forceinline__ int locate_bin(RowShared &sh, int e_field_fixed, floa
     if (FIRST) target = (double)top_p * total;     // Algorithm 2: M_target = p * sum a
     if (FIRST && !(total > 0.0)) return -1;        // no mass at all (uniform decision)
 
-    int mine = -1, low = -1;                       // boundary bin / lowest non-empty bin among this thread's
-    double run = above, mine_above = 0.0, low_above = 0.0;
-    unsigned runc = above_c, mine_c = 0, low_c = 0;
-    unsigned long long mine_h = 0, low_h = 0;
+    // Masses are non-negative, so the running sum over a thread's bins never decreases: the thread holds a
+    // feasible non-empty bin exactly if the sum after its last bin reaches the target.
+    double run_end = above;
 #pragma unroll
-    for (int j = 0; j < BPT; ++j) {
-        const unsigned cj = (unsigned)(h[j] >> CNT_SHIFT);
-        if (cj) {
-            low = top - j; low_above = run; low_c = runc; low_h = h[j];
-            if (mine < 0 && (m_above + (run + mass[j])) >= target) { mine = top - j; mine_above = run; mine_c = runc; mine_h = h[j]; }
+    for (int j = 0; j < BPT; ++j) run_end += mass[j];
+    const bool holds = lc > 0 && (m_above + run_end) >= target;
+    const unsigned long long has = __ballot(holds);
+    // per wave: the first lane (highest bins) that holds a feasible bin looks for the highest one among its own
+    if (has && lane == __ffsll((unsigned long long)has) - 1) {
+        double run = above;
+        unsigned runc = above_c;
+        bool found = false;
+#pragma unroll
+        for (int j = 0; j < BPT; ++j) {
+            const unsigned cj = (unsigned)(h[j] >> CNT_SHIFT);
+            if (!found && cj && (m_above + (run + mass[j])) >= target) {
+                found = true;
+                sh.loc[wave].bin = top - j; sh.loc[wave].m_above = run; sh.loc[wave].c_above = runc; sh.loc[wave].packed = h[j];
+            }
+            run += mass[j];
+            runc += cj;
         }
-        run += mass[j];
-        runc += cj;
     }
-    // per wave: the first lane (highest bins) that holds a boundary, and the last lane with any entry
-    const unsigned long long has_mine = __ballot(mine >= 0), has_low = __ballot(low >= 0);
-    if (has_mine && lane == __ffsll((unsigned long long)has_mine) - 1) {
-        sh.loc[wave].bin = mine; sh.loc[wave].m_above = mine_above; sh.loc[wave].c_above = mine_c; sh.loc[wave].packed = mine_h;
-    }
-    if (has_low && lane == 63 - __clzll(has_low)) {
-        sh.loc_low[wave].bin = low; sh.loc_low[wave].m_above = low_above; sh.loc_low[wave].c_above = low_c; sh.loc_low[wave].packed = low_h;
-    }
-    if (lane == 0) sh.loc_state[wave] = (has_mine ? 1 : 0) | (has_low ? 2 : 0);
+    if (lane == 0) sh.loc_state[wave] = has ? 1 : 0;
     __syncthreads();
-    int pick = -1, pick_low = -1;                  // first wave with a boundary; last wave with any entry
+    int pick = -1;                                 // first wave with a feasible bin
 #pragma unroll
-    for (int w = 0; w < NW; ++w) {
-        const int st = sh.loc_state[w];
-        if (pick < 0 && (st & 1)) pick = w;
-        if (st & 2) pick_low = w;
+    for (int w = NW - 1; w >= 0; --w)
+        if (sh.loc_state[w]) pick = w;
+    if (pick < 0) {
+        // Rounding left no feasible bin (the row total itself fell short of the target by an ulp): take the
+        // lowest non-empty bin.  Uniform over the block, and rare.
+        int low = -1;
+        double run = above, low_above = 0.0;
+        unsigned runc = above_c, low_c = 0;
+        unsigned long long low_h = 0;
+#pragma unroll
+        for (int j = 0; j < BPT; ++j) {
+            const unsigned cj = (unsigned)(h[j] >> CNT_SHIFT);
+            if (cj) { low = top - j; low_above = run; low_c = runc; low_h = h[j]; }
+            run += mass[j];
+            runc += cj;
+        }
+        const unsigned long long has_low = __ballot(low >= 0);
+        if (has_low && lane == 63 - __clzll(has_low)) {
+            sh.loc[wave].bin = low; sh.loc[wave].m_above = low_above; sh.loc[wave].c_above = low_c; sh.loc[wave].packed = low_h;
+        }
+        __syncthreads();                           // every thread has read loc_state
+        if (lane == 0) sh.loc_state[wave] = has_low ? 1 : 0;
+        __syncthreads();
+#pragma unroll
+        for (int w = 0; w < NW; ++w)
+            if (sh.loc_state[w]) pick = w;         // last wave (lowest bins) with any entry
     }
-    const LocSlot &slot = pick >= 0 ? sh.loc[pick] : sh.loc_low[pick_low];
+    const LocSlot &slot = sh.loc[pick];
     const int bin = slot.bin;
     m_above += slot.m_above;
     c_above += slot.c_above;
