@@ -114,6 +114,10 @@ typedef struct specattn_select_args {
  * A row with count 0 gives out = 0 and lse = -inf.  Accumulation is fp32;
  * `out` is fp32 whatever the input dtype.
  *
+ * Shapes: bf16 with d = 128 runs on the matrix cores for any G = H_q / H_kv (up to 32 query rows
+ * G*T per pass; larger groups are taken in equal shares of heads, each streaming the kept K/V
+ * again).  fp32, and d = 64, run on a portable kernel limited to G*T <= 64.
+ *
  * Dense layers (Section 4 keeps the first layers of the verifier dense): with
  * indices == NULL and counts == NULL every position below seq_lens[b] (n_max
  * when seq_lens is NULL) is attended to, through the same kernels, without
@@ -211,7 +215,7 @@ specattn_status specattn_sparse_decode_attn(const specattn_attn_args *attn, void
  * workgroups re-derive their share of the list from `probs` on chip.
  * sel->indices is ignored; attn->indices / attn->counts are ignored
  * (sel->counts is written and used).  attn->workspace serves both phases.
- * Supported for bf16, d = 128, G*T <= 32, contiguous or page-table layouts
+ * Supported for bf16, d = 128, contiguous or page-table layouts
  * (SPECATTN_EUNSUPPORTED otherwise).
  */
 specattn_status specattn_fused(const specattn_select_args *sel, const specattn_attn_args *attn,

@@ -86,7 +86,7 @@ specattn_status check_attn(const specattn_attn_args *a, bool fused)
     if (a->H_q % a->H_kv) { set_error("H_q is not a multiple of H_kv"); return SPECATTN_ESHAPE; }
     if (a->T > SPECATTN_MAX_T) { set_error("T exceeds %d", SPECATTN_MAX_T); return SPECATTN_ESHAPE; }
     if (a->d != 64 && a->d != 128) { set_error("d must be 64 or 128"); return SPECATTN_ESHAPE; }
-    if ((a->H_q / a->H_kv) * a->T > 64) { set_error("G*T exceeds 64 query rows per kv head"); return SPECATTN_ESHAPE; }
+    if ((a->H_q / a->H_kv) * a->T > 64 && !(a->dtype == SPECATTN_BF16 && a->d == 128)) { set_error("G*T exceeds 64 query rows per kv head (only bf16 with d = 128 takes more)"); return SPECATTN_ESHAPE; }
     if (!fused && !dense && a->idx_capacity < 1) { set_error("idx_capacity must be at least 1"); return SPECATTN_ESHAPE; }
     if (!fused && !dense && a->idx_stride_row < a->idx_capacity) { set_error("idx_stride_row is smaller than idx_capacity"); return SPECATTN_ESHAPE; }
     const bool paged = a->page_table != nullptr || a->indices_are_physical;

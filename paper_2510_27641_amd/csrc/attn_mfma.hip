@@ -290,7 +290,7 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
     const int c0 = blockIdx.x * share;
     const int c1 = (c0 + share) < total ? (c0 + share) : total;
     if (c0 >= c1) return;
-    const int G = a.H_q / a.H_kv;
+    const int G = attn_group_heads(a);
     const int QT = G * a.T;
     const float scale2 = a.sm_scale * 1.4426950408889634f;            // scores in log2 units
 
@@ -333,7 +333,7 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
         if (qi < QT) {
             const int gh = qi / a.T, tt = qi - gh * a.T;
             const uint16_t *qp = static_cast<const uint16_t *>(a.q) + (int64_t)b * a.q_stride_b +
-                                 (int64_t)(h * G + gh) * a.q_stride_h + (int64_t)tt * a.q_stride_t;
+                                 (int64_t)attn_query_head(a, h, gh) * a.q_stride_h + (int64_t)tt * a.q_stride_t;
             q_pf = *reinterpret_cast<const u32x4 *>(qp + ch * 8);
         }
     };
@@ -721,7 +721,7 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
                 if (q < QT) {
                     if (w0 == w1 && !a.k_new) {
                         const int gh = q / a.T, tt = q - gh * a.T;
-                        const int64_t orow = ((int64_t)b * a.H_q + (h * G + gh)) * a.T + tt;
+                        const int64_t orow = ((int64_t)b * a.H_q + attn_query_head(a, h, gh)) * a.T + tt;
                         *reinterpret_cast<f32x4 *>(a.out + orow * D + 16 * t + 4 * g) =
                             l > 0.0f ? acc / l : (f32x4){0.f, 0.f, 0.f, 0.f};
                         if (a.lse && g == 0 && t == 0)
@@ -746,13 +746,13 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
 __global__ void merge_partials_kernel(AttnLaunch a, Plan plan, int qtp)
 {
     __shared__ float red[2 * SPECATTN_MAX_T];
-    const int G = a.H_q / a.H_kv;
+    const int G = attn_group_heads(a);
     const int QT = G * a.T;
     const int rows = a.B * a.H_kv;
     const int r = blockIdx.x / QT, q = blockIdx.x - r * QT;
     const int b = r / a.H_kv, h = r - b * a.H_kv;
     const int gh = q / a.T, t = q - gh * a.T;
-    const int64_t orow = ((int64_t)b * a.H_q + (h * G + gh)) * a.T + t;
+    const int64_t orow = ((int64_t)b * a.H_q + attn_query_head(a, h, gh)) * a.T + t;
     const int dv = threadIdx.x;
     const bool tail = a.k_new != nullptr;
     const int total = plan.cost_prefix[rows];
@@ -783,7 +783,7 @@ __global__ void merge_partials_kernel(AttnLaunch a, Plan plan, int qtp)
     }
     if (tail) {
         float dots[SPECATTN_MAX_T];
-        tail_dots(a, b, h * G + gh, t, red, dots);
+        tail_dots(a, b, attn_query_head(a, h, gh), t, red, dots);
         const float scale2 = a.sm_scale * 1.4426950408889634f;       // m is in log2 units
         const int64_t noff = ((int64_t)b * a.H_kv + h) * a.T * D;
 #pragma unroll
@@ -799,8 +799,8 @@ __global__ void merge_partials_kernel(AttnLaunch a, Plan plan, int qtp)
 
 bool attn_mfma_supported(const AttnLaunch &a)
 {
-    const int G = a.H_q / a.H_kv;
-    return a.dtype == SPECATTN_BF16 && a.d == 128 && G * a.T <= 32 && a.H_kv <= MAX_ROWS;
+    // any number of query heads per kv head: groups of more than 32 query rows run as several launches
+    return a.dtype == SPECATTN_BF16 && a.d == 128 && a.T <= 32 && a.H_kv <= MAX_ROWS;
 }
 
 int attn_mfma_workgroups() { return cu_count(); }
@@ -818,7 +818,7 @@ size_t attn_mfma_workspace_bytes(int rows, int G, int T)
 static specattn_status launch_chunk(const AttnLaunch &a, hipStream_t stream)
 {
     const int rows = a.B * a.H_kv;
-    const int G = a.H_q / a.H_kv;
+    const int G = a.g_count ? a.g_count : a.H_q / a.H_kv;
     const int QT = G * a.T;
     const int qtp = QT <= 16 ? 16 : 32;
     Plan plan;
@@ -878,7 +878,28 @@ static specattn_status launch_chunk(const AttnLaunch &a, hipStream_t stream)
 
 // Batches with more rows than the kernel's LDS tables hold go out as several launches over
 // consecutive sequences (rows are independent; the workspace is reused, the stream orders them).
+// Likewise the query heads of a kv head: at most 32 query rows (heads x T) fit one launch, larger groups
+// are cut into equal shares of heads, each streaming the kept K/V again.
+static specattn_status launch_batch(const AttnLaunch &a, hipStream_t stream);
+
 specattn_status launch_attn_mfma(const AttnLaunch &a, hipStream_t stream)
+{
+    const int G = a.H_q / a.H_kv;
+    if (G * a.T <= 32) return launch_batch(a, stream);
+    const int per_launch = 32 / a.T;
+    const int shares = (G + per_launch - 1) / per_launch;
+    const int heads = (G + shares - 1) / shares;
+    for (int g0 = 0; g0 < G; g0 += heads) {
+        AttnLaunch c = a;
+        c.g_first = g0;
+        c.g_count = (G - g0) < heads ? (G - g0) : heads;
+        const specattn_status st = launch_batch(c, stream);
+        if (st != SPECATTN_OK) return st;
+    }
+    return SPECATTN_OK;
+}
+
+static specattn_status launch_batch(const AttnLaunch &a, hipStream_t stream)
 {
     const int b_max = MAX_ROWS / a.H_kv;
     if (a.B <= b_max) return launch_chunk(a, stream);

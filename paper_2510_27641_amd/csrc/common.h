@@ -93,6 +93,8 @@ struct AttnLaunch {
     int dense;               // 1: no list; every position below the sequence length is attended to
     int chunk_shift;         // > 0: list entries are chunk numbers of 1 << chunk_shift positions each
     const void *k_new, *v_new;   // [B][H_kv][T][d] new tokens behind the cache, or null
+    int g_first, g_count;        // this launch handles query heads g_first .. g_first + g_count - 1 of every kv head's
+                                 // group (g_count 0: all of them)
     float *out;
     float *lse;              // may be null
     void *workspace;
@@ -105,6 +107,13 @@ struct AttnLaunch {
     const int32_t *block_counts;
     int blocks_per_row;
 };
+__device__ __forceinline__ int attn_group_heads(const AttnLaunch &a) { return a.g_count ? a.g_count : a.H_q / a.H_kv; }
+// query head behind head gh of this launch's share of kv head h's group
+__device__ __forceinline__ int attn_query_head(const AttnLaunch &a, int h, int gh)
+{
+    return h * (a.H_q / a.H_kv) + a.g_first + gh;
+}
+
 // Number of positions row r attends to: the kept count (clamped to the list capacity), or the
 // sequence length when there is no list.  With a chunk list: the kept chunks' positions, less the
 // part of the last kept chunk that lies past the sequence length (the list is ascending, so only

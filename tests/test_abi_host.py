@@ -71,7 +71,7 @@ def test_select_argument_errors(kw, status):
 @pytest.mark.parametrize("kw,status", [
     (dict(q=None), sa.EINVAL), (dict(out=None), sa.EINVAL), (dict(indices=None), sa.EINVAL),
     (dict(H_q=30), sa.ESHAPE), (dict(T=9), sa.ESHAPE), (dict(d=96), sa.ESHAPE), (dict(dtype=7), sa.EUNSUPPORTED),
-    (dict(H_q=128, T=8), sa.ESHAPE), (dict(k=0x2004), sa.EALIGN), (dict(kv_stride_n=132), sa.EALIGN),
+    (dict(H_q=128, T=8, dtype=sa.F32, kv_stride_n=128), sa.ESHAPE), (dict(k=0x2004), sa.EALIGN), (dict(kv_stride_n=132), sa.EALIGN),
     (dict(kv_stride_n=64), sa.ESHAPE), (dict(idx_capacity=0), sa.ESHAPE),
     (dict(page_table=0x9000, page_size=10, max_pages_per_seq=1000, kv_stride_page=8 * 16 * 128), sa.ESHAPE),
     (dict(page_table=0x9000, page_size=16, max_pages_per_seq=1000, kv_stride_page=0), sa.ESHAPE),

@@ -106,6 +106,8 @@ def test_ragged_list_lengths(count):
     # query rows per kv head at and around the matrix-core kernel's tile sizes (16 and 32)
     dict(H_q=8, H_kv=2, T=8, d=128), dict(H_q=4, H_kv=2, T=8, d=128), dict(H_q=6, H_kv=2, T=7, d=128),
     dict(H_q=2, H_kv=2, T=5, d=128), dict(H_q=34, H_kv=2, T=1, d=128), dict(H_q=22, H_kv=2, T=3, d=128),
+    # more than 32 query rows per kv head: the matrix-core kernel takes the heads in equal shares
+    dict(H_q=64, H_kv=8, T=5, d=128), dict(H_q=32, H_kv=2, T=8, d=128), dict(H_q=14, H_kv=2, T=5, d=128),
 ])
 def test_other_shapes_and_dtypes(shape):
     w = W.llama8b_layer(seed=6, B=2, n=1300, **shape)

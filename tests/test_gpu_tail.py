@@ -133,3 +133,14 @@ def test_paged_with_new_tokens():
         out, _ = run(w, k_new, v_new, mode=mode, seq_lens=w.seq_lens, page_table=w.page_table)
         o_ref, _ = reference(w, k_new, v_new, mode)
         assert row_rel_err(out, o_ref) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("mode", ["sparse", "fused"])
+def test_eight_query_heads_per_kv_head(mode):
+    # 40 query rows per kv head: the matrix-core kernel runs the heads in two shares; the new tokens join in the merge
+    w = W.llama8b_layer(seed=61, B=2, n=3000, top_p=0.9, H_q=64, H_kv=8)
+    k_new, v_new = new_tokens(w, 62)
+    out, lse = run(w, k_new, v_new, mode=mode)
+    o_ref, l_ref = reference(w, k_new, v_new, mode)
+    assert row_rel_err(out, o_ref) <= TOL["bf16"]
+    assert np.abs(lse - l_ref).max() <= 1e-3
