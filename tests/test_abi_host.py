@@ -148,3 +148,32 @@ def test_union_workspace_size():
     assert small > 0 and small % 256 == 0
     assert sa.specattn_union_workspace_size(_union(S=8)) > small
     assert sa.specattn_union_workspace_size(_union(H_kv=3)) == 0
+
+
+def test_header_is_plain_c(tmp_path):
+    """The public header must compile as C (no C++ constructs), and a C caller must link against the library."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no C compiler")
+    src = tmp_path / "caller.c"
+    src.write_text(
+        '#include "specattn.h"\n'
+        "#include <stdio.h>\n"
+        "int main(void) {\n"
+        "    specattn_select_args s = {0};\n"
+        "    specattn_attn_args a = {0};\n"
+        "    specattn_union_args u = {0};\n"
+        "    /* NULL arguments are rejected on the host: nothing is launched */\n"
+        "    int r1 = specattn_topp_select(&s, NULL, 0, NULL);\n"
+        "    int r2 = specattn_sparse_decode_attn(&a, NULL);\n"
+        "    int r3 = specattn_topp_select_union(&u, NULL, 0, NULL);\n"
+        '    printf("%d %d %d %d %s\\n", r1, r2, r3, specattn_version(), specattn_last_error());\n'
+        "    return (r1 == SPECATTN_EINVAL && r2 == SPECATTN_EINVAL && r3 == SPECATTN_EINVAL) ? 0 : 1;\n"
+        "}\n")
+    exe = tmp_path / "caller"
+    libdir = os.path.dirname(sa.LIB_PATH)
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), str(src),
+                           "-L", libdir, "-lspecattn", "-Wl,-rpath," + libdir, "-o", str(exe)])
+    out = subprocess.run([str(exe)], capture_output=True, text=True, timeout=120)
+    assert out.returncode == 0, out.stdout + out.stderr
