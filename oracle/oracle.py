@@ -214,20 +214,21 @@ def nucleus_bisection(row: np.ndarray, p: float, iters: int):
 
 
 def masked_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, mask: np.ndarray,
-                     *, bf16: bool = False, lens: Optional[np.ndarray] = None,
+                     *, bf16: bool = False, f16: bool = False, lens: Optional[np.ndarray] = None,
                      sm_scale: Optional[float] = None,
                      which: Optional[Sequence[Sequence[int]]] = None,
                      k_new: Optional[np.ndarray] = None, v_new: Optional[np.ndarray] = None):
     """Masked dense attention in fp64.
 
-    q [B,H_q,T,d], k/v [B,H_kv,n,d]: float32 arrays, or uint16 bf16 bit
-    patterns when bf16=True.  mask [B,H_kv,n] (nonzero = selected).
+    q [B,H_q,T,d], k/v [B,H_kv,n,d]: float32 arrays, or uint16 bit patterns
+    (bf16 when bf16=True, IEEE half when f16=True).  mask [B,H_kv,n] (nonzero = selected).
     k_new/v_new [B,H_kv,T,d] (optional): the new tokens' keys and values;
     query t also attends to new tokens 0..t, whatever the mask says.
     which: optional list of (b, h_q, t) rows; default all, returned as
     out [B,H_q,T,d] / lse [B,H_q,T].  With `which`, out is [len(which), d].
     """
-    want = np.uint16 if bf16 else np.float32
+    assert not (bf16 and f16)
+    want = np.uint16 if (bf16 or f16) else np.float32
     q, k, v = (np.ascontiguousarray(a) for a in (q, k, v))
     assert q.dtype == want and k.dtype == want and v.dtype == want
     B, H_q, T, d = q.shape
@@ -252,7 +253,7 @@ def masked_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, mask: np.ndarr
     rows = which_a.shape[0]
     out = np.zeros((rows, d), dtype=np.float64)
     lse = np.zeros(rows, dtype=np.float64)
-    rc = _load().oracle_masked_attention_tail(q.ctypes.data, k.ctypes.data, v.ctypes.data, int(bf16),
+    rc = _load().oracle_masked_attention_tail(q.ctypes.data, k.ctypes.data, v.ctypes.data, 1 if bf16 else (2 if f16 else 0),
                                               B, H_q, H_kv, T, d, n, mask.ctypes.data, lens.ctypes.data,
                                               None if k_new is None else k_new.ctypes.data,
                                               None if v_new is None else v_new.ctypes.data,

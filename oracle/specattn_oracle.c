@@ -51,8 +51,8 @@
  *                            the log-sum-exp merge identity, Appendix A's
  *                            error bound.
  *
- * Floating point: inputs are read exactly (fp32, or bf16 bit patterns
- * widened to fp32) and all arithmetic is fp64.
+ * Floating point: inputs are read exactly (fp32, or bf16 / fp16 bit patterns
+ * widened) and all arithmetic is fp64.
  */
 #include <math.h>
 #include <stdint.h>
@@ -256,11 +256,21 @@ int oracle_chunk_masses(const float *probs, int64_t row_stride, int rows, const 
     return 0;
 }
 
-static inline double load_elem(const void *base, int64_t i, int is_bf16)
+/* fmt: 0 = fp32, 1 = bf16 bit patterns, 2 = IEEE half (fp16) bit patterns; every value is read exactly */
+static inline double load_elem(const void *base, int64_t i, int fmt)
 {
-    if (is_bf16) {
+    if (fmt == 1) {
         uint32_t u = (uint32_t)((const uint16_t *)base)[i] << 16;
         float f; memcpy(&f, &u, 4); return (double)f;
+    }
+    if (fmt == 2) {
+        const uint16_t hbits = ((const uint16_t *)base)[i];
+        const int sign = hbits >> 15, e = (hbits >> 10) & 31, m = hbits & 1023;
+        double v;
+        if (e == 0) v = ldexp((double)m, -24);                    /* zero and subnormals: m * 2^-24 */
+        else if (e == 31) v = m ? NAN : INFINITY;
+        else v = ldexp((double)(1024 + m), e - 25);               /* (1 + m/1024) * 2^(e-15) */
+        return sign ? -v : v;
     }
     return (double)((const float *)base)[i];
 }
@@ -268,7 +278,7 @@ static inline double load_elem(const void *base, int64_t i, int is_bf16)
 /*
  * Masked dense attention for a list of output rows, optionally with the verifier's own new tokens.
  *
- * q      [B][H_q][T][d], k/v [B][H_kv][n][d]   (fp32, or bf16 bit patterns when is_bf16)
+ * q      [B][H_q][T][d], k/v [B][H_kv][n][d]   (is_bf16 = 0: fp32; 1: bf16 bit patterns; 2: fp16 bit patterns)
  * mask   [B][H_kv][n] uint8, 1 = position selected for that kv head
  * lens   [B] valid context length per sequence (positions >= lens[b] never attend)
  * k_new, v_new  [B][H_kv][T][d] or NULL: keys and values of the T tokens being verified (Algorithm 1

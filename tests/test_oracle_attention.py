@@ -225,3 +225,18 @@ def test_tail_is_causal_later_new_tokens_do_not_matter():
     o2, _ = oracle.masked_attention(q, k, v, mask, k_new=k2, v_new=v2)
     np.testing.assert_array_equal(o1[:, :, :3], o2[:, :, :3])
     assert np.abs(o1[:, :, 3] - o2[:, :, 3]).max() > 1e-3
+
+
+def test_fp16_bit_inputs_equal_widened_inputs():
+    q, k, v, mask = _rand(21, B=2, H_q=4, H_kv=2, T=3, d=16, n=60)
+    k_new, v_new = _tail(22, 2, 2, 3, 16)
+    h = [a.astype(np.float16) for a in (q, k, v, k_new, v_new)]
+    h[1][0, 0, 5, 3] = np.float16(6.1e-5)          # smallest normal
+    h[1][0, 0, 6, 3] = np.float16(6e-8)            # subnormal
+    h[2][1, 1, 7, 0] = np.float16(-65504.0)        # largest magnitude
+    wide = [a.astype(np.float32) for a in h]
+    bits = [a.view(np.uint16) for a in h]
+    o_w, l_w = oracle.masked_attention(wide[0], wide[1], wide[2], mask, k_new=wide[3], v_new=wide[4])
+    o_b, l_b = oracle.masked_attention(bits[0], bits[1], bits[2], mask, f16=True, k_new=bits[3], v_new=bits[4])
+    np.testing.assert_array_equal(o_w, o_b)
+    np.testing.assert_array_equal(l_w, l_b)
