@@ -38,7 +38,7 @@ typedef enum specattn_status {
     SPECATTN_EHIP = -6          /* a launch failed; text in specattn_last_error() */
 } specattn_status;
 
-typedef enum specattn_dtype { SPECATTN_F32 = 0, SPECATTN_BF16 = 1 } specattn_dtype;
+typedef enum specattn_dtype { SPECATTN_F32 = 0, SPECATTN_BF16 = 1, SPECATTN_F16 = 2 /* IEEE half */ } specattn_dtype;
 
 /* bits of row_flags[r] */
 #define SPECATTN_ROW_INVALID 1u        /* NaN / negative / infinite entry, zero row sum or length 0: count = 0 */
@@ -114,7 +114,7 @@ typedef struct specattn_select_args {
  * A row with count 0 gives out = 0 and lse = -inf.  Accumulation is fp32;
  * `out` is fp32 whatever the input dtype.
  *
- * Shapes: bf16 with d = 128 runs on the matrix cores for any G = H_q / H_kv (up to 32 query rows
+ * Shapes: bf16 and fp16 with d = 128 run on the matrix cores for any G = H_q / H_kv (up to 32 query rows
  * G*T per pass; larger groups are taken in equal shares of heads, each streaming the kept K/V
  * again).  fp32, and d = 64, run on a portable kernel limited to G*T <= 64.
  *
@@ -215,7 +215,7 @@ specattn_status specattn_sparse_decode_attn(const specattn_attn_args *attn, void
  * workgroups re-derive their share of the list from `probs` on chip.
  * sel->indices is ignored; attn->indices / attn->counts are ignored
  * (sel->counts is written and used).  attn->workspace serves both phases.
- * Supported for bf16, d = 128, contiguous or page-table layouts
+ * Supported for bf16 and fp16, d = 128, contiguous or page-table layouts
  * (SPECATTN_EUNSUPPORTED otherwise).
  */
 specattn_status specattn_fused(const specattn_select_args *sel, const specattn_attn_args *attn,

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libspecattn.so")
 OK, EINVAL, ESHAPE, EALIGN, EWORKSPACE, EUNSUPPORTED, EHIP = 0, -1, -2, -3, -4, -5, -6
 ROW_INVALID, ROW_NEAR_BOUNDARY, ROW_OVERFLOW = 1, 2, 4
 SEL_BLOCK = 1024
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
 
 EXPORTS = ("specattn_topp_select", "specattn_topp_select_union", "specattn_union_workspace_size", "specattn_sparse_decode_attn", "specattn_fused",
            "specattn_workspace_size", "specattn_stream_read", "specattn_last_error", "specattn_version")
@@ -209,13 +209,13 @@ def attn_args(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, *, out: torch.T
     """q [B,H_q,T,d]; contiguous k/v [B,H_kv,n,d]; paged k/v pool [pages,H_kv,page_size,d];
     k_new/v_new [B,H_kv,T,d] contiguous (the new tokens behind the cache), optional."""
     assert q.dim() == 4 and k.dim() == 4 and k.shape == v.shape and k.stride() == v.stride()
-    assert q.dtype == k.dtype == v.dtype and q.dtype in (torch.float32, torch.bfloat16)
+    assert q.dtype == k.dtype == v.dtype and q.dtype in (torch.float32, torch.bfloat16, torch.float16)
     assert q.stride(3) == 1 and k.stride(3) == 1
     B, H_q, T, d = q.shape
     paged = page_table is not None or indices_are_physical
     a = AttnArgs()
     a.q, a.k, a.v = q.data_ptr(), k.data_ptr(), v.data_ptr()
-    a.dtype = BF16 if q.dtype == torch.bfloat16 else F32
+    a.dtype = {torch.bfloat16: BF16, torch.float16: F16, torch.float32: F32}[q.dtype]
     a.B, a.H_q, a.H_kv, a.T, a.d = B, H_q, k.shape[1], T, d
     a.sm_scale = sm_scale
     a.q_stride_b, a.q_stride_h, a.q_stride_t = q.stride(0), q.stride(1), q.stride(2)

@@ -82,11 +82,11 @@ specattn_status check_attn(const specattn_attn_args *a, bool fused)
     if (!fused && !dense && (!a->indices || !a->counts)) { set_error("indices and counts must both be given, or both be NULL (dense)"); return SPECATTN_EINVAL; }
     if (dense && a->indices_are_physical) { set_error("indices_are_physical without an index list"); return SPECATTN_EINVAL; }
     if (a->B <= 0 || a->H_q <= 0 || a->H_kv <= 0 || a->T <= 0 || a->d <= 0 || a->n_max <= 0) { set_error("sizes must be positive"); return SPECATTN_EINVAL; }
-    if (a->dtype != SPECATTN_F32 && a->dtype != SPECATTN_BF16) { set_error("unknown dtype %d", (int)a->dtype); return SPECATTN_EUNSUPPORTED; }
+    if (a->dtype != SPECATTN_F32 && a->dtype != SPECATTN_BF16 && a->dtype != SPECATTN_F16) { set_error("unknown dtype %d", (int)a->dtype); return SPECATTN_EUNSUPPORTED; }
     if (a->H_q % a->H_kv) { set_error("H_q is not a multiple of H_kv"); return SPECATTN_ESHAPE; }
     if (a->T > SPECATTN_MAX_T) { set_error("T exceeds %d", SPECATTN_MAX_T); return SPECATTN_ESHAPE; }
     if (a->d != 64 && a->d != 128) { set_error("d must be 64 or 128"); return SPECATTN_ESHAPE; }
-    if ((a->H_q / a->H_kv) * a->T > 64 && !(a->dtype == SPECATTN_BF16 && a->d == 128)) { set_error("G*T exceeds 64 query rows per kv head (only bf16 with d = 128 takes more)"); return SPECATTN_ESHAPE; }
+    if ((a->H_q / a->H_kv) * a->T > 64 && !(a->dtype != SPECATTN_F32 && a->d == 128)) { set_error("G*T exceeds 64 query rows per kv head (only bf16 / fp16 with d = 128 take more)"); return SPECATTN_ESHAPE; }
     if (!fused && !dense && a->idx_capacity < 1) { set_error("idx_capacity must be at least 1"); return SPECATTN_ESHAPE; }
     if (!fused && !dense && a->idx_stride_row < a->idx_capacity) { set_error("idx_stride_row is smaller than idx_capacity"); return SPECATTN_ESHAPE; }
     const bool paged = a->page_table != nullptr || a->indices_are_physical;
@@ -100,7 +100,7 @@ specattn_status check_attn(const specattn_attn_args *a, bool fused)
     if ((a->k_new == nullptr) != (a->v_new == nullptr)) { set_error("k_new and v_new must both be given or both be NULL"); return SPECATTN_EINVAL; }
     if (a->k_new && (!aligned(a->k_new, 16) || !aligned(a->v_new, 16))) { set_error("k_new and v_new must be 16-byte aligned"); return SPECATTN_EALIGN; }
     if (a->kv_stride_n < a->d) { set_error("kv_stride_n is smaller than d"); return SPECATTN_ESHAPE; }
-    const size_t es = a->dtype == SPECATTN_BF16 ? 2 : 4;
+    const size_t es = a->dtype == SPECATTN_F32 ? 4 : 2;
     if (!aligned(a->q, 16) || !aligned(a->k, 16) || !aligned(a->v, 16) || !aligned(a->out, 16)) { set_error("q, k, v and out must be 16-byte aligned"); return SPECATTN_EALIGN; }
     const int64_t strides[] = {a->q_stride_b, a->q_stride_h, a->q_stride_t, a->kv_stride_b, a->kv_stride_h,
                                a->kv_stride_n, paged ? a->kv_stride_page : 0};
@@ -310,7 +310,7 @@ specattn_status specattn_fused(const specattn_select_args *sel, const specattn_a
     }
     AttnLaunch al = make_attn(attn);
     if (!attn_mfma_supported(al) || attn->indices_are_physical) {
-        set_error("the fused path is built for bf16, d = 128, G*T <= 32, logical positions");
+        set_error("the fused path is built for bf16 / fp16, d = 128, logical positions");
         return SPECATTN_EUNSUPPORTED;
     }
     st = check_workspace(attn->workspace, attn->workspace_bytes, specattn_workspace_size(sel, attn));
@@ -383,6 +383,6 @@ size_t specattn_workspace_size(const specattn_select_args *sel, const specattn_a
 
 const char *specattn_last_error(void) { return g_error; }
 
-int specattn_version(void) { return 1004; }
+int specattn_version(void) { return 1005; }
 
 }  // extern "C"

@@ -24,6 +24,9 @@ template <typename T> struct Elem;
 template <> struct Elem<float> {
     static __device__ __forceinline__ float ld(const void *p, int64_t i) { return static_cast<const float *>(p)[i]; }
 };
+template <> struct Elem<_Float16> {
+    static __device__ __forceinline__ float ld(const void *p, int64_t i) { return (float) static_cast<const _Float16 *>(p)[i]; }
+};
 template <> struct Elem<__hip_bfloat16> {
     static __device__ __forceinline__ float ld(const void *p, int64_t i)
     {
@@ -270,6 +273,8 @@ specattn_status launch_attn(const AttnLaunch &a, hipStream_t stream)
     else if (a.dtype == SPECATTN_F32 && a.d == 128) st = run_generic<float, 128>(a, rows, ns, part_o, part_ml, stream);
     else if (a.dtype == SPECATTN_BF16 && a.d == 64) st = run_generic<__hip_bfloat16, 64>(a, rows, ns, part_o, part_ml, stream);
     else if (a.dtype == SPECATTN_BF16 && a.d == 128) st = run_generic<__hip_bfloat16, 128>(a, rows, ns, part_o, part_ml, stream);
+    else if (a.dtype == SPECATTN_F16 && a.d == 64) st = run_generic<_Float16, 64>(a, rows, ns, part_o, part_ml, stream);
+    else if (a.dtype == SPECATTN_F16 && a.d == 128) st = run_generic<_Float16, 128>(a, rows, ns, part_o, part_ml, stream);
     else { set_error("no attention kernel for dtype %d, d %d", a.dtype, a.d); return SPECATTN_EUNSUPPORTED; }
     if (st != SPECATTN_OK) return st;
     hipLaunchKernelGGL(merge_kernel, dim3(rows * QT), dim3(a.d < 64 ? 64 : a.d), 0, stream, a, ns, part_o, part_ml);

@@ -1,5 +1,5 @@
 // Sparse decode attention over a selected index list (Section 3.1.2, Eq. 2-3; Section 3.5),
-// bf16, d = 128, up to 32 query rows per kv head (G*T <= 32): the gfx950 matrix-core variant.
+// bf16 or fp16, d = 128, up to 32 query rows per kv head and launch: the gfx950 matrix-core variant.
 //
 // Work split ("stream-K" over kept positions): the kept positions of all rows, in 32-position
 // tiles, form one sequence; workgroup w takes an equal contiguous share of it, so the split is
@@ -24,12 +24,29 @@
 namespace specattn {
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+
+// The two 16-bit element types the matrix cores take here.  Both contractions use the 16x16x32 shape;
+// the softmax weights are handed over as a high part (the weight rounded to the element type) and a low
+// part (the rounding error, rounded again), so that the type's short significand costs no accuracy.
+template <bool F16> struct Half;
+template <> struct Half<false> {
+    typedef bf16x8 x8;
+    typedef bf16x2 x2;
+    static __device__ __forceinline__ f32x4 mfma(x8 a, x8 b, f32x4 c) { return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0); }
+};
+template <> struct Half<true> {
+    typedef f16x8 x8;
+    typedef f16x2 x2;
+    static __device__ __forceinline__ f32x4 mfma(x8 a, x8 b, f32x4 c) { return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0); }
+};
 
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T *)(p))
 #define GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
@@ -231,9 +248,11 @@ struct Merge {
     }
 };
 
-template <int NQT, int LAYOUT, bool FUSED>
+template <int NQT, int LAYOUT, bool FUSED, bool F16>
 __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan plan)
 {
+    typedef typename Half<F16>::x8 h16x8;
+    typedef typename Half<F16>::x2 h16x2;
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     constexpr int QTP = NQT * 16;
     constexpr int EPT = CHUNK_TILES * TILE / THREADS;                   // list entries staged per thread
@@ -589,8 +608,8 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
                             f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                             for (int c = 0; c < 4; ++c)
-                                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf.f[pt][c]),
-                                                                              __builtin_bit_cast(bf16x8, qf.f[c]), acc, 0, 0, 0);
+                                acc = Half<F16>::mfma(__builtin_bit_cast(h16x8, kf.f[pt][c]),
+                                                      __builtin_bit_cast(h16x8, qf.f[c]), acc);
                             s[qt][pt] = acc;
                         }
                     }
@@ -598,7 +617,7 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
 
                 // ---- softmax weights; lane (q = l16, g) holds positions 16pt + 4g + i ---------------
                 const int remaining = count - lt * TILE;               // > 0; < TILE only on a row's last tile
-                bf16x8 p_hi[NQT], p_lo[NQT];
+                h16x8 p_hi[NQT], p_lo[NQT];
 #pragma unroll
                 for (int qt = 0; qt < NQT; ++qt) {
                     float x[8];
@@ -628,9 +647,9 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
                         const float p0 = __builtin_amdgcn_exp2f(fmaf(x[e], scale2, -mr));
                         const float p1 = __builtin_amdgcn_exp2f(fmaf(x[e + 1], scale2, -mr));
                         psum += p0 + p1;
-                        const bf16x2 hi = __builtin_convertvector((f32x2){p0, p1}, bf16x2);
+                        const h16x2 hi = __builtin_convertvector((f32x2){p0, p1}, h16x2);
                         const f32x2 back = __builtin_convertvector(hi, f32x2);
-                        const bf16x2 lo = __builtin_convertvector((f32x2){p0 - back[0], p1 - back[1]}, bf16x2);
+                        const h16x2 lo = __builtin_convertvector((f32x2){p0 - back[0], p1 - back[1]}, h16x2);
                         p_hi[qt][e] = hi[0]; p_hi[qt][e + 1] = hi[1];
                         p_lo[qt][e] = lo[0]; p_lo[qt][e + 1] = lo[1];
                     }
@@ -648,11 +667,11 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
 #pragma unroll
                     for (int t = 0; t < 4; ++t) {
                         const u32x4 both = (u32x4){vh.f[t][0][0], vh.f[t][0][1], vh.f[t][1][0], vh.f[t][1][1]};
-                        const bf16x8 vf = __builtin_bit_cast(bf16x8, both);
+                        const h16x8 vf = __builtin_bit_cast(h16x8, both);
 #pragma unroll
                         for (int qt = 0; qt < NQT; ++qt) {
-                            o[qt][tb + t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, p_hi[qt], o[qt][tb + t], 0, 0, 0);
-                            o[qt][tb + t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, p_lo[qt], o[qt][tb + t], 0, 0, 0);
+                            o[qt][tb + t] = Half<F16>::mfma(vf, p_hi[qt], o[qt][tb + t]);
+                            o[qt][tb + t] = Half<F16>::mfma(vf, p_lo[qt], o[qt][tb + t]);
                         }
                     }
                 }
@@ -800,7 +819,7 @@ __global__ void merge_partials_kernel(AttnLaunch a, Plan plan, int qtp)
 bool attn_mfma_supported(const AttnLaunch &a)
 {
     // any number of query heads per kv head: groups of more than 32 query rows run as several launches
-    return a.dtype == SPECATTN_BF16 && a.d == 128 && a.T <= 32 && a.H_kv <= MAX_ROWS;
+    return (a.dtype == SPECATTN_BF16 || a.dtype == SPECATTN_F16) && a.d == 128 && a.T <= 32 && a.H_kv <= MAX_ROWS;
 }
 
 int attn_mfma_workgroups() { return cu_count(); }
@@ -833,21 +852,20 @@ static specattn_status launch_chunk(const AttnLaunch &a, hipStream_t stream)
     const int layout = a.indices_are_physical ? PHYSICAL : (a.page_table ? PAGE_TABLE : CONTIGUOUS);
     const void *fn = nullptr;
     const bool fused = a.probs != nullptr;
-#define PICK(NQT, LAY)                                                                                           \
-    if (qtp == 16 * NQT && layout == LAY)                                                                        \
-        fn = fused ? reinterpret_cast<const void *>(&attn_mfma_kernel<NQT, LAY, true>)                           \
-                   : reinterpret_cast<const void *>(&attn_mfma_kernel<NQT, LAY, false>);
-    PICK(1, CONTIGUOUS) PICK(1, PAGE_TABLE) PICK(2, CONTIGUOUS) PICK(2, PAGE_TABLE)
-    if (!fused) {
-        if (qtp == 16 && layout == PHYSICAL) fn = reinterpret_cast<const void *>(&attn_mfma_kernel<1, PHYSICAL, false>);
-        if (qtp == 32 && layout == PHYSICAL) fn = reinterpret_cast<const void *>(&attn_mfma_kernel<2, PHYSICAL, false>);
-    }
+    const bool f16 = a.dtype == SPECATTN_F16;
+#define PICK(NQT, LAY, FUS)                                                                                      \
+    if (qtp == 16 * NQT && layout == LAY && fused == FUS)                                                        \
+        fn = f16 ? reinterpret_cast<const void *>(&attn_mfma_kernel<NQT, LAY, FUS, true>)                        \
+                 : reinterpret_cast<const void *>(&attn_mfma_kernel<NQT, LAY, FUS, false>);
+    PICK(1, CONTIGUOUS, false) PICK(1, PAGE_TABLE, false) PICK(1, PHYSICAL, false)
+    PICK(2, CONTIGUOUS, false) PICK(2, PAGE_TABLE, false) PICK(2, PHYSICAL, false)
+    PICK(1, CONTIGUOUS, true) PICK(1, PAGE_TABLE, true) PICK(2, CONTIGUOUS, true) PICK(2, PAGE_TABLE, true)
     if (!fn) { set_error("the fused path takes logical positions, not pool slots"); return SPECATTN_EUNSUPPORTED; }
 #undef PICK
     {
         // the kernels use more LDS than the default limit; raise it once per kernel (any thread may call)
         static std::mutex mu;
-        static const void *configured[16] = {nullptr};
+        static const void *configured[32] = {nullptr};
         std::lock_guard<std::mutex> lock(mu);
         bool seen = false;
         for (const void *c : configured) seen = seen || c == fn;
@@ -903,7 +921,7 @@ static specattn_status launch_batch(const AttnLaunch &a, hipStream_t stream)
 {
     const int b_max = MAX_ROWS / a.H_kv;
     if (a.B <= b_max) return launch_chunk(a, stream);
-    const int es = 2;                                       // bf16
+    const int es = 2;                                       // bf16 or fp16
     const int G = a.H_q / a.H_kv;
     for (int b0 = 0; b0 < a.B; b0 += b_max) {
         AttnLaunch c = a;

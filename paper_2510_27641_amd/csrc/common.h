@@ -147,6 +147,7 @@ __device__ __forceinline__ int attn_list_pos(const AttnLaunch &a, const int32_t 
 __device__ __forceinline__ float ld_elem(const void *p, int64_t i, int dtype)
 {
     if (dtype == SPECATTN_BF16) return __uint_as_float((uint32_t) static_cast<const uint16_t *>(p)[i] << 16);
+    if (dtype == SPECATTN_F16) return (float) static_cast<const _Float16 *>(p)[i];
     return static_cast<const float *>(p)[i];
 }
 

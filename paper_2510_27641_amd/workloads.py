@@ -155,7 +155,7 @@ class Workload:
     d: int
     n: int                      # n_max (padded context length)
     top_p: float
-    dtype: str                  # "f32" | "bf16"
+    dtype: str                  # "f32" | "bf16" | "f16"
     probs: np.ndarray           # [B, H_kv, n] float32
     q: np.ndarray               # [B, H_q, T, d] float32 (bf16-representable when dtype == "bf16")
     k: np.ndarray               # [B, H_kv, n, d] float32, logical (un-paged) order
@@ -194,6 +194,8 @@ def _qkv(rng, B, H_q, H_kv, T, d, n, dtype):
     v = rng.standard_normal((B, H_kv, n, d), dtype=np.float32)
     if dtype == "bf16":
         q, k, v = (bf16_bits_to_f32(round_to_bf16_bits(a)).reshape(a.shape) for a in (q, k, v))
+    elif dtype == "f16":
+        q, k, v = (a.astype(np.float16).astype(np.float32) for a in (q, k, v))
     return q, k, v
 
 

@@ -12,7 +12,7 @@ import oracle
 from paper_2510_27641_amd import binding as sa
 from paper_2510_27641_amd import workloads as W
 
-TOL = {"bf16": 2e-3, "f32": 1e-5}     # max |out - ref| / max |ref| per output row
+TOL = {"bf16": 2e-3, "f16": 2e-3, "f32": 1e-5}     # max |out - ref| / max |ref| per output row
 
 
 def dev(x: np.ndarray, dtype=None) -> torch.Tensor:
@@ -24,7 +24,7 @@ def dev(x: np.ndarray, dtype=None) -> torch.Tensor:
 
 def kv_tensors(w: W.Workload):
     """q, k, v on the device in the workload's dtype (and paged pools when the workload is paged)."""
-    dt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    dt = {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32}[w.dtype]
     q = dev(w.q, dt)
     if w.page_table is not None:
         k, v = dev(w.paged_pool(w.k), dt), dev(w.paged_pool(w.v), dt)
@@ -113,6 +113,9 @@ def oracle_attention(w: W.Workload, mask: np.ndarray, which=None):
     if w.dtype == "bf16":
         qb, kb, vb = (W.round_to_bf16_bits(a).reshape(a.shape) for a in (w.q, w.k, w.v))
         return oracle.masked_attention(qb, kb, vb, mask, bf16=True, lens=w.seq_lens, which=which)
+    if w.dtype == "f16":
+        qb, kb, vb = (a.astype(np.float16).view(np.uint16) for a in (w.q, w.k, w.v))
+        return oracle.masked_attention(qb, kb, vb, mask, f16=True, lens=w.seq_lens, which=which)
     return oracle.masked_attention(w.q, w.k, w.v, mask, lens=w.seq_lens, which=which)
 
 
