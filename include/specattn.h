@@ -161,6 +161,10 @@ typedef struct specattn_attn_args {
        chunk-granular specattn_topp_select (counts and idx_capacity in chunks); positions past seq_lens[b]
        in the last chunk are not attended to.  Not available with indices_are_physical or specattn_fused. */
     int32_t chunk_size;
+
+    /* optional: a second copy of the output in the dtype of q/k/v (round to nearest even), [B][H_q][T][d]
+       contiguous, 16-byte aligned - what a following projection in that dtype reads.  NULL = not written. */
+    void *out_lowp;
 } specattn_attn_args;
 
 /*

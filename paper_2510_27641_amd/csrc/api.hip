@@ -97,6 +97,7 @@ specattn_status check_attn(const specattn_attn_args *a, bool fused)
     }
     if (a->chunk_size < 0 || (a->chunk_size > 1 && (!is_pow2(a->chunk_size) || a->chunk_size > 1024))) { set_error("chunk_size must be 0, 1 or a power of two up to 1024"); return SPECATTN_ESHAPE; }
     if (a->chunk_size > 1 && (fused || dense || a->indices_are_physical)) { set_error("chunk lists are not available with the fused call, dense calls or physical indices"); return SPECATTN_EUNSUPPORTED; }
+    if (a->out_lowp && !aligned(a->out_lowp, 16)) { set_error("out_lowp must be 16-byte aligned"); return SPECATTN_EALIGN; }
     if ((a->k_new == nullptr) != (a->v_new == nullptr)) { set_error("k_new and v_new must both be given or both be NULL"); return SPECATTN_EINVAL; }
     if (a->k_new && (!aligned(a->k_new, 16) || !aligned(a->v_new, 16))) { set_error("k_new and v_new must be 16-byte aligned"); return SPECATTN_EALIGN; }
     if (a->kv_stride_n < a->d) { set_error("kv_stride_n is smaller than d"); return SPECATTN_ESHAPE; }
@@ -169,6 +170,7 @@ AttnLaunch make_attn(const specattn_attn_args *a)
     l.k_new = a->k_new;
     l.v_new = a->v_new;
     l.out = a->out;
+    l.out_lowp = a->out_lowp;
     l.lse = a->lse;
     l.workspace = a->workspace;
     l.workspace_bytes = a->workspace_bytes;
@@ -383,6 +385,6 @@ size_t specattn_workspace_size(const specattn_select_args *sel, const specattn_a
 
 const char *specattn_last_error(void) { return g_error; }
 
-int specattn_version(void) { return 1005; }
+int specattn_version(void) { return 1006; }
 
 }  // extern "C"

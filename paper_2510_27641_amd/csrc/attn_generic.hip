@@ -205,7 +205,9 @@ __global__ void merge_kernel(AttnLaunch a, int n_splits, const float *part_o, co
 #pragma unroll
         for (int p = 0; p < SPECATTN_MAX_T; ++p)
             if (p < n_tail) o += wt[p] * ld_elem(a.v_new, noff + (int64_t)p * D + dd, a.dtype);
-        a.out[orow * D + dd] = l > 0.0f ? o / l : 0.0f;
+        const float res = l > 0.0f ? o / l : 0.0f;
+        a.out[orow * D + dd] = res;
+        if (a.out_lowp) st_lowp(a.out_lowp, orow * D + dd, res, a.dtype);
     }
     if (a.lse && threadIdx.x == 0) a.lse[orow] = l > 0.0f ? m + __logf(l) : -INFINITY;
 }

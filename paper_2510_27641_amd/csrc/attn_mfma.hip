@@ -741,8 +741,12 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
                     if (w0 == w1 && !a.k_new) {
                         const int gh = q / a.T, tt = q - gh * a.T;
                         const int64_t orow = ((int64_t)b * a.H_q + attn_query_head(a, h, gh)) * a.T + tt;
-                        *reinterpret_cast<f32x4 *>(a.out + orow * D + 16 * t + 4 * g) =
-                            l > 0.0f ? acc / l : (f32x4){0.f, 0.f, 0.f, 0.f};
+                        const f32x4 res = l > 0.0f ? acc / l : (f32x4){0.f, 0.f, 0.f, 0.f};
+                        *reinterpret_cast<f32x4 *>(a.out + orow * D + 16 * t + 4 * g) = res;
+                        if (a.out_lowp) {
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) st_lowp(a.out_lowp, orow * D + 16 * t + 4 * g + i, res[i], a.dtype);
+                        }
                         if (a.lse && g == 0 && t == 0)
                             a.lse[orow] = l > 0.0f ? (m + log2f(l)) * 0.6931471805599453f : -INFINITY;
                     } else {
@@ -778,6 +782,7 @@ __global__ void merge_partials_kernel(AttnLaunch a, Plan plan, int qtp)
     const int p0 = plan.cost_prefix[r], p1 = plan.cost_prefix[r + 1];
     if (p0 == p1 && !tail) {
         a.out[orow * D + dv] = 0.0f;
+        if (a.out_lowp) st_lowp(a.out_lowp, orow * D + dv, 0.0f, a.dtype);
         if (a.lse && dv == 0) a.lse[orow] = -INFINITY;
         return;
     }
@@ -809,7 +814,9 @@ __global__ void merge_partials_kernel(AttnLaunch a, Plan plan, int qtp)
         for (int p = 0; p < SPECATTN_MAX_T; ++p)
             if (p <= t) acc.add(dots[p] * scale2, 1.0f, ld_elem(a.v_new, noff + (int64_t)p * D + dv, a.dtype));
     }
-    a.out[orow * D + dv] = acc.l > 0.0f ? acc.o / acc.l : 0.0f;
+    const float res = acc.l > 0.0f ? acc.o / acc.l : 0.0f;
+    a.out[orow * D + dv] = res;
+    if (a.out_lowp) st_lowp(a.out_lowp, orow * D + dv, res, a.dtype);
     // m is in log2 units of the scaled scores
     if (a.lse && dv == 0) a.lse[orow] = acc.l > 0.0f ? (acc.m + log2f(acc.l)) * 0.6931471805599453f : -INFINITY;
 }
@@ -937,6 +944,7 @@ static specattn_status launch_batch(const AttnLaunch &a, hipStream_t stream)
         if (a.indices) c.indices = a.indices + r0 * a.idx_stride;
         if (a.counts) c.counts = a.counts + r0;
         c.out = a.out + (int64_t)b0 * a.H_q * a.T * a.d;
+        if (a.out_lowp) c.out_lowp = static_cast<char *>(a.out_lowp) + (int64_t)b0 * a.H_q * a.T * a.d * es;
         if (a.lse) c.lse = a.lse + (int64_t)b0 * a.H_q * a.T;
         if (a.seq_lens) c.seq_lens = a.seq_lens + b0;
         if (a.k_new) {

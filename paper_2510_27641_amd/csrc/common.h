@@ -96,6 +96,7 @@ struct AttnLaunch {
     int g_first, g_count;        // this launch handles query heads g_first .. g_first + g_count - 1 of every kv head's
                                  // group (g_count 0: all of them)
     float *out;
+    void *out_lowp;          // may be null: the output once more in the input dtype
     float *lse;              // may be null
     void *workspace;
     size_t workspace_bytes;
@@ -149,6 +150,20 @@ __device__ __forceinline__ float ld_elem(const void *p, int64_t i, int dtype)
     if (dtype == SPECATTN_BF16) return __uint_as_float((uint32_t) static_cast<const uint16_t *>(p)[i] << 16);
     if (dtype == SPECATTN_F16) return (float) static_cast<const _Float16 *>(p)[i];
     return static_cast<const float *>(p)[i];
+}
+
+// Element i of the optional second output copy, in the input dtype (round to nearest even).
+__device__ __forceinline__ void st_lowp(void *p, int64_t i, float x, int dtype)
+{
+    if (dtype == SPECATTN_BF16) {
+        uint32_t u = __float_as_uint(x);
+        u = ((u & 0x7fffffffu) > 0x7f800000u) ? (u | 0x00400000u) : (u + 0x7fffu + ((u >> 16) & 1u));     // NaN stays NaN
+        static_cast<uint16_t *>(p)[i] = (uint16_t)(u >> 16);
+    } else if (dtype == SPECATTN_F16) {
+        static_cast<_Float16 *>(p)[i] = (_Float16)x;
+    } else {
+        static_cast<float *>(p)[i] = x;
+    }
 }
 
 // Scores of query row (b, hq, t) against the keys of new tokens 0..t (unscaled dot products), computed
