@@ -39,9 +39,154 @@ def parse():
     ap.add_argument("--top-p", type=float, default=0.9)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--path", choices=["both", "unfused", "fused"], default="both")
+    ap.add_argument("--workload", choices=["headline", "side"], default="headline",
+                    help="headline: the 32-layer verify step (one JSON line).  side: the other workloads and calls "
+                         "(8k layer, long-context sweep, ragged paged batch, dense, new tokens, chunks, union, large "
+                         "GQA group), one JSON line each")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device copy (reference for rocprofv3 --pmc byte counters)")
     return ap.parse_args()
+
+
+def side_workloads(torch, sa, W):
+    """The workloads besides the headline one, and the calls beyond the selection + attention pair: HIP-event
+    times of each call (mean of 20 after 3 warm-up calls, layer instances rotating so that nothing is served from
+    the Infinity Cache unless the workload itself is that small)."""
+    H_q, H_kv, T, d = 32, 8, 5, 128
+
+    def timed(fn, reps=20, warm=3):
+        for _ in range(warm):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps * 1e3          # us
+
+    def emit(name, **kw):
+        print(json.dumps(dict(workload=name, **kw)), flush=True)
+
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(7)
+
+    def kv(shape):
+        return (torch.randn(shape, generator=gen, device="cuda", dtype=torch.bfloat16),
+                torch.randn(shape, generator=gen, device="cuda", dtype=torch.bfloat16))
+
+    def pair(name, probs_np, top_p, B, n, *, H_q=H_q, seq_lens=None, page_table=None, pool_pages=0, copies=1):
+        """selection + attention of one layer; `copies` layer instances are rotated through."""
+        R = B * H_kv
+        p = torch.from_numpy(probs_np).cuda()
+        sl = None if seq_lens is None else torch.from_numpy(seq_lens.astype(np.int32)).cuda()
+        pt = None if page_table is None else torch.from_numpy(page_table).cuda()
+        idx = torch.empty((R, n), dtype=torch.int32, device="cuda")
+        cnt = torch.zeros(R, dtype=torch.int32, device="cuda")
+        s = sa.select_args(p, top_p, indices=idx, counts=cnt, seq_lens=sl)
+        need = sa.specattn_workspace_size(s, None)
+        ws_s = sa.alloc_workspace(need) if need else None
+        out = torch.empty((B, H_q, T, d), dtype=torch.float32, device="cuda")
+        calls = []
+        for _ in range(copies):
+            q = torch.randn((B, H_q, T, d), generator=gen, device="cuda").to(torch.bfloat16)
+            k, v = kv((pool_pages, H_kv, 16, d) if pool_pages else (B, H_kv, n, d))
+            extra = dict(page_table=pt, page_size=16, n_max=n) if pt is not None else {}
+            a = sa.attn_args(q, k, v, out=out, indices=idx, counts=cnt, **extra)
+            ws = sa.alloc_workspace(sa.specattn_workspace_size(None, a))
+            a.workspace, a.workspace_bytes = ws.data_ptr(), ws.numel()
+            calls.append((a, ws, q, k, v))
+        t_sel = timed(lambda: sa.specattn_topp_select(s, ws_s))
+        state = {"i": 0}
+
+        def attend():
+            sa.specattn_sparse_decode_attn(calls[state["i"] % copies][0])
+            state["i"] += 1
+        t_att = timed(attend)
+        kept = int(cnt.sum().item())
+        total = int(seq_lens.sum()) * H_kv if seq_lens is not None else R * n
+        emit(name, rows=R, n=n, top_p=top_p, kept_fraction=round(kept / total, 4), select_us=round(t_sel, 1),
+             split_selection=bool(need), attention_us=round(t_att, 1), kept_kv_MB=round(kept * 512 / 1e6, 1),
+             attention_GBps=round(kept * 512.0 / t_att / 1e3, 1))
+
+    w = W.llama8b_layer(seed=1, with_kv=False)
+    pair("llama8b_layer n=8192 p=0.95 (cache-resident)", w.probs, 0.95, 1, 8192)
+    for clip in (None, 8.0):
+        w = W.long_context(seed=3, B=4, n=131072, logit_clip=clip, with_kv=False)
+        for tp in (0.8, 0.9, 0.95, 0.99):
+            pair(f"long_context B=4 n=131072 logits {'literal' if clip is None else 'clipped to 8'}", w.probs, tp, 4, 131072)
+    w = W.ragged_paged(seed=0, B=64, with_kv=False)
+    pair("ragged_paged B=64 lens 4096..65536, 16-token pages", w.probs, 0.95, 64, w.n, seq_lens=w.seq_lens,
+         page_table=w.page_table, pool_pages=w.n_pool_pages)
+
+    # ---- the calls beyond the pair, at the headline layer shape ---------------------------------------------
+    B, n, L = 8, 32768, 6
+    R = B * H_kv
+    rng = np.random.default_rng(11)
+    probs = torch.from_numpy(W.draft_probs(rng, L * R, n).reshape(L * B, H_kv, n)).cuda()
+    k, v = kv((L * B, H_kv, n, d))
+    k_new, v_new = kv((L * B, H_kv, T, d))
+    idx = torch.zeros((L * R, n), dtype=torch.int32, device="cuda")
+    cnt = torch.zeros((L * R,), dtype=torch.int32, device="cuda")
+    sel = sa.select_args(probs, 0.9, indices=idx, counts=cnt)
+    sa.specattn_topp_select(sel)
+    torch.cuda.synchronize()
+    kept_bytes = float(cnt.sum().item()) / L * 512
+
+    def layer_calls(H_q_, **kw):
+        q = torch.randn((L * B, H_q_, T, d), generator=gen, device="cuda").to(torch.bfloat16)
+        out = torch.empty((B, H_q_, T, d), dtype=torch.float32, device="cuda")
+        calls = []
+        for l in range(L):
+            b, r = slice(l * B, (l + 1) * B), slice(l * R, (l + 1) * R)
+            extra = {key: (val[b] if key in ("k_new", "v_new") else val[r] if key in ("indices", "counts") else val)
+                     for key, val in kw.items()}
+            a = sa.attn_args(q[b], k[b], v[b], out=out, **extra)
+            ws = sa.alloc_workspace(sa.specattn_workspace_size(None, a))
+            a.workspace, a.workspace_bytes = ws.data_ptr(), ws.numel()
+            calls.append((a, ws))
+        return calls, q, out
+
+    def per_layer(calls):
+        return timed(lambda: [sa.specattn_sparse_decode_attn(a) for a, _ in calls]) / L
+
+    c, *_k = layer_calls(H_q, indices=idx, counts=cnt)
+    t = per_layer(c)
+    emit("headline layer, list", attention_us=round(t, 1), attention_GBps=round(kept_bytes / t / 1e3, 1))
+    c, *_k = layer_calls(H_q, indices=idx, counts=cnt, k_new=k_new, v_new=v_new)
+    emit("headline layer, list + new tokens behind the cache", attention_us=round(per_layer(c), 1))
+    c, *_k = layer_calls(H_q)
+    t = timed(lambda: [sa.specattn_sparse_decode_attn(a) for a, _ in c], reps=5) / L
+    emit("headline layer, dense (no list)", attention_us=round(t, 1), attention_GBps=round(R * n * 512.0 / t / 1e3, 1))
+    for hq in (64, 128):
+        c, *_k = layer_calls(hq, indices=idx, counts=cnt)
+        t = per_layer(c)
+        emit(f"headline layer, {hq // H_kv} query heads per kv head", attention_us=round(t, 1),
+             kept_kv_GBps_counted_once=round(kept_bytes / t / 1e3, 1))
+    nc = n // 16
+    idc = torch.zeros((L * R, nc), dtype=torch.int32, device="cuda")
+    cc = torch.zeros((L * R,), dtype=torch.int32, device="cuda")
+    selc = sa.select_args(probs, 0.9, indices=idc, counts=cc, chunk_size=16)
+    wsc = sa.alloc_workspace(sa.specattn_workspace_size(selc, None))
+    t_tok = timed(lambda: sa.specattn_topp_select(sel))
+    t_chk = timed(lambda: sa.specattn_topp_select(selc, wsc))
+    chunk_bytes = float(cc.sum().item()) / L * 16 * 512
+    c, *_k = layer_calls(H_q, indices=idc, counts=cc, chunk_size=16)
+    t = per_layer(c)
+    emit("selection in chunks of 16 + attention over chunk lists", rows=L * R, n=n, select_tokens_us=round(t_tok, 1),
+         select_chunks_us=round(t_chk, 1), kept_chunk_fraction=round(float(cc.float().mean().item()) / nc, 4),
+         attention_us=round(t, 1), attention_GBps=round(chunk_bytes / t / 1e3, 1))
+    for hd, steps in ((8, 4), (32, 4)):
+        pu = torch.from_numpy(W.draft_step_probs(np.random.default_rng(2), B, hd, steps, n)).cuda()
+        iu = torch.zeros((R, n), dtype=torch.int32, device="cuda")
+        cu = torch.zeros((R,), dtype=torch.int32, device="cuda")
+        ua = sa.union_args(pu, 0.9, H_kv, indices=iu, counts=cu)
+        wsu = sa.alloc_workspace(sa.specattn_union_workspace_size(ua))
+        t = timed(lambda: sa.specattn_topp_select_union(ua, wsu))
+        emit(f"union over {steps} draft steps x {hd // H_kv} draft heads per kv head", member_rows=B * hd * steps, n=n,
+             probs_MB=round(B * hd * steps * n * 4 / 1e6, 1), union_us=round(t, 1),
+             union_fraction=round(float(cu.float().mean().item()) / n, 4))
 
 
 def main():
@@ -57,6 +202,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     sa.load()
+    if args.workload == "side":
+        side_workloads(torch, sa, W)
+        return
     L, B, n, top_p = args.layers, args.batch, args.context, args.top_p
     H_q, H_kv, T, d = 32, 8, 5, 128
     R = B * H_kv
