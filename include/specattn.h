@@ -230,6 +230,18 @@ specattn_status specattn_fused(const specattn_select_args *sel, const specattn_a
 size_t specattn_workspace_size(const specattn_select_args *sel, const specattn_attn_args *attn);
 
 /*
+ * Debugging aid: checks, on the device and without touching K/V, the index lists that
+ * specattn_sparse_decode_attn(attn) would read (Section 3.5: the selection reaches the attention kernel as an
+ * index structure).  Counted as violations: a negative count or sequence length, an entry outside
+ * [0, seq_len) (chunk lists: outside the sequence's chunks), a list that is not strictly ascending, a page-table
+ * entry of a listed position that is negative or beyond the pool; for physical lists, an entry outside
+ * [0, pool_slots).  pool_slots = pages * page_size of the pool, or 0 to skip the pool-size checks.
+ * *n_bad (device int32) receives the number of violations; the caller reads it after synchronising.
+ * Dense calls (no list) have nothing to check: SPECATTN_EINVAL.
+ */
+specattn_status specattn_check_lists(const specattn_attn_args *attn, int64_t pool_slots, int32_t *n_bad, void *stream);
+
+/*
  * Measurement aid, not a step of the method: reads `bytes` of device memory at `src` once with plain
  * 16-byte-per-lane loads and discards them (`sink`, optional, is a device word that is almost never
  * written; it only keeps the loads alive).  Timed by the caller, it gives the read rate this machine

@@ -21,7 +21,7 @@ SEL_BLOCK = 1024
 F32, BF16, F16 = 0, 1, 2
 
 EXPORTS = ("specattn_topp_select", "specattn_topp_select_union", "specattn_union_workspace_size", "specattn_sparse_decode_attn", "specattn_fused",
-           "specattn_workspace_size", "specattn_stream_read", "specattn_last_error", "specattn_version")
+           "specattn_workspace_size", "specattn_check_lists", "specattn_stream_read", "specattn_last_error", "specattn_version")
 
 
 class SelectArgs(C.Structure):
@@ -100,6 +100,8 @@ def load() -> C.CDLL:
         lib.specattn_fused.argtypes = [C.POINTER(SelectArgs), C.POINTER(AttnArgs), C.c_void_p]
         lib.specattn_workspace_size.restype = C.c_size_t
         lib.specattn_workspace_size.argtypes = [C.POINTER(SelectArgs), C.POINTER(AttnArgs)]
+        lib.specattn_check_lists.restype = C.c_int
+        lib.specattn_check_lists.argtypes = [C.POINTER(AttnArgs), C.c_int64, C.c_void_p, C.c_void_p]
         lib.specattn_stream_read.restype = C.c_int
         lib.specattn_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         lib.specattn_last_error.restype = C.c_char_p
@@ -285,6 +287,12 @@ def specattn_sparse_decode_attn(attn: AttnArgs, stream=None) -> None:
 
 def specattn_fused(sel: SelectArgs, attn: AttnArgs, stream=None) -> None:
     _check(load().specattn_fused(C.byref(sel), C.byref(attn), _stream(stream)))
+
+
+def specattn_check_lists(attn: AttnArgs, n_bad: torch.Tensor, pool_slots: int = 0, stream=None) -> None:
+    """Counts the index-list violations of an attention call into n_bad (int32 device tensor of one element)."""
+    assert n_bad.dtype == torch.int32 and n_bad.numel() == 1
+    _check(load().specattn_check_lists(C.byref(attn), pool_slots, _ptr(n_bad), _stream(stream)))
 
 
 def specattn_stream_read(src: torch.Tensor, sink: Optional[torch.Tensor] = None, stream=None) -> None:

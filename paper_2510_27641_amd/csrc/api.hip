@@ -295,6 +295,16 @@ specattn_status specattn_sparse_decode_attn(const specattn_attn_args *attn, void
     return launch_attn(make_attn(attn), static_cast<hipStream_t>(stream));
 }
 
+specattn_status specattn_check_lists(const specattn_attn_args *attn, int64_t pool_slots, int32_t *n_bad, void *stream)
+{
+    clear_error();
+    specattn_status st = check_attn(attn, false);
+    if (st != SPECATTN_OK) return st;
+    if (!attn->indices) { set_error("a dense call has no index list to check"); return SPECATTN_EINVAL; }
+    if (!n_bad || pool_slots < 0) { set_error("n_bad must not be NULL and pool_slots must not be negative"); return SPECATTN_EINVAL; }
+    return launch_check_lists(make_attn(attn), pool_slots, n_bad, static_cast<hipStream_t>(stream));
+}
+
 specattn_status specattn_fused(const specattn_select_args *sel, const specattn_attn_args *attn, void *stream)
 {
     clear_error();

@@ -195,6 +195,9 @@ int attn_num_splits(int rows, int idx_capacity);
 size_t attn_workspace_bytes(int rows, int G, int T, int d, int idx_capacity);
 specattn_status launch_attn(const AttnLaunch &a, hipStream_t stream);
 
+// counts the index-list violations of an attention call into *n_bad (device memory)
+specattn_status launch_check_lists(const AttnLaunch &a, int64_t pool_slots, int32_t *n_bad, hipStream_t stream);
+
 // matrix-core variant (bf16, d = 128, G*T <= 32)
 bool attn_mfma_supported(const AttnLaunch &a);
 size_t attn_mfma_workspace_bytes(int rows, int G, int T);

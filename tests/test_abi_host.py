@@ -177,3 +177,12 @@ def test_header_is_plain_c(tmp_path):
                            "-L", libdir, "-lspecattn", "-Wl,-rpath," + libdir, "-o", str(exe)])
     out = subprocess.run([str(exe)], capture_output=True, text=True, timeout=120)
     assert out.returncode == 0, out.stdout + out.stderr
+
+
+def test_check_lists_argument_errors():
+    lib = sa.load()
+    lib.specattn_check_lists.argtypes = [C.POINTER(sa.AttnArgs), C.c_int64, C.c_void_p, C.c_void_p]
+    assert lib.specattn_check_lists(C.byref(_attn(indices=None, counts=None)), 0, 0x7000, None) == sa.EINVAL
+    assert lib.specattn_check_lists(C.byref(_attn()), 0, None, None) == sa.EINVAL
+    assert lib.specattn_check_lists(C.byref(_attn()), -1, 0x7000, None) == sa.EINVAL
+    assert lib.specattn_check_lists(C.byref(_attn(H_q=30)), 0, 0x7000, None) == sa.ESHAPE
