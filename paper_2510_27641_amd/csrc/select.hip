@@ -230,6 +230,14 @@ __global__ __launch_bounds__(THREADS, 4) void topp_select_kernel(SelectLaunch a)
 
     SSTAMP(0);
     bool bad = false;
+    // -0.0 is zero; negative, infinite and NaN entries make the row invalid
+    auto clean = [&](uint32_t x) -> uint32_t {
+        if (x == 0x80000000u) return 0u;
+        if (x >= 0x7f800000u) { bad = true; return 0u; }
+        return x;
+    };
+    auto clean4 = [&](uint4 u) -> uint4 { return make_uint4(clean(u.x), clean(u.y), clean(u.z), clean(u.w)); };
+    // Slow form of an item's load (rows that are not 16-byte aligned or hold fewer than four entries).
     auto load_item = [&](int i) -> uint4 {
         const int p = (i * THREADS + tid) * 4;
         uint4 u = make_uint4(0, 0, 0, 0);
@@ -241,20 +249,46 @@ __global__ __launch_bounds__(THREADS, 4) void topp_select_kernel(SelectLaunch a)
             if (p + 2 < len) u.z = __float_as_uint(row[p + 2]);
             if (p + 3 < len) u.w = __float_as_uint(row[p + 3]);
         }
-        // -0.0 is zero; negative, infinite and NaN entries make the row invalid
-        auto clean = [&](uint32_t x) -> uint32_t {
-            if (x == 0x80000000u) return 0u;
-            if (x >= 0x7f800000u) { bad = true; return 0u; }
-            return x;
-        };
-        u.x = clean(u.x); u.y = clean(u.y); u.z = clean(u.z); u.w = clean(u.w);
-        return u;
+        return clean4(u);
+    };
+    // Fast form: every thread issues plain 16-byte loads with nothing between them that waits for data, so
+    // all of a thread's loads are in flight together.  An item that reaches past the row's end loads the
+    // row's last whole vector instead (in bounds) and is masked afterwards; the at most three entries behind
+    // the last whole vector are fetched once, by the thread that owns them.
+    const bool vec_ok = aligned && len >= 4;                   // uniform
+    const int last4 = (len - 4) & ~3;                          // start of the row's last whole vector
+    const int tail_p = (len & 3) ? (len & ~3) : -1;            // start of the partial vector, if any
+    uint4 tailv = make_uint4(0, 0, 0, 0);
+    if (vec_ok && tail_p >= 0 && tid == (tail_p % ITEM) / 4) {
+        tailv.x = __float_as_uint(row[tail_p]);
+        if (tail_p + 1 < len) tailv.y = __float_as_uint(row[tail_p + 1]);
+        if (tail_p + 2 < len) tailv.z = __float_as_uint(row[tail_p + 2]);
+    }
+    auto raw_load = [&](int i) -> uint4 {
+        const int p = (i * THREADS + tid) * 4;
+        return *reinterpret_cast<const uint4 *>(row + (p < last4 ? p : last4));
+    };
+    auto finish_item = [&](int i, uint4 u) -> uint4 {
+        const int p = (i * THREADS + tid) * 4;
+        if (p + 3 >= len) u = (p == tail_p) ? tailv : make_uint4(0, 0, 0, 0);
+        return clean4(u);
     };
 
     uint4 data[RESIDENT ? NV4 : 1];
     if (RESIDENT) {
+        if (vec_ok) {
 #pragma unroll
-        for (int i = 0; i < NV4; ++i) data[i] = (i < n_items) ? load_item(i) : make_uint4(0, 0, 0, 0);
+            for (int i = 0; i < NV4; ++i) data[i] = raw_load(i);
+        } else {
+#pragma unroll
+            for (int i = 0; i < NV4; ++i) data[i] = (i < n_items) ? load_item(i) : make_uint4(0, 0, 0, 0);
+        }
+    }
+    // the histogram is cleared while the loads are in flight
+    clear_hist<THREADS, NB1>(sh);
+    if (RESIDENT && vec_ok) {
+#pragma unroll
+        for (int i = 0; i < NV4; ++i) data[i] = finish_item(i, data[i]);
     }
     auto for_items = [&](auto &&fn) {
         if (RESIDENT) {
@@ -265,8 +299,15 @@ __global__ __launch_bounds__(THREADS, 4) void topp_select_kernel(SelectLaunch a)
             // rows too long for the registers: stream them, four loads in flight per thread
             for (int i0 = 0; i0 < n_items; i0 += 4) {
                 uint4 u[4];
+                if (vec_ok) {
 #pragma unroll
-                for (int k = 0; k < 4; ++k) u[k] = (i0 + k < n_items) ? load_item(i0 + k) : make_uint4(0, 0, 0, 0);
+                    for (int k = 0; k < 4; ++k) u[k] = raw_load(i0 + k);
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) u[k] = finish_item(i0 + k, u[k]);
+                } else {
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) u[k] = (i0 + k < n_items) ? load_item(i0 + k) : make_uint4(0, 0, 0, 0);
+                }
 #pragma unroll
                 for (int k = 0; k < 4; ++k)
                     if (i0 + k < n_items) fn(i0 + k, u[k]);
@@ -276,7 +317,6 @@ __global__ __launch_bounds__(THREADS, 4) void topp_select_kernel(SelectLaunch a)
 
     SSTAMP(1);
     // ---- pass 1: bits[30:20] -----------------------------------------------------------------
-    clear_hist<THREADS, NB1>(sh);
     for_items([&](int, uint4 u) {
         if (u.x) atomicAdd(&sh.hist[u.x >> 20], packed_entry(u.x));
         if (u.y) atomicAdd(&sh.hist[u.y >> 20], packed_entry(u.y));
