@@ -66,6 +66,10 @@ constexpr int MAX_BLOCKS = SPECATTN_MAX_N / SEL_BLOCK;   // selection blocks per
 constexpr int LDS_BYTES = NW * WAVE_LDS +
                           (2 * MAX_ROWS + 1 + NW + 1 + CHUNK_TILES * TILE + MAX_BLOCKS + 1 + 2 * (NW + 1)) * 4 + 48 +
                           2 * 16 * ROW_BYTES;
+#ifndef SPECATTN_KV_AUX
+#define SPECATTN_KV_AUX 2
+#endif
+constexpr int KV_AUX = SPECATTN_KV_AUX;   // cache policy bits of the K/V gathers
 constexpr int SEG_COST = 10;          // cost of starting a row segment, in tiles
 constexpr float RESCALE_SLACK = 8.0f; // log2 units the running max may exceed the reference by
 
@@ -188,8 +192,10 @@ struct Plan {
 };
 
 #ifdef SPECATTN_TIMING
-#define STAMP(k) do { if (threadIdx.x == 0) plan.timing[blockIdx.x * 8 + (k)] = wall_clock64(); } while (0)
+#define STAMP(k) do { if (threadIdx.x == 0) plan.timing[blockIdx.x * 16 + (k)] = wall_clock64(); } while (0)
+#define STAMP_ONCE(k) do { if (threadIdx.x == 0 && !(stamped & (1u << (k)))) { stamped |= 1u << (k); plan.timing[blockIdx.x * 16 + (k)] = wall_clock64(); } } while (0)
 #else
+#define STAMP_ONCE(k) do { } while (0)
 #define STAMP(k) do { } while (0)
 #endif
 
@@ -298,6 +304,9 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
 #pragma unroll
     for (int j = 0; j < 4; ++j) lane_chunk[j] = (int64_t)((l16 ^ swz(4 * j + g)) << 4);
 
+#ifdef SPECATTN_TIMING
+    unsigned stamped = 0;
+#endif
     STAMP(0);
     cost_prefix(a, rows, pre, cnt_lds, wsum);
     STAMP(1);
@@ -503,13 +512,14 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
 #pragma unroll
             for (int i = 0; i < 8; ++i)
                 __builtin_amdgcn_global_load_lds(GLOBAL_PTR(kb0 + ((int64_t)e[i] << 4) + lane_chunk[i & 3]),
-                                                 LDS_PTR(void, wave_lds + i * 1024), 16, 0, 0);
+                                                 LDS_PTR(void, wave_lds + i * 1024), 16, 0, KV_AUX);
 #pragma unroll
             for (int i = 0; i < 8; ++i)
                 __builtin_amdgcn_global_load_lds(GLOBAL_PTR(vb0 + ((int64_t)e[i] << 4) + lane_chunk[i & 3]),
-                                                 LDS_PTR(void, wave_lds + TILE_BYTES + i * 1024), 16, 0, 0);
+                                                 LDS_PTR(void, wave_lds + TILE_BYTES + i * 1024), 16, 0, KV_AUX);
         }
     }
+    STAMP_ONCE(8);
     bool head_start = !FUSED;                 // true until the first chunk of the first segment has begun
 
     while (r < rows) {
@@ -536,7 +546,7 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 const char *src = base + ((int64_t)ent[i] << 4) + lane_chunk[i & 3];
-                __builtin_amdgcn_global_load_lds(GLOBAL_PTR(src), LDS_PTR(void, buf + i * 1024), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds(GLOBAL_PTR(src), LDS_PTR(void, buf + i * 1024), 16, 0, KV_AUX);
             }
         };
 
@@ -556,6 +566,7 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
             if (tid == 0) *tile_ctr = head_start ? ((ch_end - ch_begin) < NW ? (ch_end - ch_begin) : NW) : 0;
             __syncthreads();
             STAMP(2);
+            STAMP_ONCE(9);
             if (ch_begin == lt_begin) {
 #pragma unroll
                 for (int qt = 0; qt < NQT; ++qt) {
@@ -589,6 +600,7 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
                 const int lt = ch_begin + cur;
                 const bool has_next = nxt < n_ch;
                 asm volatile("s_waitcnt vmcnt(8)" ::: "memory");        // K(t) landed; V(t) may be in flight
+                STAMP_ONCE(10);
 
                 // ---- S^T[pos][q] = K Q^T -----------------------------------------------------------
                 f32x4 s[NQT][2];
@@ -680,6 +692,7 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
             }
         }   // chunks
         STAMP(3);
+        STAMP_ONCE(11);
 
         // ---- request what the next segment needs, to arrive while this one is wrapped up --------------
         if (r_next < rows) {

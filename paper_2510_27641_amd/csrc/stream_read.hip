@@ -9,6 +9,9 @@ namespace specattn {
 namespace {
 
 constexpr int UNROLL = 8;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+// streaming (non-temporal) loads: the data is used once and should not displace anything in the caches
+__device__ __forceinline__ u32x4 ld_stream(const uint4 *p) { return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p)); }
 
 __global__ __launch_bounds__(256) void stream_read_kernel(const uint4 *__restrict__ p, size_t n16, uint32_t *sink)
 {
@@ -16,14 +19,14 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const uint4 *__restric
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     uint32_t acc = 0;
     for (; i + (UNROLL - 1) * stride < n16; i += UNROLL * stride) {
-        uint4 v[UNROLL];
+        u32x4 v[UNROLL];
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) v[u] = p[i + u * stride];
+        for (int u = 0; u < UNROLL; ++u) v[u] = ld_stream(p + i + u * stride);
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
     }
     for (; i < n16; i += stride) {
-        const uint4 v = p[i];
+        const u32x4 v = ld_stream(p + i);
         acc ^= v.x ^ v.y ^ v.z ^ v.w;
     }
     // keeps the loads alive; one lane in 2^32 writes, and only if the caller gave a sink
