@@ -94,6 +94,21 @@ struct KvMap {
         const int page = LAYOUT == PAGE_TABLE ? ptab[idx >> page_shift] : (idx >> page_shift);
         return (int64_t)page * stride_page + (int64_t)(idx & mask) * stride_n;
     }
+    // the same for N positions, with the page-table loads (if any) in flight together
+    template <int LAYOUT, int N> __device__ __forceinline__ void rel_n(const int (&idx)[N], uint32_t (&off16)[N]) const
+    {
+        if (LAYOUT == CONTIGUOUS) {
+#pragma unroll
+            for (int i = 0; i < N; ++i) off16[i] = (uint32_t)(((int64_t)idx[i] * stride_n) >> 3);
+            return;
+        }
+        const int mask = (1 << page_shift) - 1;
+        int page[N];
+#pragma unroll
+        for (int i = 0; i < N; ++i) page[i] = LAYOUT == PAGE_TABLE ? ptab[idx[i] >> page_shift] : (idx[i] >> page_shift);
+#pragma unroll
+        for (int i = 0; i < N; ++i) off16[i] = (uint32_t)(((int64_t)page[i] * stride_page + (int64_t)(idx[i] & mask) * stride_n) >> 3);
+    }
 };
 
 template <int LAYOUT> __device__ __forceinline__ KvMap make_map(const AttnLaunch &a, int b, int h)
@@ -207,6 +222,24 @@ __device__ __forceinline__ int row_cost(int count) { return count > 0 ? (count +
 __device__ __forceinline__ void cost_prefix(const AttnLaunch &a, int rows, int *pre, int *cnt, int *wsum)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (rows <= 64) {
+        // Few rows: every wave scans all of them by itself and writes the (identical) tables; a wave reads
+        // back only after its own writes (LDS operations of a wave complete in order), so no barrier is needed.
+        const int c = lane < rows ? attn_row_count(a, lane) : 0;
+        const int cost = row_cost(c);
+        int inc = cost;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int o = __shfl_up(inc, off, 64);
+            if (lane >= off) inc += o;
+        }
+        if (lane < rows) { cnt[lane] = c; pre[lane] = inc - cost; }
+        if (lane == 63) pre[rows] = inc;                  // lanes past the last row add nothing
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        return;
+    }
     const int per = (rows + THREADS - 1) / THREADS;
     const int r0 = tid * per;
     int local = 0;
@@ -238,6 +271,48 @@ __device__ __forceinline__ void cost_prefix(const AttnLaunch &a, int rows, int *
     }
     if (tid == THREADS - 1) pre[rows] = base + inc;
     __syncthreads();
+}
+
+// The share [c0, c1) of the cost line a workgroup takes, and where a row's tiles fall inside it: tile k of
+// row r sits at pre[r] + SEG_COST + k.
+struct Share {
+    int c0, c1;
+    // local tile range of row r inside the share; empty when lt_begin >= lt_end
+    __device__ __forceinline__ void seg_range(const int *pre, const int *cnt, int r, int &lt_begin, int &lt_end) const
+    {
+        const int tiles = (cnt[r] + TILE - 1) / TILE;
+        const int lo = c0 - pre[r] - SEG_COST, hi = c1 - pre[r] - SEG_COST;
+        lt_begin = lo < 0 ? 0 : (lo > tiles ? tiles : lo);
+        lt_end = hi < 0 ? 0 : (hi > tiles ? tiles : hi);
+    }
+    // first row at or after r with work for this workgroup, or `rows`
+    __device__ __forceinline__ int next_seg(const int *pre, const int *cnt, int rows, int r) const
+    {
+        for (; r < rows && pre[r] < c1; ++r) {
+            int lb, le;
+            seg_range(pre, cnt, r, lb, le);
+            if (lb < le) return r;
+        }
+        return rows;
+    }
+    // first row with work for this workgroup, or `rows`
+    __device__ __forceinline__ int first_seg(const int *pre, const int *cnt, int rows) const
+    {
+        int lo = 0, hi = rows;                      // row holding cost c0: pre[r] <= c0 < pre[r+1]
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (pre[mid] <= c0) lo = mid; else hi = mid;
+        }
+        return next_seg(pre, cnt, rows, lo);
+    }
+};
+__device__ __forceinline__ Share make_share(int total, int n_wg, int w)
+{
+    const int share = (total + n_wg - 1) / n_wg;
+    Share s;
+    s.c0 = w * share;
+    s.c1 = (s.c0 + share) < total ? (s.c0 + share) : total;
+    return s;
 }
 
 // One step of merging partial (m, l, o) triples that share the log2-unit convention.
@@ -307,46 +382,42 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
 #ifdef SPECATTN_TIMING
     unsigned stamped = 0;
 #endif
+    // Every kernel argument the main path uses is fetched here, in one batch: left to the compiler, the
+    // argument loads are issued where each is first needed, and every such group is one more round trip to
+    // memory on the way to the first gather.
+#define SPECATTN_PRELOAD(x) asm volatile("" ::"s"(x))
+    SPECATTN_PRELOAD(a.q); SPECATTN_PRELOAD(a.k); SPECATTN_PRELOAD(a.v);
+    SPECATTN_PRELOAD(a.B); SPECATTN_PRELOAD(a.H_q); SPECATTN_PRELOAD(a.H_kv); SPECATTN_PRELOAD(a.T);
+    SPECATTN_PRELOAD(a.sm_scale);
+    SPECATTN_PRELOAD(a.q_stride_b); SPECATTN_PRELOAD(a.q_stride_h); SPECATTN_PRELOAD(a.q_stride_t);
+    SPECATTN_PRELOAD(a.kv_stride_b); SPECATTN_PRELOAD(a.kv_stride_h); SPECATTN_PRELOAD(a.kv_stride_n);
+    SPECATTN_PRELOAD(a.indices); SPECATTN_PRELOAD(a.idx_stride); SPECATTN_PRELOAD(a.counts);
+    SPECATTN_PRELOAD(a.idx_capacity); SPECATTN_PRELOAD(a.dense); SPECATTN_PRELOAD(a.chunk_shift);
+    SPECATTN_PRELOAD(a.g_first); SPECATTN_PRELOAD(a.g_count); SPECATTN_PRELOAD(a.k_new);
+    SPECATTN_PRELOAD(a.out); SPECATTN_PRELOAD(a.out_lowp); SPECATTN_PRELOAD(a.lse);
+    SPECATTN_PRELOAD(plan.part_ml); SPECATTN_PRELOAD(plan.part_o); SPECATTN_PRELOAD(plan.cost_prefix);
+    SPECATTN_PRELOAD(plan.n_wg);
+    if (LAYOUT != CONTIGUOUS) { SPECATTN_PRELOAD(a.page_table); SPECATTN_PRELOAD(a.page_shift); SPECATTN_PRELOAD(a.max_pages); SPECATTN_PRELOAD(a.kv_stride_page); }
+    if (FUSED) { SPECATTN_PRELOAD(a.probs); SPECATTN_PRELOAD(a.probs_stride_b); SPECATTN_PRELOAD(a.probs_stride_h); SPECATTN_PRELOAD(a.seq_lens); SPECATTN_PRELOAD(a.tau); SPECATTN_PRELOAD(a.block_counts); SPECATTN_PRELOAD(a.blocks_per_row); SPECATTN_PRELOAD(a.n_max); }
+#undef SPECATTN_PRELOAD
     STAMP(0);
     cost_prefix(a, rows, pre, cnt_lds, wsum);
     STAMP(1);
     if (blockIdx.x == 0)
         for (int rr = tid; rr <= rows; rr += THREADS) plan.cost_prefix[rr] = pre[rr];
-    // This workgroup's share of the cost line [c0, c1); tile k of row r sits at pre[r] + SEG_COST + k.
+    // This workgroup's share of the cost line
     const int total = pre[rows];
     const int share = (total + plan.n_wg - 1) / plan.n_wg;
-    const int c0 = blockIdx.x * share;
-    const int c1 = (c0 + share) < total ? (c0 + share) : total;
+    const Share sh = make_share(total, plan.n_wg, blockIdx.x);
+    const int c0 = sh.c0, c1 = sh.c1;
     if (c0 >= c1) return;
     const int G = attn_group_heads(a);
     const int QT = G * a.T;
     const float scale2 = a.sm_scale * 1.4426950408889634f;            // scores in log2 units
 
-    // local tile range of row r inside [c0, c1); empty when lt_begin >= lt_end
-    auto seg_range = [&](int r, int &lt_begin, int &lt_end) {
-        const int tiles = (cnt_lds[r] + TILE - 1) / TILE;
-        int lo = c0 - pre[r] - SEG_COST, hi = c1 - pre[r] - SEG_COST;
-        lt_begin = lo < 0 ? 0 : (lo > tiles ? tiles : lo);
-        lt_end = hi < 0 ? 0 : (hi > tiles ? tiles : hi);
-    };
-    // first row at or after r with work for this workgroup, or `rows`
-    auto next_seg = [&](int r) {
-        for (; r < rows && pre[r] < c1; ++r) {
-            int lb, le;
-            seg_range(r, lb, le);
-            if (lb < le) return r;
-        }
-        return rows;
-    };
-    int r;
-    {
-        int lo = 0, hi = rows;                      // row holding cost c0: pre[r] <= c0 < pre[r+1]
-        while (hi - lo > 1) {
-            const int mid = (lo + hi) >> 1;
-            if (pre[mid] <= c0) lo = mid; else hi = mid;
-        }
-        r = next_seg(lo);
-    }
+    auto seg_range = [&](int r, int &lt_begin, int &lt_end) { sh.seg_range(pre, cnt_lds, r, lt_begin, lt_end); };
+    auto next_seg = [&](int r) { return sh.next_seg(pre, cnt_lds, rows, r); };
+    int r = sh.first_seg(pre, cnt_lds, rows);
     if (r >= rows) return;
 
     // ---- per-segment inputs that are fetched ahead of time -------------------------------------------
@@ -377,13 +448,15 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
         const KvMap map = make_map<LAYOUT>(a, b, h);
         const int32_t *idx = a.indices + (int64_t)rr * a.idx_stride;
         const int count = cnt_lds[rr];
+        int jj[EPT], pos[EPT];
 #pragma unroll
         for (int k = 0; k < EPT; ++k) {
-            const int j = tid + k * THREADS;
-            int jj = first + j;
-            jj = jj < count ? jj : count - 1;
-            out[k] = j < n ? (uint32_t)(map.rel<LAYOUT>(attn_list_pos(a, idx, jj)) >> 3) : 0u;
+            jj[k] = first + tid + k * THREADS;
+            jj[k] = jj[k] < count ? jj[k] : count - 1;
         }
+        attn_list_pos_n(a, idx, jj, pos);
+        map.rel_n<LAYOUT>(pos, out);
+        (void)n;                                   // entries past n are computed (in bounds) and never stored
     };
     auto store_entries = [&](int n, const uint32_t (&in)[EPT]) {
 #pragma unroll
@@ -490,23 +563,41 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
     {
         int lb, le;
         seg_range(r, lb, le);
-        fetch_q(r);
+        STAMP_ONCE(12);
         const int n0 = ((le - lb) < CHUNK_TILES ? (le - lb) : CHUNK_TILES) * TILE;
-        if (!FUSED) fetch_entries(r, lb * TILE, n0, ent_pf);
         // Head start: wave w fetches the indices of tile w of the first chunk itself and requests that
-        // tile's rows at once, instead of waiting until the whole chunk's list is staged in LDS.
-        if (!FUSED && wave < n0 / TILE) {
-            const int b = r / a.H_kv, h = r - b * a.H_kv;
-            const KvMap map = make_map<LAYOUT>(a, b, h);
+        // tile's rows at once, instead of waiting until the whole chunk's list is staged in LDS.  These index
+        // loads go out before everything else the segment needs, since the first gathers wait for them.
+        const bool ahead = !FUSED && wave < n0 / TILE;
+        const int b_first = r / a.H_kv, h_first = r - b_first * a.H_kv;
+        const KvMap map_first = make_map<LAYOUT>(a, b_first, h_first);
+        int jj_first[8], raw_first[8];
+        if (ahead) {
             const int32_t *idx = a.indices + (int64_t)r * a.idx_stride;
             const int count = cnt_lds[r];
-            uint32_t e[8];
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                int jj = (lb + wave) * TILE + 4 * i + g;
-                jj = jj < count ? jj : count - 1;
-                e[i] = (uint32_t)(map.rel<LAYOUT>(attn_list_pos(a, idx, jj)) >> 3);
+                jj_first[i] = (lb + wave) * TILE + 4 * i + g;
+                jj_first[i] = jj_first[i] < count ? jj_first[i] : count - 1;
             }
+            attn_list_request_n(a, idx, jj_first, raw_first);
+        }
+        fetch_q(r);
+        if (!FUSED) fetch_entries(r, lb * TILE, n0, ent_pf);
+        // What has been requested so far is taken in before the gathers go out: loads return in order, so a value
+        // left outstanding here could later only be waited for together with the gathers issued behind it.
+        asm volatile("" ::"v"(q_pf));
+        if (!FUSED) {
+#pragma unroll
+            for (int k = 0; k < EPT; ++k) asm volatile("" ::"v"(ent_pf[k]));
+        }
+        STAMP_ONCE(13);
+        if (ahead) {
+            const KvMap &map = map_first;
+            int pos_first[8];
+            attn_list_finish_n(a, jj_first, raw_first, pos_first);
+            uint32_t e[8];
+            map.rel_n<LAYOUT>(pos_first, e);
             const char *kb0 = static_cast<const char *>(a.k) + map.base * 2;
             const char *vb0 = static_cast<const char *>(a.v) + map.base * 2;
 #pragma unroll

@@ -145,6 +145,39 @@ __device__ __forceinline__ int attn_list_pos(const AttnLaunch &a, const int32_t 
     return idx[jj];
 }
 
+// The same for N ranks at once, written so that all N loads are in flight together (a branch per rank would make
+// every load wait for the one before).
+template <int N>
+__device__ __forceinline__ void attn_list_pos_n(const AttnLaunch &a, const int32_t *idx, const int (&jj)[N], int (&pos)[N])
+{
+    if (a.dense) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) pos[i] = jj[i];
+        return;
+    }
+    const int cs = a.chunk_shift, low = (1 << cs) - 1;
+    int v[N];
+#pragma unroll
+    for (int i = 0; i < N; ++i) v[i] = idx[jj[i] >> cs];
+#pragma unroll
+    for (int i = 0; i < N; ++i) pos[i] = (v[i] << cs) | (jj[i] & low);
+}
+// In two steps, for callers that have other loads to issue before they need the positions: the raw list words
+// first (nothing waits), the positions from them later.  Not for dense calls (no list).
+template <int N>
+__device__ __forceinline__ void attn_list_request_n(const AttnLaunch &a, const int32_t *idx, const int (&jj)[N], int (&raw)[N])
+{
+#pragma unroll
+    for (int i = 0; i < N; ++i) raw[i] = a.dense ? jj[i] : idx[jj[i] >> a.chunk_shift];
+}
+template <int N>
+__device__ __forceinline__ void attn_list_finish_n(const AttnLaunch &a, const int (&jj)[N], const int (&raw)[N], int (&pos)[N])
+{
+    const int cs = a.chunk_shift, low = (1 << cs) - 1;
+#pragma unroll
+    for (int i = 0; i < N; ++i) pos[i] = a.dense ? jj[i] : ((raw[i] << cs) | (jj[i] & low));
+}
+
 __device__ __forceinline__ float ld_elem(const void *p, int64_t i, int dtype)
 {
     if (dtype == SPECATTN_BF16) return __uint_as_float((uint32_t) static_cast<const uint16_t *>(p)[i] << 16);

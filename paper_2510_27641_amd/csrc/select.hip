@@ -266,7 +266,10 @@ __global__ __launch_bounds__(THREADS, 4) void topp_select_kernel(SelectLaunch a)
     }
     auto raw_load = [&](int i) -> uint4 {
         const int p = (i * THREADS + tid) * 4;
-        return *reinterpret_cast<const uint4 *>(row + (p < last4 ? p : last4));
+        // streaming load: a row is read once and should not displace anything in the caches
+        typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+        const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(row + (p < last4 ? p : last4)));
+        return make_uint4(v.x, v.y, v.z, v.w);
     };
     auto finish_item = [&](int i, uint4 u) -> uint4 {
         const int p = (i * THREADS + tid) * 4;
