@@ -196,6 +196,10 @@ __device__ __forceinline__ int lds_claim(uint32_t addr, int lane)
     return (int)__builtin_amdgcn_readfirstlane(v);
 }
 
+// Workgroup barrier for data handed over through LDS only: waits for this wave's LDS operations, not for its
+// outstanding global loads (a plain __syncthreads() also waits for every gather and prefetch still in flight).
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n s_barrier" ::: "memory"); }
+
 struct Plan {
     float *part_ml;           // [slots][QTP][2]
     float *part_o;            // [slots][QTP][D]
@@ -227,12 +231,7 @@ __device__ __forceinline__ void cost_prefix(const AttnLaunch &a, int rows, int *
         // back only after its own writes (LDS operations of a wave complete in order), so no barrier is needed.
         const int c = lane < rows ? attn_row_count(a, lane) : 0;
         const int cost = row_cost(c);
-        int inc = cost;
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            const int o = __shfl_up(inc, off, 64);
-            if (lane >= off) inc += o;
-        }
+        const int inc = wave_inclusive_sum(cost);
         if (lane < rows) { cnt[lane] = c; pre[lane] = inc - cost; }
         if (lane == 63) pre[rows] = inc;                  // lanes past the last row add nothing
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -251,14 +250,9 @@ __device__ __forceinline__ void cost_prefix(const AttnLaunch &a, int rows, int *
             local += row_cost(c);
         }
     }
-    int inc = local;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const int o = __shfl_up(inc, off, 64);
-        if (lane >= off) inc += o;
-    }
+    const int inc = wave_inclusive_sum(local);
     if (lane == 63) wsum[wave] = inc;
-    __syncthreads();
+    lds_barrier();
     int base = 0;
     for (int w = 0; w < wave; ++w) base += wsum[w];
     int run = base + inc - local;
@@ -270,7 +264,7 @@ __device__ __forceinline__ void cost_prefix(const AttnLaunch &a, int rows, int *
         }
     }
     if (tid == THREADS - 1) pre[rows] = base + inc;
-    __syncthreads();
+    lds_barrier();
 }
 
 // The share [c0, c1) of the cost line a workgroup takes, and where a row's tiles fall inside it: tile k of
@@ -345,7 +339,7 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
     uint32_t *ent_lds = reinterpret_cast<uint32_t *>(tile_ctr + 1);       // [CHUNK_TILES * TILE] row offsets / 16 B
     float *ml_lds = reinterpret_cast<float *>(ent_lds);                 // wave merge: [NW][2][32], same space
     int *blk_pre = reinterpret_cast<int *>(ent_lds + CHUNK_TILES * TILE);   // fused: [MAX_BLOCKS + 1] kept before block
-    int *scan_ws = blk_pre + MAX_BLOCKS + 1;                            // fused: [2][NW + 1] scan scratch
+    int *scan_ws = blk_pre + MAX_BLOCKS + 1;                            // spare
     char *q_lds = smem + LDS_BYTES - NQT * 16 * ROW_BYTES;              // Q tile [NQT*16][256 B], chunks swizzled like K
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -401,6 +395,21 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
     if (FUSED) { SPECATTN_PRELOAD(a.probs); SPECATTN_PRELOAD(a.probs_stride_b); SPECATTN_PRELOAD(a.probs_stride_h); SPECATTN_PRELOAD(a.seq_lens); SPECATTN_PRELOAD(a.tau); SPECATTN_PRELOAD(a.block_counts); SPECATTN_PRELOAD(a.blocks_per_row); SPECATTN_PRELOAD(a.n_max); }
 #undef SPECATTN_PRELOAD
     STAMP(0);
+    // Fused path, small calls: the per-block kept counts and thresholds of all rows are requested together with
+    // the counts (the row this workgroup starts in is not known yet), so that its first segment need not wait
+    // for them again.  The block counts pass through the list buffer, which is free until the first chunk.
+    constexpr int EPT0 = CHUNK_TILES * TILE / THREADS;
+    const bool bc_all = FUSED && rows <= 64 && rows * a.blocks_per_row <= CHUNK_TILES * TILE;
+    int bc_pf[EPT0];
+    uint32_t tau_pf = 0;
+    if (bc_all) {
+#pragma unroll
+        for (int k = 0; k < EPT0; ++k) {
+            const int j = tid + k * THREADS;
+            bc_pf[k] = a.block_counts[j < rows * a.blocks_per_row ? j : 0];
+        }
+        tau_pf = __float_as_uint(a.tau[lane < rows ? lane : 0]);
+    }
     cost_prefix(a, rows, pre, cnt_lds, wsum);
     STAMP(1);
     if (blockIdx.x == 0)
@@ -467,29 +476,31 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
     };
     // ---- fused path: the list is never read from memory; it is rebuilt from the draft row ----------
     // blk_pre[b] = number of kept positions of row rr before block b (blocks of SEL_BLOCK positions)
+    uint32_t seg_tau = 0;                    // tau* of the current segment's row, as bits
+    bool bc_in_lds = false;                  // the list buffer holds the block counts of all rows
     auto fused_prepare_row = [&](int rr) {
-        __syncthreads();
+        lds_barrier();
         const int32_t *bc = a.block_counts + (int64_t)rr * a.blocks_per_row;
+        const int *bc_lds = reinterpret_cast<const int *>(ent_lds) + rr * a.blocks_per_row;
+        seg_tau = bc_in_lds ? (uint32_t)__builtin_amdgcn_readlane((int)tau_pf, __builtin_amdgcn_readfirstlane(rr)) : __float_as_uint(a.tau[rr]);
         if (wave == 0) {
             int running = 0;
             for (int base = 0; base < a.blocks_per_row; base += 64) {
-                const int c = (base + lane < a.blocks_per_row) ? bc[base + lane] : 0;
-                int inc = c;
-#pragma unroll
-                for (int off = 1; off < 64; off <<= 1) {
-                    const int o = __shfl_up(inc, off, 64);
-                    if (lane >= off) inc += o;
-                }
+                const int c = (base + lane < a.blocks_per_row) ? (bc_in_lds ? bc_lds[base + lane] : bc[base + lane]) : 0;
+                const int inc = wave_inclusive_sum(c);
                 if (base + lane < a.blocks_per_row) blk_pre[base + lane + 1] = running + inc;
-                running += __shfl(inc, 63, 64);
+                running += __builtin_amdgcn_readlane(inc, 63);
             }
             if (lane == 0) blk_pre[0] = 0;
         }
-        __syncthreads();
+        lds_barrier();
+        bc_in_lds = false;                   // the list buffer is about to be overwritten
     };
-    // ent_lds[0 .. n) <- row offsets of the kept positions of rank first .. first + n - 1 of row rr:
-    // scan the draft probabilities against tau* from the block that holds rank `first`, 8 positions
-    // per thread and pass, and number the kept ones by a workgroup-wide prefix sum.
+    // ent_lds[0 .. n) <- row offsets of the kept positions of rank first .. first + n - 1 of row rr.  The block
+    // prefix gives the rank at which every block of SEL_BLOCK positions starts, so the blocks that hold those
+    // ranks are independent: each wave takes every NW-th of them, compares the block's draft probabilities
+    // with tau* (16 positions per lane, as four coalesced 16-byte loads) and numbers the kept ones with
+    // wave-wide prefix sums - no workgroup-wide scan, no barrier between blocks, nothing scanned in vain.
     auto fused_stage = [&](int rr, int first, int n) {
         const int b = rr / a.H_kv, h = rr - b * a.H_kv;
         const KvMap map = make_map<LAYOUT>(a, b, h);
@@ -497,69 +508,88 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
         const bool aligned = (reinterpret_cast<uintptr_t>(row) & 15) == 0;
         int len = a.seq_lens ? a.seq_lens[b] : a.n_max;
         len = len < 0 ? 0 : (len > a.n_max ? a.n_max : len);
-        const uint32_t tau_bits = __float_as_uint(a.tau[rr]);
+        const uint32_t tau_bits = seg_tau;
         const int count = cnt_lds[rr];
         const int last = (first + n) < count ? (first + n) : count;      // ranks [first, last) exist
-        int b0;
-        {
-            int lo = 0, hi = a.blocks_per_row;                           // blk_pre[b0] <= first < blk_pre[b0 + 1]
+        auto block_of = [&](int rank) {                                  // blk_pre[b] <= rank < blk_pre[b + 1]
+            int lo = 0, hi = a.blocks_per_row;
             while (hi - lo > 1) {
                 const int mid = (lo + hi) >> 1;
-                if (blk_pre[mid] <= first) lo = mid; else hi = mid;
+                if (blk_pre[mid] <= rank) lo = mid; else hi = mid;
             }
-            b0 = lo;
-        }
-        int pos = b0 * SEL_BLOCK, rank_base = blk_pre[b0], pass = 0;
-        while (rank_base < last) {                                       // uniform
-            const int p0 = pos + tid * 8;
-            uint32_t u[8];
-            if (aligned && p0 + 7 < len) {
-                const uint4 x = *reinterpret_cast<const uint4 *>(row + p0);
-                const uint4 y = *reinterpret_cast<const uint4 *>(row + p0 + 4);
-                u[0] = x.x; u[1] = x.y; u[2] = x.z; u[3] = x.w; u[4] = y.x; u[5] = y.y; u[6] = y.z; u[7] = y.w;
-            } else {
+            return lo;
+        };
+        const int b0 = block_of(first), b1 = block_of(last - 1);
+        constexpr int QUARTER = SEL_BLOCK / 4;                           // positions one load instruction covers
+        static_assert(QUARTER == 64 * 4, "a wave covers a quarter block with one 16-byte load per lane");
+        const bool vec_ok = aligned && len >= 4;
+        const int last4 = (len - 4) & ~3;                                // start of the row's last whole vector
+        for (int blk = b0 + wave; blk <= b1; blk += 2 * NW) {            // two blocks per round and wave
+            uint4 u[2][4];
 #pragma unroll
-                for (int i = 0; i < 8; ++i) u[i] = (p0 + i < len) ? __float_as_uint(row[p0 + i]) : 0u;
-            }
-            int c = 0;
+            for (int t = 0; t < 2; ++t) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                if (u[i] == 0x80000000u) u[i] = 0u;                      // -0.0 is zero, as in the selection
-                c += u[i] >= tau_bits ? 1 : 0;
-            }
-            int inc = c;
-#pragma unroll
-            for (int off = 1; off < 64; off <<= 1) {
-                const int o = __shfl_up(inc, off, 64);
-                if (lane >= off) inc += o;
-            }
-            int *ws = scan_ws + (pass & 1) * (NW + 1);
-            if (lane == 63) ws[wave] = inc;
-            __syncthreads();
-            int before = 0, all = 0;
-#pragma unroll
-            for (int w = 0; w < NW; ++w) {
-                const int t = ws[w];
-                if (w < wave) before += t;
-                all += t;
-            }
-            int rk = rank_base + before + inc - c;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                if (u[i] >= tau_bits) {
-                    if (rk >= first && rk < last) ent_lds[rk - first] = (uint32_t)(map.rel<LAYOUT>(p0 + i) >> 3);
-                    ++rk;
+                for (int k = 0; k < 4; ++k) {
+                    const int p0 = (blk + t * NW) * SEL_BLOCK + k * QUARTER + lane * 4;
+                    if (vec_ok) {
+                        u[t][k] = *reinterpret_cast<const uint4 *>(row + (p0 < last4 ? p0 : last4));   // inside the row
+                    } else {
+                        u[t][k].x = p0 < len ? __float_as_uint(row[p0]) : 0u;
+                        u[t][k].y = p0 + 1 < len ? __float_as_uint(row[p0 + 1]) : 0u;
+                        u[t][k].z = p0 + 2 < len ? __float_as_uint(row[p0 + 2]) : 0u;
+                        u[t][k].w = p0 + 3 < len ? __float_as_uint(row[p0 + 3]) : 0u;
+                    }
                 }
             }
-            rank_base += all;
-            pos += THREADS * 8;
-            ++pass;
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const int bb = blk + t * NW;
+                if (bb > b1) break;                                      // uniform over the wave
+                int rk = blk_pre[bb];                                    // rank of the block's first kept position
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const int p0 = bb * SEL_BLOCK + k * QUARTER + lane * 4;
+                    uint32_t x[4] = {u[t][k].x, u[t][k].y, u[t][k].z, u[t][k].w};
+                    if (vec_ok && p0 + 3 >= len) {                       // reaches past the row's end: entry by entry
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) x[i] = (p0 + i < len) ? __float_as_uint(row[p0 + i]) : 0u;
+                    }
+                    // kept entries before this lane's four: ballots and per-lane bit counts (no scan)
+                    bool keep[4];
+                    unsigned long long m[4];
+                    int before = 0;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        keep[i] = x[i] != 0x80000000u && x[i] >= tau_bits;       // -0.0 is zero, as in the selection
+                        m[i] = __ballot(keep[i]);
+                        before = __builtin_amdgcn_mbcnt_hi((uint32_t)(m[i] >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m[i], before));
+                    }
+                    int mine = rk + before - first;                      // slot of this lane's first kept entry
+                    const uint32_t off0 = (uint32_t)(map.rel<LAYOUT>(p0) >> 3);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const uint32_t off = LAYOUT == CONTIGUOUS ? off0 + (uint32_t)i * (uint32_t)(map.stride_n >> 3)
+                                                                  : (uint32_t)(map.rel<LAYOUT>(p0 + i) >> 3);
+                        if (keep[i] && mine >= 0 && mine < last - first) ent_lds[mine] = off;
+                        mine += keep[i] ? 1 : 0;
+                    }
+                    rk += __popcll(m[0]) + __popcll(m[1]) + __popcll(m[2]) + __popcll(m[3]);
+                }
+            }
         }
-        __syncthreads();
+        STAMP_ONCE(8);
+        lds_barrier();
+        STAMP_ONCE(10);
         // ranks past the end of the list repeat the last kept position (their scores are masked)
         for (int j = last - first + tid; j < n; j += THREADS) ent_lds[j] = ent_lds[last - first - 1];
     };
 
+    bool first_staged = false;               // fused: the first chunk's list is already in LDS
+    if (bc_all) {
+#pragma unroll
+        for (int k = 0; k < EPT0; ++k) reinterpret_cast<int *>(ent_lds)[tid + k * THREADS] = bc_pf[k];
+        bc_in_lds = true;                    // visible after the barrier that fused_prepare_row starts with
+    }
     {
         int lb, le;
         seg_range(r, lb, le);
@@ -583,6 +613,14 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
             attn_list_request_n(a, idx, jj_first, raw_first);
         }
         fetch_q(r);
+        if (FUSED) {
+            // The first chunk of the first segment is staged right here, ahead of the set-up code of the tile loop
+            // (several hundred instructions that the unfused path runs while its first gathers are in flight).
+            fused_prepare_row(r);
+            STAMP_ONCE(14);
+            fused_stage(r, lb * TILE, n0);
+            first_staged = true;
+        }
         if (!FUSED) fetch_entries(r, lb * TILE, n0, ent_pf);
         // What has been requested so far is taken in before the gathers go out: loads return in order, so a value
         // left outstanding here could later only be waited for together with the gathers issued behind it.
@@ -610,7 +648,7 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
                                                  LDS_PTR(void, wave_lds + TILE_BYTES + i * 1024), 16, 0, KV_AUX);
         }
     }
-    STAMP_ONCE(8);
+    if (!FUSED) STAMP_ONCE(8);
     bool head_start = !FUSED;                 // true until the first chunk of the first segment has begun
 
     while (r < rows) {
@@ -645,17 +683,20 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
             const int ch_end = (ch_begin + CHUNK_TILES) < lt_end ? (ch_begin + CHUNK_TILES) : lt_end;
             // ---- stage this chunk's row offsets in LDS (the first chunk's were fetched ahead) ----------
             if (FUSED) {
-                if (ch_begin == lt_begin) fused_prepare_row(r); else __syncthreads();
+                if (!first_staged) {
+                    if (ch_begin == lt_begin) fused_prepare_row(r); else lds_barrier();
+                    fused_stage(r, ch_begin * TILE, (ch_end - ch_begin) * TILE);
+                }
+                first_staged = false;
                 if (ch_begin == lt_begin) store_q();
-                fused_stage(r, ch_begin * TILE, (ch_end - ch_begin) * TILE);
             } else {
                 if (ch_begin != lt_begin) fetch_entries(r, ch_begin * TILE, (ch_end - ch_begin) * TILE, ent_pf);
-                __syncthreads();                                       // previous users of ent_lds / q_lds are done
+                lds_barrier();                                       // previous users of ent_lds / q_lds are done
                 store_entries((ch_end - ch_begin) * TILE, ent_pf);
                 if (ch_begin == lt_begin) store_q();
             }
             if (tid == 0) *tile_ctr = head_start ? ((ch_end - ch_begin) < NW ? (ch_end - ch_begin) : NW) : 0;
-            __syncthreads();
+            lds_barrier();
             STAMP(2);
             STAMP_ONCE(9);
             if (ch_begin == lt_begin) {
@@ -691,7 +732,7 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
                 const int lt = ch_begin + cur;
                 const bool has_next = nxt < n_ch;
                 asm volatile("s_waitcnt vmcnt(8)" ::: "memory");        // K(t) landed; V(t) may be in flight
-                STAMP_ONCE(10);
+                if (!FUSED) STAMP_ONCE(10);
 
                 // ---- S^T[pos][q] = K Q^T -----------------------------------------------------------
                 f32x4 s[NQT][2];
@@ -797,7 +838,7 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
         // ---- combine the waves of this workgroup: every wave hands its state over lane by lane through its
         //      own, now idle, tile buffers; wave w then reduces and writes the (query tile, dv tile) blocks
         //      k = w * KPW .. of all eight states ---------------------------------------------------------
-        __syncthreads();                         // every wave is done with its buffers and with ent_lds
+        lds_barrier();                         // every wave is done with its buffers and with ent_lds
         STAMP(4);
         float *mlw = ml_lds;                     // [NW][64 lanes][2 * NQT]: m, l of every lane
         {
@@ -811,7 +852,7 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
                 mlw[(wave * 64 + lane) * 2 * NQT + 2 * qt + 1] = l_sum[qt];
             }
         }
-        __syncthreads();
+        lds_barrier();
         STAMP(5);
         // Workgroups w0..w1 share row r: a row owned by one workgroup is finished here; otherwise the
         // partial goes to slot w + r for the merge kernel.

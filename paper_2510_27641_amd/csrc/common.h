@@ -115,6 +115,19 @@ __device__ __forceinline__ int attn_query_head(const AttnLaunch &a, int h, int g
     return h * (a.H_q / a.H_kv) + a.g_first + gh;
 }
 
+// Inclusive prefix sum over the 64 lanes of a wave on the vector ALU (no LDS traffic): shifts by 1, 2, 4, 8 inside
+// each row of 16 lanes, then lane 15 of rows 0 and 2 into rows 1 and 3, then lane 31 into rows 2 and 3.
+__device__ __forceinline__ int wave_inclusive_sum(int v)
+{
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false);    // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false);    // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false);    // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false);    // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);    // row_bcast:15 into rows 1 and 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);    // row_bcast:31 into rows 2 and 3
+    return v;
+}
+
 // Number of positions row r attends to: the kept count (clamped to the list capacity), or the
 // sequence length when there is no list.  With a chunk list: the kept chunks' positions, less the
 // part of the last kept chunk that lies past the sequence length (the list is ascending, so only
