@@ -254,8 +254,8 @@ size_t attn_workspace_bytes(int rows, int G, int T, int d, int idx_capacity)
     const size_t qt = (size_t)G * T;
     size_t bytes = (size_t)rows * ns * qt * (size_t)(d + 2) * sizeof(float);
     bytes = (bytes + 255) & ~(size_t)255;
-    if (d == 128 && qt <= 32) {                      // the matrix-core variant may take this shape
-        const size_t other = attn_mfma_workspace_bytes(rows, G, T);
+    if (d == 128) {                                  // the matrix-core variant may take this shape (larger groups of
+        const size_t other = attn_mfma_workspace_bytes(rows, G, T);   // query heads run as several launches over it)
         if (other > bytes) bytes = other;
     }
     return bytes;

@@ -70,7 +70,10 @@ constexpr int LDS_BYTES = NW * WAVE_LDS +
 #define SPECATTN_KV_AUX 2
 #endif
 constexpr int KV_AUX = SPECATTN_KV_AUX;   // cache policy bits of the K/V gathers
-constexpr int SEG_COST = 10;          // cost of starting a row segment, in tiles
+#ifndef SPECATTN_SEG_COST
+#define SPECATTN_SEG_COST 12
+#endif
+constexpr int SEG_COST = SPECATTN_SEG_COST;          // cost of starting a row segment, in tiles
 constexpr float RESCALE_SLACK = 8.0f; // log2 units the running max may exceed the reference by
 
 // 16-byte chunk c of row `row` is stored in slot c ^ swz(row): makes both the K fragment reads
@@ -300,13 +303,22 @@ struct Share {
         return next_seg(pre, cnt, rows, lo);
     }
 };
+// The first min(n_wg, total) workgroups share the line: workgroup w takes [w * total / n, (w + 1) * total / n),
+// so shares differ by at most one unit and none of them is empty (every workgroup between the first and the
+// last of a row therefore holds tiles of that row, which the merge relies on).
 __device__ __forceinline__ Share make_share(int total, int n_wg, int w)
 {
-    const int share = (total + n_wg - 1) / n_wg;
+    const int n = n_wg < total ? n_wg : total;
     Share s;
-    s.c0 = w * share;
-    s.c1 = (s.c0 + share) < total ? (s.c0 + share) : total;
+    s.c0 = w < n ? (int)(((int64_t)w * total) / n) : total;
+    s.c1 = w < n ? (int)(((int64_t)(w + 1) * total) / n) : total;
     return s;
+}
+// the workgroup whose share holds cost position c (0 <= c < total)
+__device__ __forceinline__ int share_of(int total, int n_wg, int c)
+{
+    const int n = n_wg < total ? n_wg : total;
+    return (int)((((int64_t)c + 1) * n - 1) / total);
 }
 
 // One step of merging partial (m, l, o) triples that share the log2-unit convention.
@@ -416,7 +428,6 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
         for (int rr = tid; rr <= rows; rr += THREADS) plan.cost_prefix[rr] = pre[rr];
     // This workgroup's share of the cost line
     const int total = pre[rows];
-    const int share = (total + plan.n_wg - 1) / plan.n_wg;
     const Share sh = make_share(total, plan.n_wg, blockIdx.x);
     const int c0 = sh.c0, c1 = sh.c1;
     if (c0 >= c1) return;
@@ -565,12 +576,13 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
                         before = __builtin_amdgcn_mbcnt_hi((uint32_t)(m[i] >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m[i], before));
                     }
                     int mine = rk + before - first;                      // slot of this lane's first kept entry
-                    const uint32_t off0 = (uint32_t)(map.rel<LAYOUT>(p0) >> 3);
+                    const uint32_t off0 = LAYOUT == CONTIGUOUS ? (uint32_t)(map.rel<LAYOUT>(p0) >> 3) : 0u;
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        const uint32_t off = LAYOUT == CONTIGUOUS ? off0 + (uint32_t)i * (uint32_t)(map.stride_n >> 3)
-                                                                  : (uint32_t)(map.rel<LAYOUT>(p0 + i) >> 3);
-                        if (keep[i] && mine >= 0 && mine < last - first) ent_lds[mine] = off;
+                        // (kept positions lie below the row's length, so the page-table lookup stays inside the table)
+                        if (keep[i] && mine >= 0 && mine < last - first)
+                            ent_lds[mine] = LAYOUT == CONTIGUOUS ? off0 + (uint32_t)i * (uint32_t)(map.stride_n >> 3)
+                                                                 : (uint32_t)(map.rel<LAYOUT>(p0 + i) >> 3);
                         mine += keep[i] ? 1 : 0;
                     }
                     rk += __popcll(m[0]) + __popcll(m[1]) + __popcll(m[2]) + __popcll(m[3]);
@@ -856,7 +868,7 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
         STAMP(5);
         // Workgroups w0..w1 share row r: a row owned by one workgroup is finished here; otherwise the
         // partial goes to slot w + r for the merge kernel.
-        const int w0 = (pre[r] + SEG_COST) / share, w1 = (pre[r + 1] - 1) / share;
+        const int w0 = share_of(total, plan.n_wg, pre[r] + SEG_COST), w1 = share_of(total, plan.n_wg, pre[r + 1] - 1);
         {
             constexpr int KPW = NQT * 8 / NW;    // blocks per wave (2 or 1)
             const int slot = blockIdx.x + r;
@@ -933,8 +945,7 @@ __global__ void merge_partials_kernel(AttnLaunch a, Plan plan, int qtp)
     }
     Merge acc;
     if (p0 != p1) {
-        const int share = (total + plan.n_wg - 1) / plan.n_wg;
-        const int w0 = (p0 + SEG_COST) / share, w1 = (p1 - 1) / share;
+        const int w0 = share_of(total, plan.n_wg, p0 + SEG_COST), w1 = share_of(total, plan.n_wg, p1 - 1);
         if (w0 == w1 && !tail) return;              // finished by its only workgroup
         for (int wb = w0; wb <= w1; wb += 8) {      // eight partials per round trip
             float mw[8], lw[8], ow[8];
@@ -995,6 +1006,11 @@ static specattn_status launch_chunk(const AttnLaunch &a, hipStream_t stream)
     Plan plan;
     plan.n_wg = attn_mfma_workgroups();
     const size_t slots = (size_t)plan.n_wg + rows;
+    // every workgroup may leave a partial in slot (workgroup + row): never launch over a workspace that cannot hold them
+    if (!a.workspace || a.workspace_bytes < attn_mfma_workspace_bytes(rows, G, a.T)) {
+        set_error("attention workspace has %zu bytes, %zu needed", a.workspace_bytes, attn_mfma_workspace_bytes(rows, G, a.T));
+        return SPECATTN_EWORKSPACE;
+    }
     char *ws = static_cast<char *>(a.workspace);
     plan.cost_prefix = reinterpret_cast<int32_t *>(ws);
     ws += (((size_t)rows + 1) * sizeof(int32_t) + 255) & ~(size_t)255;

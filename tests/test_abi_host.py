@@ -102,6 +102,23 @@ def test_workspace_size_is_monotone_and_zero_for_selection():
     assert sa.specattn_workspace_size(None, _attn(H_q=30)) == 0
 
 
+@pytest.mark.parametrize("H_q", [8, 16, 32, 64, 128])
+@pytest.mark.parametrize("B,cap", [(1, 4096), (2, 3000), (8, 32768), (64, 512)])
+def test_attention_workspace_holds_every_partial_of_the_matrix_core_route(H_q, B, cap):
+    """The bf16 / fp16, d = 128 route leaves one partial per (workgroup, row) in slot workgroup + row, at most
+    32 query rows wide (larger groups of query heads run as several launches over the same slots), behind a
+    256-byte aligned table of rows + 1 ints.  The size query must cover that for any number of query heads per
+    kv head (with 8 heads per kv head and T = 5 it once did not: 40 query rows took the portable route's size)."""
+    H_kv, T, d = 8, 5, 128
+    a = _attn(B=B, H_q=H_q, idx_capacity=cap, idx_stride_row=cap, n_max=max(cap, 4096),
+              q_stride_b=H_q * T * d, kv_stride_b=H_kv * max(cap, 4096) * d, kv_stride_h=max(cap, 4096) * d)
+    rows = B * H_kv
+    n_wg = 256                                                   # no device here: the library assumes 256 compute units
+    qtp = 16 if (H_q // H_kv) * T <= 16 else 32
+    need = ((rows + 1) * 4 + 255) // 256 * 256 + (n_wg + rows) * qtp * (d + 2) * 4
+    assert sa.specattn_workspace_size(None, a) >= need
+
+
 def test_chunk_selection_workspace_size():
     assert sa.specattn_workspace_size(_sel(chunk_size=16), None) == 2 * 4 * 64 * 4
     assert sa.specattn_workspace_size(_sel(chunk_size=16, n_max=1000, probs_stride_h=1024), None) == ((2 * 4 * 63 * 4 + 255) // 256) * 256
