@@ -303,6 +303,14 @@ struct Share {
         return next_seg(pre, cnt, rows, lo);
     }
 };
+// floor(a / b) for 0 <= a < 2^52, 0 < b < 2^31 in one fp64 division instead of the long 64-bit integer division
+// sequence: both operands are exact in fp64, the correctly rounded quotient can only reach the next integer from
+// below when a / b is within 2^-53 of it, and a true quotient that is no integer lies at least 1 / b below it.
+__device__ __forceinline__ int floor_div(int64_t a, int b)
+{
+    return (int)floor((double)a / (double)b);
+}
+
 // The first min(n_wg, total) workgroups share the line: workgroup w takes [w * total / n, (w + 1) * total / n),
 // so shares differ by at most one unit and none of them is empty (every workgroup between the first and the
 // last of a row therefore holds tiles of that row, which the merge relies on).
@@ -310,15 +318,15 @@ __device__ __forceinline__ Share make_share(int total, int n_wg, int w)
 {
     const int n = n_wg < total ? n_wg : total;
     Share s;
-    s.c0 = w < n ? (int)(((int64_t)w * total) / n) : total;
-    s.c1 = w < n ? (int)(((int64_t)(w + 1) * total) / n) : total;
+    s.c0 = w < n ? floor_div((int64_t)w * total, n) : total;
+    s.c1 = w < n ? floor_div((int64_t)(w + 1) * total, n) : total;
     return s;
 }
 // the workgroup whose share holds cost position c (0 <= c < total)
 __device__ __forceinline__ int share_of(int total, int n_wg, int c)
 {
     const int n = n_wg < total ? n_wg : total;
-    return (int)((((int64_t)c + 1) * n - 1) / total);
+    return floor_div(((int64_t)c + 1) * n - 1, total);
 }
 
 // One step of merging partial (m, l, o) triples that share the log2-unit convention.
