@@ -640,12 +640,29 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
             STAMP_ONCE(14);
             fused_stage(r, lb * TILE, n0);
             first_staged = true;
+            // Head start as on the unfused path: wave w requests tile w of the staged chunk at once.
+            lds_barrier();                       // the padding entries behind the end of the list are in place
+            asm volatile("" ::"v"(q_pf));        // Q has arrived long ago; taken in before the gathers (see below)
+            if (wave < n0 / TILE) {
+                uint32_t e[8];
+                lds_read_entries(e, ent_addr + (uint32_t)((wave * TILE + g) << 2));
+                const char *kb0 = static_cast<const char *>(a.k) + map_first.base * 2;
+                const char *vb0 = static_cast<const char *>(a.v) + map_first.base * 2;
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    __builtin_amdgcn_global_load_lds(GLOBAL_PTR(kb0 + ((int64_t)e[i] << 4) + lane_chunk[i & 3]),
+                                                     LDS_PTR(void, wave_lds + i * 1024), 16, 0, KV_AUX);
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    __builtin_amdgcn_global_load_lds(GLOBAL_PTR(vb0 + ((int64_t)e[i] << 4) + lane_chunk[i & 3]),
+                                                     LDS_PTR(void, wave_lds + TILE_BYTES + i * 1024), 16, 0, KV_AUX);
+            }
         }
         if (!FUSED) fetch_entries(r, lb * TILE, n0, ent_pf);
         // What has been requested so far is taken in before the gathers go out: loads return in order, so a value
         // left outstanding here could later only be waited for together with the gathers issued behind it.
-        asm volatile("" ::"v"(q_pf));
         if (!FUSED) {
+            asm volatile("" ::"v"(q_pf));
 #pragma unroll
             for (int k = 0; k < EPT; ++k) asm volatile("" ::"v"(ent_pf[k]));
         }
@@ -669,7 +686,7 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
         }
     }
     if (!FUSED) STAMP_ONCE(8);
-    bool head_start = !FUSED;                 // true until the first chunk of the first segment has begun
+    bool head_start = true;                   // true until the first chunk of the first segment has begun
 
     while (r < rows) {
         int lt_begin, lt_end;
