@@ -400,11 +400,15 @@ def main():
     if not args.no_cpu_baseline:
         import oracle
         cores = oracle.set_threads(0)
-        n_samp = min(4, L)                                          # whole layers 0 .. n_samp-1
+        budget_s = 20.0                                             # whole layers 0, 1, ... until about this much CPU work
+        n_samp = 0
         t_sel = t_att = 0.0
         samp_bytes = 0.0
         worst = 0.0
-        for layer in range(n_samp):
+        for layer in range(L):
+            if t_sel + t_att > budget_s:
+                break
+            n_samp += 1
             rows_s = probs_host[layer * B:(layer + 1) * B].reshape(R, n)
             t0 = time.time()
             ref = oracle.topp_select(rows_s, top_p)
