@@ -395,6 +395,6 @@ size_t specattn_workspace_size(const specattn_select_args *sel, const specattn_a
 
 const char *specattn_last_error(void) { return g_error; }
 
-int specattn_version(void) { return 1006; }
+int specattn_version(void) { return 1007; }
 
 }  // extern "C"
