@@ -3,6 +3,7 @@
 Only tests/, the smoke check and the bench's cpu_baseline leg may import this
 package.  It never imports the HIP binding.
 """
+from .layer_map import layer_map, layer_map_exhaustive, layer_similarity, layer_similarity_fast, monotone_maps  # noqa: F401
 from .oracle import (  # noqa: F401
     ROW_INVALID,
     ROW_NEAR_BOUNDARY,
