@@ -42,7 +42,7 @@ def parse():
     ap.add_argument("--workload", choices=["headline", "side"], default="headline",
                     help="headline: the 32-layer verify step (one JSON line).  side: the other workloads and calls "
                          "(8k layer, long-context sweep, ragged paged batch, dense, new tokens, chunks, union, large "
-                         "GQA group), one JSON line each")
+                         "GQA group, offline layer mapping), one JSON line each")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device copy (reference for rocprofv3 --pmc byte counters)")
     return ap.parse_args()
@@ -177,6 +177,22 @@ def side_workloads(torch, sa, W):
     emit("selection in chunks of 16 + attention over chunk lists", rows=L * R, n=n, select_tokens_us=round(t_tok, 1),
          select_chunks_us=round(t_chk, 1), kept_chunk_fraction=round(float(cc.float().mean().item()) / nc, 4),
          attention_us=round(t, 1), attention_GBps=round(chunk_bytes / t / 1e3, 1))
+    # ---- offline layer mapping (runs once per model pair, not per decoding step) --------------------------------
+    for (m_, n_, rows_, L_) in ((22, 32, 64, 2048), (32, 80, 256, 4096)):
+        ad, av = W.layer_attention_maps(seed=0, m=m_, n=n_, rows=rows_, L=L_)
+        ad_d, av_d = torch.from_numpy(ad).cuda(), torch.from_numpy(av).cuda()
+        S = torch.empty((m_, n_), dtype=torch.float64, device="cuda")
+        fmap = torch.empty((n_,), dtype=torch.int32, device="cuda")
+        tot = torch.empty((1,), dtype=torch.float64, device="cuda")
+        ws1 = sa.alloc_workspace(int(sa.load().specattn_layer_similarity_workspace_size(m_, n_, rows_, L_)))
+        ws2 = sa.alloc_workspace(int(sa.load().specattn_layer_map_workspace_size(m_, n_)))
+        t_sim = timed(lambda: sa.specattn_layer_similarity(ad_d, av_d, S, ws1), reps=5, warm=1)
+        t_map = timed(lambda: sa.specattn_layer_map(S, fmap, tot, ws2), reps=5, warm=1)
+        terms = m_ * n_ * rows_ * L_
+        emit(f"offline layer mapping, {m_} draft x {n_} verifier layers, {rows_} rows x {L_} positions",
+             similarity_us=round(t_sim, 1), terms=terms, Gterms_per_s=round(terms / t_sim / 1e3, 2),
+             input_MB=round((m_ + n_) * rows_ * L_ * 4 / 1e6, 1), alignment_us=round(t_map, 1),
+             total_score=round(float(tot.item()), 4))
     for hd, steps in ((8, 4), (32, 4)):
         pu = torch.from_numpy(W.draft_step_probs(np.random.default_rng(2), B, hd, steps, n)).cuda()
         iu = torch.zeros((R, n), dtype=torch.int32, device="cuda")

@@ -209,6 +209,35 @@ size_t specattn_union_workspace_size(const specattn_union_args *args);
 specattn_status specattn_topp_select(const specattn_select_args *sel, void *workspace,
                                      size_t workspace_bytes, void *stream);
 
+/*
+ * Offline layer mapping (Section 3.3, Eq. 4; Appendix B, Algorithm 3): which draft layer's attention a verifier
+ * layer's selection is taken from.  Run once per model pair on attention rows collected from a representative
+ * data set; nothing of it runs during decoding.
+ *
+ * specattn_layer_similarity: attn_draft [m][rows][L], attn_verifier [n][rows][L], fp32 probabilities (>= 0;
+ * positions a row cannot see hold 0), contiguous, device memory; row r of every layer of both models belongs to
+ * the same query of the same text.  S [m][n] fp64 (device, out): S[i*n + j] = -(1/rows) * sum_r
+ * D_KL(attn_verifier[j][r] || attn_draft[i][r]) - Eq. 4 averaged over the rows (natural logarithm; a verifier
+ * entry of 0 adds nothing; a draft entry of 0 under verifier mass gives -infinity).  Workspace:
+ * specattn_layer_similarity_workspace_size bytes, 256-byte aligned.  m*n <= 65535.
+ *
+ * specattn_layer_map: S [m][n] fp64 as above (device); f [n] int32 (device, out): the non-decreasing map from
+ * verifier layer j to draft layer f[j] (0-based) that maximises sum_j S[f[j]*n + j] (draft layers may be
+ * skipped or serve several verifier layers); *total (device, out) that maximum.  Among equal maxima the
+ * recurrence of Algorithm 3 keeps the smallest draft index at every step.  m <= 1024, n <= 65535.  Workspace:
+ * specattn_layer_map_workspace_size bytes, 256-byte aligned.
+ *
+ * Both: asynchronous on stream; SPECATTN_EINVAL / SPECATTN_ESHAPE / SPECATTN_EWORKSPACE before anything is
+ * launched; the size queries return 0 for sizes the calls reject.
+ */
+size_t specattn_layer_similarity_workspace_size(int32_t m, int32_t n, int32_t rows, int32_t L);
+specattn_status specattn_layer_similarity(const float *attn_draft, const float *attn_verifier, int32_t m, int32_t n,
+                                          int32_t rows, int32_t L, double *S, void *workspace,
+                                          size_t workspace_bytes, void *stream);
+size_t specattn_layer_map_workspace_size(int32_t m, int32_t n);
+specattn_status specattn_layer_map(const double *S, int32_t m, int32_t n, int32_t *f, double *total,
+                                   void *workspace, size_t workspace_bytes, void *stream);
+
 /* Attention alone, over an index list already in device memory. */
 specattn_status specattn_sparse_decode_attn(const specattn_attn_args *attn, void *stream);
 

@@ -21,7 +21,8 @@ SEL_BLOCK = 1024
 F32, BF16, F16 = 0, 1, 2
 
 EXPORTS = ("specattn_topp_select", "specattn_topp_select_union", "specattn_union_workspace_size", "specattn_sparse_decode_attn", "specattn_fused",
-           "specattn_workspace_size", "specattn_check_lists", "specattn_stream_read", "specattn_last_error", "specattn_version")
+           "specattn_workspace_size", "specattn_layer_similarity", "specattn_layer_similarity_workspace_size",
+           "specattn_layer_map", "specattn_layer_map_workspace_size", "specattn_check_lists", "specattn_stream_read", "specattn_last_error", "specattn_version")
 
 
 class SelectArgs(C.Structure):
@@ -100,6 +101,16 @@ def load() -> C.CDLL:
         lib.specattn_fused.argtypes = [C.POINTER(SelectArgs), C.POINTER(AttnArgs), C.c_void_p]
         lib.specattn_workspace_size.restype = C.c_size_t
         lib.specattn_workspace_size.argtypes = [C.POINTER(SelectArgs), C.POINTER(AttnArgs)]
+        lib.specattn_layer_similarity_workspace_size.restype = C.c_size_t
+        lib.specattn_layer_similarity_workspace_size.argtypes = [C.c_int32] * 4
+        lib.specattn_layer_similarity.restype = C.c_int
+        lib.specattn_layer_similarity.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                                  C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        lib.specattn_layer_map_workspace_size.restype = C.c_size_t
+        lib.specattn_layer_map_workspace_size.argtypes = [C.c_int32] * 2
+        lib.specattn_layer_map.restype = C.c_int
+        lib.specattn_layer_map.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                           C.c_size_t, C.c_void_p]
         lib.specattn_check_lists.restype = C.c_int
         lib.specattn_check_lists.argtypes = [C.POINTER(AttnArgs), C.c_int64, C.c_void_p, C.c_void_p]
         lib.specattn_stream_read.restype = C.c_int
@@ -283,6 +294,29 @@ def specattn_topp_select_union(args: UnionArgs, workspace: torch.Tensor, stream=
 
 def specattn_sparse_decode_attn(attn: AttnArgs, stream=None) -> None:
     _check(load().specattn_sparse_decode_attn(C.byref(attn), _stream(stream)))
+
+
+def specattn_layer_similarity(attn_draft: torch.Tensor, attn_verifier: torch.Tensor, S: torch.Tensor,
+                              workspace: Optional[torch.Tensor] = None, stream=None) -> None:
+    """attn_draft [m, rows, L], attn_verifier [n, rows, L] fp32 contiguous; S [m, n] fp64 (out)."""
+    assert attn_draft.dtype == attn_verifier.dtype == torch.float32 and S.dtype == torch.float64
+    assert attn_draft.is_contiguous() and attn_verifier.is_contiguous() and S.is_contiguous()
+    m, rows, L = attn_draft.shape
+    n = attn_verifier.shape[0]
+    assert tuple(attn_verifier.shape[1:]) == (rows, L) and tuple(S.shape) == (m, n)
+    ws = workspace if workspace is not None else alloc_workspace(int(load().specattn_layer_similarity_workspace_size(m, n, rows, L)))
+    _check(load().specattn_layer_similarity(_ptr(attn_draft), _ptr(attn_verifier), m, n, rows, L, _ptr(S), _ptr(ws),
+                                            ws.numel(), _stream(stream)))
+
+
+def specattn_layer_map(S: torch.Tensor, f: torch.Tensor, total: torch.Tensor, workspace: Optional[torch.Tensor] = None,
+                       stream=None) -> None:
+    """S [m, n] fp64 contiguous; f [n] int32 (out); total [1] fp64 (out)."""
+    assert S.dtype == torch.float64 and S.is_contiguous() and S.dim() == 2
+    m, n = S.shape
+    assert f.dtype == torch.int32 and f.numel() == n and total.dtype == torch.float64 and total.numel() == 1
+    ws = workspace if workspace is not None else alloc_workspace(int(load().specattn_layer_map_workspace_size(m, n)))
+    _check(load().specattn_layer_map(_ptr(S), m, n, _ptr(f), _ptr(total), _ptr(ws), ws.numel(), _stream(stream)))
 
 
 def specattn_fused(sel: SelectArgs, attn: AttnArgs, stream=None) -> None:

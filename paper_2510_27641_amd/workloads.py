@@ -271,3 +271,32 @@ def ragged_paged(seed: int = 0, B: int = 64, len_lo: int = 4096, len_hi: int = 6
         q = k = v = np.zeros((0,), dtype=np.float32)
     return Workload("ragged_paged", B, H_q, H_kv, T, d, n, top_p, "bf16", probs, q, k, v,
                     seq_lens=lens, page_table=table, n_pool_pages=total_pages)
+
+
+def layer_attention_maps(seed: int = 0, m: int = 22, n: int = 32, rows: int = 64, L: int = 2048):
+    """Aligned causal attention rows of a draft model with m layers and a verifier with n layers (stand-ins for the
+    rows collected on a text corpus): row r sees the first len_r positions; a layer at relative depth t in [0, 1]
+    puts weight on the first position (sink, growing with depth), on a recency window (narrowing with depth) and
+    on a few content positions shared by both models, over layer-specific noise.  Layers of the two models at the
+    same relative depth therefore resemble each other.  Returns (attn_draft [m, rows, L], attn_verifier
+    [n, rows, L]) float32, rows summing to 1 over the visible positions and 0 beyond."""
+    rng = np.random.default_rng(seed)
+    lens = rng.integers(min(L, max(8, L // 8)), L + 1, size=rows)
+    content = [rng.choice(int(lens[r]), size=min(8, int(lens[r])), replace=False) for r in range(rows)]
+
+    def model(layers):
+        out = np.zeros((layers, rows, L), dtype=np.float64)
+        for i in range(layers):
+            t = i / max(layers - 1, 1)
+            for r in range(rows):
+                ln = int(lens[r])
+                logit = 0.5 * rng.standard_normal(ln)
+                logit[0] += 2.0 + 4.0 * t
+                width = int(min(ln, max(2, round(ln * (0.25 - 0.2 * t)))))
+                logit[ln - width:] += 2.0
+                logit[content[r]] += 1.0 + 3.0 * np.sin(np.pi * t)
+                e = np.exp(logit - logit.max())
+                out[i, r, :ln] = e / e.sum()
+        return out.astype(np.float32)
+
+    return model(m), model(n)

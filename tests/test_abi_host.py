@@ -203,3 +203,25 @@ def test_check_lists_argument_errors():
     assert lib.specattn_check_lists(C.byref(_attn()), 0, None, None) == sa.EINVAL
     assert lib.specattn_check_lists(C.byref(_attn()), -1, 0x7000, None) == sa.EINVAL
     assert lib.specattn_check_lists(C.byref(_attn(H_q=30)), 0, 0x7000, None) == sa.ESHAPE
+
+
+def test_layer_mapping_argument_errors_and_sizes():
+    lib = sa.load()
+    assert lib.specattn_layer_similarity_workspace_size(22, 32, 64, 2048) % 256 == 0
+    assert lib.specattn_layer_similarity_workspace_size(22, 32, 64, 2048) >= 22 * 32 * 8
+    assert lib.specattn_layer_similarity_workspace_size(0, 32, 64, 2048) == 0
+    assert lib.specattn_layer_similarity_workspace_size(300, 300, 64, 2048) == 0          # more than 65535 pairs
+    assert lib.specattn_layer_map_workspace_size(22, 32) == ((22 * 32 * 4 + 255) // 256) * 256
+    assert lib.specattn_layer_map_workspace_size(1025, 32) == 0
+    assert lib.specattn_layer_similarity(None, 0x2000, 2, 2, 2, 8, 0x3000, 0x10000, 1 << 20, None) == sa.EINVAL
+    assert lib.specattn_layer_similarity(0x1000, 0x2000, 0, 2, 2, 8, 0x3000, 0x10000, 1 << 20, None) == sa.EINVAL
+    assert lib.specattn_layer_similarity(0x1000, 0x2000, 300, 300, 2, 8, 0x3000, 0x10000, 1 << 20, None) == sa.ESHAPE
+    assert lib.specattn_layer_similarity(0x1000, 0x2000, 2, 2, 2, 8, 0x3000, None, 0, None) == sa.EWORKSPACE
+    assert lib.specattn_layer_similarity(0x1000, 0x2000, 2, 2, 2, 8, 0x3000, 0x10040, 1 << 20, None) == sa.EWORKSPACE
+    assert lib.specattn_layer_similarity(0x1000, 0x2000, 2, 2, 2, 8, 0x3000, 0x10000, 8, None) == sa.EWORKSPACE
+    assert lib.specattn_layer_map(None, 2, 2, 0x2000, 0x3000, 0x10000, 1 << 20, None) == sa.EINVAL
+    assert lib.specattn_layer_map(0x1000, 2, 0, 0x2000, 0x3000, 0x10000, 1 << 20, None) == sa.EINVAL
+    assert lib.specattn_layer_map(0x1000, 2000, 2, 0x2000, 0x3000, 0x10000, 1 << 20, None) == sa.ESHAPE
+    assert lib.specattn_layer_map(0x1000, 2, 2, 0x2000, 0x3000, None, 0, None) == sa.EWORKSPACE
+    assert lib.specattn_layer_map(0x1000, 2, 2, 0x2000, 0x3000, 0x10000, 8, None) == sa.EWORKSPACE
+    assert sa.last_error() != ""
