@@ -111,3 +111,59 @@ def test_nothing_outside_the_outputs_is_written():
     torch.cuda.synchronize()
     for buf in (ubuf, bbuf, kbuf, cbuf):
         assert _margins_intact(buf, -77)
+
+
+@pytest.mark.parametrize("H_q", [32, 64, 128])
+@pytest.mark.parametrize("mode", ["list", "fused"])
+def test_workspace_is_never_exceeded_whatever_the_group_size(H_q, mode):
+    """Every workgroup may leave a partial in the workspace, and groups of more than 32 query rows per kv head run
+    as several launches over it: a wide margin behind the workspace of the size the query reports stays untouched."""
+    w = W.llama8b_layer(seed=55, B=2, n=6000, top_p=0.9, H_q=H_q, H_kv=8)
+    q, k, v = kv_tensors(w)
+    probs = dev(w.probs)
+    B, H, n = probs.shape
+    idx = torch.zeros((B * H, n), dtype=torch.int32, device="cuda")
+    cnt = torch.zeros((B * H,), dtype=torch.int32, device="cuda")
+    out = torch.full(tuple(q.shape), float("nan"), dtype=torch.float32, device="cuda")
+    sel = sa.select_args(probs, w.top_p, indices=idx if mode == "list" else None, counts=cnt)
+    att = sa.attn_args(q, k, v, out=out, indices=idx, counts=cnt) if mode == "list" else sa.attn_args(q, k, v, out=out)
+    need = sa.specattn_workspace_size(sel if mode == "fused" else None, att)
+    margin = 8 << 20
+    wbuf = torch.full((256 + need + margin,), 0x5A, dtype=torch.uint8, device="cuda")
+    att.workspace, att.workspace_bytes = wbuf.data_ptr() + 256, need
+    if mode == "list":
+        sa.specattn_topp_select(sel)
+        sa.specattn_sparse_decode_attn(att)
+    else:
+        sa.specattn_fused(sel, att)
+    torch.cuda.synchronize()
+    assert bool((wbuf[:256] == 0x5A).all().item()) and bool((wbuf[256 + need:] == 0x5A).all().item())
+    assert bool(torch.isfinite(out).all().item())
+    # a workspace one byte short is refused before anything is launched
+    att.workspace_bytes = need - 1
+    with pytest.raises(sa.SpecAttnError):
+        if mode == "list":
+            sa.specattn_sparse_decode_attn(att)
+        else:
+            sa.specattn_fused(sel, att)
+
+
+def test_layer_mapping_writes_only_its_outputs():
+    ad, av = W.layer_attention_maps(seed=56, m=7, n=11, rows=9, L=300)
+    sbuf, S = _guarded((7, 11), torch.float64, -77.0)
+    fbuf, f = _guarded((11,), torch.int32, -77)
+    tbuf, tot = _guarded((1,), torch.float64, -77.0)
+    lib = sa.load()
+    n1 = int(lib.specattn_layer_similarity_workspace_size(7, 11, 9, 300))
+    n2 = int(lib.specattn_layer_map_workspace_size(7, 11))
+    w1 = torch.full((n1 + 512,), 0x5A, dtype=torch.uint8, device="cuda")
+    w2 = torch.full((n2 + 512,), 0x5A, dtype=torch.uint8, device="cuda")
+    sa.specattn_layer_similarity(dev(ad), dev(av), S, workspace=w1[256:256 + n1])
+    sa.specattn_layer_map(S, f, tot, workspace=w2[256:256 + n2])
+    torch.cuda.synchronize()
+    for buf, fill in ((sbuf, -77.0), (fbuf, -77), (tbuf, -77.0)):
+        assert _margins_intact(buf, fill)
+    for wb, nn in ((w1, n1), (w2, n2)):
+        assert bool((wb[:256] == 0x5A).all().item()) and bool((wb[256 + nn:] == 0x5A).all().item())
+    f_ref, v_ref = oracle.layer_map(oracle.layer_similarity_fast(ad, av))
+    assert np.array_equal(f.cpu().numpy(), f_ref) and abs(tot.item() - v_ref) <= 1e-9 * abs(v_ref)
