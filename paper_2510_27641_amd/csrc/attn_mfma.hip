@@ -214,11 +214,16 @@ struct Plan {
 };
 
 #ifdef SPECATTN_TIMING
-#define STAMP(k) do { if (threadIdx.x == 0) plan.timing[blockIdx.x * 16 + (k)] = wall_clock64(); } while (0)
-#define STAMP_ONCE(k) do { if (threadIdx.x == 0 && !(stamped & (1u << (k)))) { stamped |= 1u << (k); plan.timing[blockIdx.x * 16 + (k)] = wall_clock64(); } } while (0)
+// Development builds: thread 0 keeps wall-clock stamps in LDS (a store to memory here would make the compiler
+// place waits on outstanding loads around it, and so change what is measured) and writes them out when it ends.
+#define STAMP_PUT(k) do { const long long t_ = wall_clock64(); if (FUSED) plan.timing[blockIdx.x * 16 + (k)] = t_; else asm volatile("ds_write_b64 %0, %1 offset:%2\n s_waitcnt lgkmcnt(0)" ::"v"(stamp_addr), "v"(t_), "n"(8 * (k)) : "memory"); } while (0)
+#define STAMP(k) do { if (threadIdx.x == 0) STAMP_PUT(k); } while (0)
+#define STAMP_ONCE(k) do { if (threadIdx.x == 0 && !(stamped & (1u << (k)))) { stamped |= 1u << (k); STAMP_PUT(k); } } while (0)
+#define STAMP_DUMP() do { if (!FUSED && threadIdx.x == 0) for (int k_ = 0; k_ < 16; ++k_) plan.timing[blockIdx.x * 16 + k_] = ((long long)stamp_lds[2 * k_ + 1] << 32) | (unsigned)stamp_lds[2 * k_]; } while (0)
 #else
 #define STAMP_ONCE(k) do { } while (0)
 #define STAMP(k) do { } while (0)
+#define STAMP_DUMP() do { } while (0)
 #endif
 
 // Cost of a row on the line the workgroups share out: its tiles, plus SEG_COST for picking the row up
@@ -395,6 +400,9 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
 
 #ifdef SPECATTN_TIMING
     unsigned stamped = 0;
+    int *stamp_lds = reinterpret_cast<int *>((reinterpret_cast<uintptr_t>(blk_pre) + 7) & ~(uintptr_t)7);   // the unfused kernels leave this array unused
+    const uint32_t stamp_addr = (uint32_t)(uintptr_t)LDS_PTR(int, stamp_lds);
+    if (!FUSED && tid == 0) for (int k = 0; k < 32; ++k) stamp_lds[k] = 0;
 #endif
     // Every kernel argument the main path uses is fetched here, in one batch: left to the compiler, the
     // argument loads are issued where each is first needed, and every such group is one more round trip to
@@ -434,19 +442,9 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
     STAMP(1);
     if (blockIdx.x == 0)
         for (int rr = tid; rr <= rows; rr += THREADS) plan.cost_prefix[rr] = pre[rr];
-    // This workgroup's share of the cost line
-    const int total = pre[rows];
-    const Share sh = make_share(total, plan.n_wg, blockIdx.x);
-    const int c0 = sh.c0, c1 = sh.c1;
-    if (c0 >= c1) return;
     const int G = attn_group_heads(a);
     const int QT = G * a.T;
     const float scale2 = a.sm_scale * 1.4426950408889634f;            // scores in log2 units
-
-    auto seg_range = [&](int r, int &lt_begin, int &lt_end) { sh.seg_range(pre, cnt_lds, r, lt_begin, lt_end); };
-    auto next_seg = [&](int r) { return sh.next_seg(pre, cnt_lds, rows, r); };
-    int r = sh.first_seg(pre, cnt_lds, rows);
-    if (r >= rows) return;
 
     // ---- per-segment inputs that are fetched ahead of time -------------------------------------------
     // The Q tile of a segment goes through LDS: thread t fetches 16-byte chunk t%16 of query row t/16
@@ -604,7 +602,18 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
         for (int j = last - first + tid; j < n; j += THREADS) ent_lds[j] = ent_lds[last - first - 1];
     };
 
+    // This workgroup's share of the cost line
+    const int total = pre[rows];
+    const Share sh = make_share(total, plan.n_wg, blockIdx.x);
+    const int c0 = sh.c0, c1 = sh.c1;
+    if (c0 >= c1) { STAMP_DUMP(); return; }
+    auto seg_range = [&](int r, int &lt_begin, int &lt_end) { sh.seg_range(pre, cnt_lds, r, lt_begin, lt_end); };
+    auto next_seg = [&](int r) { return sh.next_seg(pre, cnt_lds, rows, r); };
+    int r = sh.first_seg(pre, cnt_lds, rows);
+    if (r >= rows) { STAMP_DUMP(); return; }
+
     bool first_staged = false;               // fused: the first chunk's list is already in LDS
+    bool q_in_lds = false;                   // the first segment's Q is put into LDS before its gathers go out
     if (bc_all) {
 #pragma unroll
         for (int k = 0; k < EPT0; ++k) reinterpret_cast<int *>(ent_lds)[tid + k * THREADS] = bc_pf[k];
@@ -618,22 +627,38 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
         // Head start: wave w fetches the indices of tile w of the first chunk itself and requests that
         // tile's rows at once, instead of waiting until the whole chunk's list is staged in LDS.  These index
         // loads go out before everything else the segment needs, since the first gathers wait for them.
-        const bool ahead = !FUSED && wave < n0 / TILE;
+        const int n_ahead = (n0 / TILE) < NW ? (n0 / TILE) : NW;
+        const bool ahead = !FUSED && wave < n_ahead;
         const int b_first = r / a.H_kv, h_first = r - b_first * a.H_kv;
         const KvMap map_first = make_map<LAYOUT>(a, b_first, h_first);
         int jj_first[8], raw_first[8];
-        if (ahead) {
-            const int32_t *idx = a.indices + (int64_t)r * a.idx_stride;
-            const int count = cnt_lds[r];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                jj_first[i] = (lb + wave) * TILE + 4 * i + g;
-                jj_first[i] = jj_first[i] < count ? jj_first[i] : count - 1;
+        for (int i = 0; i < 8; ++i) jj_first[i] = raw_first[i] = 0;
+        // Everything the ordinary start requests is requested and taken in inside this one block, before any
+        // gather goes out: loads return in order, so a value left outstanding here - even one that only the
+        // compiler's bookkeeping believes outstanding on some path - could later only be waited for together with
+        // the gathers issued behind it, and such a wait holds the wave until its first tile has landed.
+        if (!FUSED) {
+            if (ahead) {
+                const int32_t *idx = a.indices + (int64_t)r * a.idx_stride;
+                const int count = cnt_lds[r];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    jj_first[i] = (lb + wave) * TILE + 4 * i + g;
+                    jj_first[i] = jj_first[i] < count ? jj_first[i] : count - 1;
+                }
+                attn_list_request_n(a, idx, jj_first, raw_first);
             }
-            attn_list_request_n(a, idx, jj_first, raw_first);
+            fetch_q(r);
+            fetch_entries(r, lb * TILE, n0, ent_pf);
+            asm volatile("" ::"v"(q_pf));
+#pragma unroll
+            for (int k = 0; k < EPT; ++k) asm volatile("" ::"v"(ent_pf[k]));
+#pragma unroll
+            for (int i = 0; i < 8; ++i) asm volatile("" ::"v"(raw_first[i]));
         }
-        fetch_q(r);
         if (FUSED) {
+            fetch_q(r);
             // The first chunk of the first segment is staged right here, ahead of the set-up code of the tile loop
             // (several hundred instructions that the unfused path runs while its first gathers are in flight).
             fused_prepare_row(r);
@@ -643,6 +668,8 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
             // Head start as on the unfused path: wave w requests tile w of the staged chunk at once.
             lds_barrier();                       // the padding entries behind the end of the list are in place
             asm volatile("" ::"v"(q_pf));        // Q has arrived long ago; taken in before the gathers (see below)
+            store_q();
+            q_in_lds = true;
             if (wave < n0 / TILE) {
                 uint32_t e[8];
                 lds_read_entries(e, ent_addr + (uint32_t)((wave * TILE + g) << 2));
@@ -658,13 +685,18 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
                                                      LDS_PTR(void, wave_lds + TILE_BYTES + i * 1024), 16, 0, KV_AUX);
             }
         }
-        if (!FUSED) fetch_entries(r, lb * TILE, n0, ent_pf);
-        // What has been requested so far is taken in before the gathers go out: loads return in order, so a value
-        // left outstanding here could later only be waited for together with the gathers issued behind it.
+        // Q goes into LDS right here.  Inside the segment loop the same store comes after a point where Q may
+        // have been requested again (for the next segment) with gathers behind it, and the wait placed there
+        // would, on the first pass, hold every wave until its head-start gathers had landed.
+        // The first chunk's list goes in with it, and the one barrier that makes both visible comes before the
+        // gathers: behind them every wave then runs on to its first tile without meeting the others again.
         if (!FUSED) {
-            asm volatile("" ::"v"(q_pf));
-#pragma unroll
-            for (int k = 0; k < EPT; ++k) asm volatile("" ::"v"(ent_pf[k]));
+            store_q();
+            q_in_lds = true;
+            store_entries(n0, ent_pf);
+            if (tid == 0) *tile_ctr = n_ahead;
+            first_staged = true;
+            lds_barrier();
         }
         STAMP_ONCE(13);
         if (ahead) {
@@ -697,6 +729,7 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
         const KvMap map = make_map<LAYOUT>(a, b, h);
         const char *kbh = static_cast<const char *>(a.k) + map.base * 2;
         const char *vbh = static_cast<const char *>(a.v) + map.base * 2;
+        STAMP_ONCE(15);
 
         f32x4 o[NQT][8];                     // O^T[dv = 16t + 4g + i][q = l16]
         float m_ref[NQT], l_sum[NQT];        // reference max (log2 units) and sum of weights
@@ -725,16 +758,21 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
                     fused_stage(r, ch_begin * TILE, (ch_end - ch_begin) * TILE);
                 }
                 first_staged = false;
-                if (ch_begin == lt_begin) store_q();
-            } else {
+                if (ch_begin == lt_begin && !q_in_lds) store_q();
+                q_in_lds = false;
+                if (tid == 0) *tile_ctr = head_start ? ((ch_end - ch_begin) < NW ? (ch_end - ch_begin) : NW) : 0;
+                lds_barrier();
+            } else if (!first_staged) {
                 if (ch_begin != lt_begin) fetch_entries(r, ch_begin * TILE, (ch_end - ch_begin) * TILE, ent_pf);
                 lds_barrier();                                       // previous users of ent_lds / q_lds are done
                 store_entries((ch_end - ch_begin) * TILE, ent_pf);
                 if (ch_begin == lt_begin) store_q();
+                if (tid == 0) *tile_ctr = 0;
+                lds_barrier();
+            } else {
+                first_staged = false;                                // staged, and made visible, before the loop
+                STAMP_ONCE(2);
             }
-            if (tid == 0) *tile_ctr = head_start ? ((ch_end - ch_begin) < NW ? (ch_end - ch_begin) : NW) : 0;
-            lds_barrier();
-            STAMP(2);
             STAMP_ONCE(9);
             if (ch_begin == lt_begin) {
 #pragma unroll
@@ -942,6 +980,7 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
         r = r_next;                              // the next segment starts with a barrier of its own
     }
     STAMP(7);
+    STAMP_DUMP();
 }
 
 // After the main kernel, one workgroup per (row, query row): rows shared by several workgroups get
