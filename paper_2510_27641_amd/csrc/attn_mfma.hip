@@ -63,9 +63,16 @@ constexpr int CHUNK_TILES = 64;       // tiles whose row offsets are staged in L
 constexpr int MAX_BLOCKS = SPECATTN_MAX_N / SEL_BLOCK;   // selection blocks per row, at most
 // dynamic LDS: wave buffers, cost prefix, counts, wave sums, tile counter, list entries, block prefix,
 // scan scratch, and the Q tile (two 16-row tiles at most) at the end
-constexpr int LDS_BYTES = NW * WAVE_LDS +
-                          (2 * MAX_ROWS + 1 + NW + 1 + CHUNK_TILES * TILE + MAX_BLOCKS + 1 + 2 * (NW + 1)) * 4 + 48 +
-                          2 * 16 * ROW_BYTES;
+constexpr int LDS_MAIN = NW * WAVE_LDS +
+                         (2 * MAX_ROWS + 1 + NW + 1 + CHUNK_TILES * TILE + MAX_BLOCKS + 1 + 2 * (NW + 1)) * 4 + 48 +
+                         2 * 16 * ROW_BYTES;
+#ifdef SPECATTN_TIMING
+constexpr int LDS_BYTES = LDS_MAIN + 256;             // development builds: room for the wall-clock stamps
+#else
+constexpr int LDS_BYTES = LDS_MAIN;
+#endif
+// the waves' (m, l) of two query tiles fit the block-prefix array and the scratch behind it
+static_assert(NW * 16 * 2 * 2 <= MAX_BLOCKS + 1 + 2 * (NW + 1), "no room for the wave merge's (m, l) table");
 #ifndef SPECATTN_KV_AUX
 #define SPECATTN_KV_AUX 2
 #endif
@@ -362,10 +369,9 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
     int *wsum = cnt_lds + MAX_ROWS;                                     // [NW]
     int *tile_ctr = wsum + NW;                                          // tiles of the current chunk claimed so far
     uint32_t *ent_lds = reinterpret_cast<uint32_t *>(tile_ctr + 1);       // [CHUNK_TILES * TILE] row offsets / 16 B
-    float *ml_lds = reinterpret_cast<float *>(ent_lds);                 // wave merge: [NW][2][32], same space
     int *blk_pre = reinterpret_cast<int *>(ent_lds + CHUNK_TILES * TILE);   // fused: [MAX_BLOCKS + 1] kept before block
-    int *scan_ws = blk_pre + MAX_BLOCKS + 1;                            // spare
-    char *q_lds = smem + LDS_BYTES - NQT * 16 * ROW_BYTES;              // Q tile [NQT*16][256 B], chunks swizzled like K
+    float *ml_lds = reinterpret_cast<float *>(blk_pre);                 // wave merge: [NW][16 query rows][2 * NQT], same space
+    char *q_lds = smem + LDS_MAIN - NQT * 16 * ROW_BYTES;              // Q tile [NQT*16][256 B], chunks swizzled like K
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l16 = lane & 15, g = lane >> 4;
@@ -400,7 +406,7 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
 
 #ifdef SPECATTN_TIMING
     unsigned stamped = 0;
-    int *stamp_lds = reinterpret_cast<int *>((reinterpret_cast<uintptr_t>(blk_pre) + 7) & ~(uintptr_t)7);   // the unfused kernels leave this array unused
+    int *stamp_lds = reinterpret_cast<int *>(smem + LDS_MAIN);
     const uint32_t stamp_addr = (uint32_t)(uintptr_t)LDS_PTR(int, stamp_lds);
     if (!FUSED && tid == 0) for (int k = 0; k < 32; ++k) stamp_lds[k] = 0;
 #endif
@@ -911,11 +917,11 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
         }
 
         // ---- combine the waves of this workgroup: every wave hands its state over lane by lane through its
-        //      own, now idle, tile buffers; wave w then reduces and writes the (query tile, dv tile) blocks
-        //      k = w * KPW .. of all eight states ---------------------------------------------------------
-        lds_barrier();                         // every wave is done with its buffers and with ent_lds
-        STAMP(4);
-        float *mlw = ml_lds;                     // [NW][64 lanes][2 * NQT]: m, l of every lane
+        //      own tile buffers, which are idle as soon as the wave itself has no tile left - before the barrier,
+        //      so that only the last wave's hand-over is waited for; wave w then reduces and writes the
+        //      (query tile, dv tile) blocks k = w * KPW .. of all eight states.  (m, l) per query row go into the
+        //      block-prefix array, which nobody reads while tiles are processed. -----------------------------
+        float *mlw = ml_lds;                     // [NW][16 query rows][2 * NQT]: m, l (summed over the lane groups)
         {
             float *dmp = reinterpret_cast<float *>(wave_lds);                  // [NQT * 8][64 lanes] float4
 #pragma unroll
@@ -923,11 +929,17 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
 #pragma unroll
                 for (int t = 0; t < 8; ++t)
                     *reinterpret_cast<f32x4 *>(dmp + ((qt * 8 + t) * 64 + lane) * 4) = o[qt][t];
-                mlw[(wave * 64 + lane) * 2 * NQT + 2 * qt] = m_ref[qt];
-                mlw[(wave * 64 + lane) * 2 * NQT + 2 * qt + 1] = l_sum[qt];
+                float l = l_sum[qt];
+                l += __shfl_xor(l, 16, 64);
+                l += __shfl_xor(l, 32, 64);
+                if (g == 0) {
+                    mlw[(wave * 16 + l16) * 2 * NQT + 2 * qt] = m_ref[qt];
+                    mlw[(wave * 16 + l16) * 2 * NQT + 2 * qt + 1] = l;
+                }
             }
         }
-        lds_barrier();
+        lds_barrier();                         // every wave has handed over, and is done with ent_lds and Q
+        STAMP(4);
         STAMP(5);
         // Workgroups w0..w1 share row r: a row owned by one workgroup is finished here; otherwise the
         // partial goes to slot w + r for the merge kernel.
@@ -943,19 +955,17 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
                 const int qt = k >> 3, t = k & 7;
                 float m = -INFINITY;
 #pragma unroll
-                for (int w = 0; w < NW; ++w) m = fmaxf(m, mlw[(w * 64 + lane) * 2 * NQT + 2 * qt]);
+                for (int w = 0; w < NW; ++w) m = fmaxf(m, mlw[(w * 16 + l16) * 2 * NQT + 2 * qt]);
                 f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
                 float l = 0.0f;
 #pragma unroll
                 for (int w = 0; w < NW; ++w) {
-                    const float mw = mlw[(w * 64 + lane) * 2 * NQT + 2 * qt];
+                    const float mw = mlw[(w * 16 + l16) * 2 * NQT + 2 * qt];
                     const float f = (mw == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(mw - m);
-                    l += f * mlw[(w * 64 + lane) * 2 * NQT + 2 * qt + 1];
+                    l += f * mlw[(w * 16 + l16) * 2 * NQT + 2 * qt + 1];
                     acc += f * *reinterpret_cast<const f32x4 *>(reinterpret_cast<const float *>(smem + w * WAVE_LDS) +
                                                                 (k * 64 + lane) * 4);
                 }
-                l += __shfl_xor(l, 16, 64);
-                l += __shfl_xor(l, 32, 64);
                 const int q = qt * 16 + l16;
                 if (q < QT) {
                     if (w0 == w1 && !a.k_new) {
