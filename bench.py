@@ -360,6 +360,46 @@ def main():
         for ab, _ in batched:
             sa.specattn_sparse_decode_attn(ab)
     ms_batched = timed(attn_batched, max(args.steps // 2, 3), 1)
+    # the same grouping on the fused path (lists rebuilt on chip from probs, tau* and the block counts)
+    ms_batched_f = None
+    if fused_ok and "fused" in results:
+        batched_f = []
+        for g0 in range(0, L, grp):
+            rows_b = slice(g0 * R, (g0 + grp) * R)
+            sb = sa.select_args(probs[g0 * B:(g0 + grp) * B], top_p, indices=None, counts=counts_f[rows_b],
+                                thresholds=tau_f[rows_b], block_counts=bc_f[rows_b], reuse_selection=True)
+            ab = sa.attn_args(q_all[g0 * B:(g0 + grp) * B], k_all[g0 * B:(g0 + grp) * B], v_all[g0 * B:(g0 + grp) * B], out=out_b)
+            wsb = sa.alloc_workspace(sa.specattn_workspace_size(sb, ab))
+            ab.workspace, ab.workspace_bytes = wsb.data_ptr(), wsb.numel()
+            batched_f.append((sb, ab, wsb))
+
+        def fused_batched():
+            for sb, ab, _ in batched_f:
+                sa.specattn_fused(sb, ab)
+        ms_batched_f = timed(fused_batched, max(args.steps // 2, 3), 1)
+
+    # whole steps in that grouping: the batched selection (or threshold pass) followed by the grouped calls
+    def step_batched():
+        sa.specattn_topp_select(sel_all)
+        attn_batched()
+    ms_step_b = timed(step_batched, max(args.steps // 2, 3), 1)
+    ms_step_bf = None
+    if ms_batched_f is not None:
+        def step_batched_f():
+            sa.specattn_topp_select(sel_all_f)
+            fused_batched()
+        ms_step_bf = timed(step_batched_f, max(args.steps // 2, 3), 1)
+    # the grouped calls compute the same thing: the last group's outputs against the per-layer calls' outputs
+    # (only the fp32 summation order differs, with the split of the rows over the workgroups)
+    attn_only()
+    attn_batched()
+    torch.cuda.synchronize()
+    grouped_diff = float((out_b.view(grp, B, H_q, T, d) - torch.stack(outs[L - grp:])).abs().max().item())
+    if ms_batched_f is not None:
+        step_fused()
+        fused_batched()
+        torch.cuda.synchronize()
+        grouped_diff = max(grouped_diff, float((out_b.view(grp, B, H_q, T, d) - torch.stack(outs_f[L - grp:])).abs().max().item()))
     # ceiling of this machine: a plain 16 B per lane read over distinct 4 GiB pieces of the K cache
     piece = max(1, (4 << 30) // (k_all[0].numel() * 2))
     pieces = [k_all[i * piece:(i + 1) * piece] for i in range(min(3, k_all.shape[0] // piece))]
@@ -400,8 +440,18 @@ def main():
                   for k, v in results.items() if k in ("unfused", "fused")},
         "kernels": {"select_all_layers_ms": round(ms_sel, 4), "attention_per_layer_ms": round(ms_attn, 5)},
         "batched_instances": {"what": f"attention of all {L} layers as {L // grp} calls of {grp} independent layer instances each "
-                                      "(not how a verifier runs its layers; shows the rate with launch phases amortised)",
-                              "ms": round(ms_batched, 4), "GBps": round(sel_bytes_step / (ms_batched * 1e-3) / 1e9, 1)},
+                                      "(the workload's layers are independent instances, so the figures hold for it; a verifier cannot run its "
+                                      "layers this way, each layer's Q/K/V depending on the layer before, which is why `value` "
+                                      "is the per-layer figure; shows the rate with the launch phases amortised)",
+                              "ms": round(ms_batched, 4), "GBps": round(sel_bytes_step / (ms_batched * 1e-3) / 1e9, 1),
+                              "fused_ms": None if ms_batched_f is None else round(ms_batched_f, 4),
+                              "fused_GBps": None if ms_batched_f is None else round(sel_bytes_step / (ms_batched_f * 1e-3) / 1e9, 1),
+                              "max_abs_diff_to_per_layer_calls": grouped_diff,
+                              "whole_step": {"what": "selection of all rows + the grouped attention calls",
+                                             "unfused_ms": round(ms_step_b, 4),
+                                             "unfused_GBps": round(sel_bytes_step / (ms_step_b * 1e-3) / 1e9, 1),
+                                             "fused_ms": None if ms_step_bf is None else round(ms_step_bf, 4),
+                                             "fused_GBps": None if ms_step_bf is None else round(sel_bytes_step / (ms_step_bf * 1e-3) / 1e9, 1)}},
         "roofline": {"bound": "hbm", "kernel": "specattn_sparse_decode_attn = attn_mfma_kernel + merge_partials_kernel, one layer",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
