@@ -618,8 +618,7 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
     int r = sh.first_seg(pre, cnt_lds, rows);
     if (r >= rows) { STAMP_DUMP(); return; }
 
-    bool first_staged = false;               // fused: the first chunk's list is already in LDS
-    bool q_in_lds = false;                   // the first segment's Q is put into LDS before its gathers go out
+    bool first_staged = false;               // the first chunk's list, Q and the tile counter are already in LDS
     if (bc_all) {
 #pragma unroll
         for (int k = 0; k < EPT0; ++k) reinterpret_cast<int *>(ent_lds)[tid + k * THREADS] = bc_pf[k];
@@ -672,11 +671,11 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
             fused_stage(r, lb * TILE, n0);
             first_staged = true;
             // Head start as on the unfused path: wave w requests tile w of the staged chunk at once.
-            lds_barrier();                       // the padding entries behind the end of the list are in place
             asm volatile("" ::"v"(q_pf));        // Q has arrived long ago; taken in before the gathers (see below)
             store_q();
-            q_in_lds = true;
-            if (wave < n0 / TILE) {
+            if (tid == 0) *tile_ctr = n_ahead;
+            lds_barrier();                       // the padding entries behind the end of the list, Q and the counter are in place
+            if (wave < n_ahead) {
                 uint32_t e[8];
                 lds_read_entries(e, ent_addr + (uint32_t)((wave * TILE + g) << 2));
                 const char *kb0 = static_cast<const char *>(a.k) + map_first.base * 2;
@@ -698,7 +697,6 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
         // gathers: behind them every wave then runs on to its first tile without meeting the others again.
         if (!FUSED) {
             store_q();
-            q_in_lds = true;
             store_entries(n0, ent_pf);
             if (tid == 0) *tile_ctr = n_ahead;
             first_staged = true;
@@ -758,15 +756,11 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
         for (int ch_begin = lt_begin; ch_begin < lt_end; ch_begin += CHUNK_TILES) {
             const int ch_end = (ch_begin + CHUNK_TILES) < lt_end ? (ch_begin + CHUNK_TILES) : lt_end;
             // ---- stage this chunk's row offsets in LDS (the first chunk's were fetched ahead) ----------
-            if (FUSED) {
-                if (!first_staged) {
-                    if (ch_begin == lt_begin) fused_prepare_row(r); else lds_barrier();
-                    fused_stage(r, ch_begin * TILE, (ch_end - ch_begin) * TILE);
-                }
-                first_staged = false;
-                if (ch_begin == lt_begin && !q_in_lds) store_q();
-                q_in_lds = false;
-                if (tid == 0) *tile_ctr = head_start ? ((ch_end - ch_begin) < NW ? (ch_end - ch_begin) : NW) : 0;
+            if (FUSED && !first_staged) {
+                if (ch_begin == lt_begin) fused_prepare_row(r); else lds_barrier();
+                fused_stage(r, ch_begin * TILE, (ch_end - ch_begin) * TILE);
+                if (ch_begin == lt_begin) store_q();
+                if (tid == 0) *tile_ctr = 0;
                 lds_barrier();
             } else if (!first_staged) {
                 if (ch_begin != lt_begin) fetch_entries(r, ch_begin * TILE, (ch_end - ch_begin) * TILE, ent_pf);
