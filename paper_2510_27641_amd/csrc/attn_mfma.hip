@@ -223,10 +223,10 @@ struct Plan {
 #ifdef SPECATTN_TIMING
 // Development builds: thread 0 keeps wall-clock stamps in LDS (a store to memory here would make the compiler
 // place waits on outstanding loads around it, and so change what is measured) and writes them out when it ends.
-#define STAMP_PUT(k) do { const long long t_ = wall_clock64(); if (FUSED) plan.timing[blockIdx.x * 16 + (k)] = t_; else asm volatile("ds_write_b64 %0, %1 offset:%2\n s_waitcnt lgkmcnt(0)" ::"v"(stamp_addr), "v"(t_), "n"(8 * (k)) : "memory"); } while (0)
+#define STAMP_PUT(k) do { const long long t_ = wall_clock64(); asm volatile("ds_write_b64 %0, %1 offset:%2\n s_waitcnt lgkmcnt(0)" ::"v"(stamp_addr), "v"(t_), "n"(8 * (k)) : "memory"); } while (0)
 #define STAMP(k) do { if (threadIdx.x == 0) STAMP_PUT(k); } while (0)
 #define STAMP_ONCE(k) do { if (threadIdx.x == 0 && !(stamped & (1u << (k)))) { stamped |= 1u << (k); STAMP_PUT(k); } } while (0)
-#define STAMP_DUMP() do { if (!FUSED && threadIdx.x == 0) for (int k_ = 0; k_ < 16; ++k_) plan.timing[blockIdx.x * 16 + k_] = ((long long)stamp_lds[2 * k_ + 1] << 32) | (unsigned)stamp_lds[2 * k_]; } while (0)
+#define STAMP_DUMP() do { if (threadIdx.x == 0) for (int k_ = 0; k_ < 16; ++k_) plan.timing[blockIdx.x * 16 + k_] = ((long long)stamp_lds[2 * k_ + 1] << 32) | (unsigned)stamp_lds[2 * k_]; } while (0)
 #else
 #define STAMP_ONCE(k) do { } while (0)
 #define STAMP(k) do { } while (0)
@@ -408,7 +408,7 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
     unsigned stamped = 0;
     int *stamp_lds = reinterpret_cast<int *>(smem + LDS_MAIN);
     const uint32_t stamp_addr = (uint32_t)(uintptr_t)LDS_PTR(int, stamp_lds);
-    if (!FUSED && tid == 0) for (int k = 0; k < 32; ++k) stamp_lds[k] = 0;
+    if (tid == 0) for (int k = 0; k < 32; ++k) stamp_lds[k] = 0;
 #endif
     // Every kernel argument the main path uses is fetched here, in one batch: left to the compiler, the
     // argument loads are issued where each is first needed, and every such group is one more round trip to
@@ -534,15 +534,25 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
         const uint32_t tau_bits = seg_tau;
         const int count = cnt_lds[rr];
         const int last = (first + n) < count ? (first + n) : count;      // ranks [first, last) exist
-        auto block_of = [&](int rank) {                                  // blk_pre[b] <= rank < blk_pre[b + 1]
-            int lo = 0, hi = a.blocks_per_row;
-            while (hi - lo > 1) {
-                const int mid = (lo + hi) >> 1;
-                if (blk_pre[mid] <= rank) lo = mid; else hi = mid;
-            }
-            return lo;
-        };
-        const int b0 = block_of(first), b1 = block_of(last - 1);
+        // blocks that hold ranks `first` and `last - 1`: blk_pre[b] <= rank < blk_pre[b + 1].  Up to 64 blocks per
+        // row every lane looks at one block (one LDS round trip instead of a chain of dependent ones).
+        int b0, b1;
+        if (a.blocks_per_row <= 64) {
+            const int lo = lane < a.blocks_per_row ? blk_pre[lane] : 0x7fffffff;
+            const int b0m = __popcll(__ballot(lo <= first)), b1m = __popcll(__ballot(lo <= last - 1));
+            b0 = (b0m > 0 ? b0m : 1) - 1;                                // blk_pre[0] = 0 <= any rank
+            b1 = (b1m > 0 ? b1m : 1) - 1;
+        } else {
+            auto block_of = [&](int rank) {
+                int lo = 0, hi = a.blocks_per_row;
+                while (hi - lo > 1) {
+                    const int mid = (lo + hi) >> 1;
+                    if (blk_pre[mid] <= rank) lo = mid; else hi = mid;
+                }
+                return lo;
+            };
+            b0 = block_of(first); b1 = block_of(last - 1);
+        }
         constexpr int QUARTER = SEL_BLOCK / 4;                           // positions one load instruction covers
         static_assert(QUARTER == 64 * 4, "a wave covers a quarter block with one 16-byte load per lane");
         const bool vec_ok = aligned && len >= 4;
