@@ -45,7 +45,7 @@ struct RowShared {
     unsigned wave_c[16];
     unsigned wave_tot[2][16];
     unsigned wt[256];            // kept entries per (item, wave), then their exclusive prefix
-    int32_t wbuf[16][256];       // per wave: one item's kept entries, staged for contiguous stores
+    int32_t wbuf[32][256];       // per wave: the kept entries of 32 / waves items, staged for contiguous stores
     double total_m;
     double m_above;
     unsigned c_above;
@@ -495,27 +495,40 @@ __global__ __launch_bounds__(THREADS, 4) void topp_select_kernel(SelectLaunch a)
         __syncthreads();
         if (out) {
             // Per item the wave's kept entries are consecutive in the list: gather them in LDS in
-            // list order, then store them with whole-wave contiguous writes.
-            int32_t *wb = sh.wbuf[wave];
+            // list order, then store them with whole-wave contiguous writes.  Several items go through
+            // buffers of their own at a time, so that the stores and reads of one item do not each wait
+            // for the round trip of the item before (a wave's LDS accesses are served in order).
+            constexpr int SLOTS = 32 / NW;
+            int32_t *wb = sh.wbuf[wave * SLOTS];
 #pragma unroll
-            for (int i = 0; i < NV4; ++i) {
-                if (i < n_items) {
-                    unsigned o = before[i];
-                    const int p = (i * THREADS + tid) * 4;
+            for (int i0 = 0; i0 < NV4; i0 += SLOTS) {
 #pragma unroll
-                    for (int c = 0; c < 4; ++c) {
-                        if (fl[i] & (1 << c)) {
-                            const int pos = p + c;
-                            int32_t val = pos;
-                            if (ptab) val = (ptab[pos >> a.page_shift] << a.page_shift) | (pos & ((1 << a.page_shift) - 1));
-                            wb[o++] = val;
+                for (int sl = 0; sl < SLOTS; ++sl) {
+                    const int i = i0 + sl;
+                    if (i < NV4 && i < n_items) {
+                        unsigned o = before[i];
+                        const int p = (i * THREADS + tid) * 4;
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) {
+                            if (fl[i] & (1 << c)) {
+                                const int pos = p + c;
+                                int32_t val = pos;
+                                if (ptab) val = (ptab[pos >> a.page_shift] << a.page_shift) | (pos & ((1 << a.page_shift) - 1));
+                                wb[sl * 256 + o++] = val;
+                            }
                         }
                     }
-                    const unsigned base = sh.wt[i * NW + wave];
-                    const unsigned next = (i * NW + wave + 1 < NE) ? sh.wt[i * NW + wave + 1] : kept;
-                    const unsigned cnt_w = next - base;            // wave-uniform, at most 256
-                    for (unsigned k = lane; k < cnt_w; k += 64)
-                        if (base + k < (unsigned)a.idx_capacity) out[base + k] = wb[k];
+                }
+#pragma unroll
+                for (int sl = 0; sl < SLOTS; ++sl) {
+                    const int i = i0 + sl;
+                    if (i < NV4 && i < n_items) {
+                        const unsigned base = sh.wt[i * NW + wave];
+                        const unsigned next = (i * NW + wave + 1 < NE) ? sh.wt[i * NW + wave + 1] : kept;
+                        const unsigned cnt_w = next - base;            // wave-uniform, at most 256
+                        for (unsigned k = lane; k < cnt_w; k += 64)
+                            if (base + k < (unsigned)a.idx_capacity) out[base + k] = wb[sl * 256 + k];
+                    }
                 }
             }
         }
