@@ -618,14 +618,47 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
         for (int j = last - first + tid; j < n; j += THREADS) ent_lds[j] = ent_lds[last - first - 1];
     };
 
-    // This workgroup's share of the cost line
-    const int total = pre[rows];
+    // This workgroup's share of the cost line, and the rows of which it holds tiles.  Up to 64 rows, lane i looks
+    // at row i: one LDS round trip, the share, every row's local tile range at once and a ballot, instead of a
+    // binary search and a row-by-row walk over the table, each step of which waits for an LDS read.
+    const bool few_rows = rows <= 64;                    // uniform
+    int row_lo = 0, row_cnt = 0, row_hi = 0;
+    if (few_rows) {
+        row_lo = lane < rows ? pre[lane] : 0;
+        row_hi = lane < rows ? pre[lane + 1] : 0;
+        row_cnt = lane < rows ? cnt_lds[lane] : 0;
+    }
+    const int total = few_rows ? __builtin_amdgcn_readlane(row_hi, rows - 1) : pre[rows];
     const Share sh = make_share(total, plan.n_wg, blockIdx.x);
     const int c0 = sh.c0, c1 = sh.c1;
     if (c0 >= c1) { STAMP_DUMP(); return; }
-    auto seg_range = [&](int r, int &lt_begin, int &lt_end) { sh.seg_range(pre, cnt_lds, r, lt_begin, lt_end); };
-    auto next_seg = [&](int r) { return sh.next_seg(pre, cnt_lds, rows, r); };
-    int r = sh.first_seg(pre, cnt_lds, rows);
+    int my_lb = 0, my_le = 0;                            // few rows: local tile range of row `lane`
+    unsigned long long seg_mask = 0;                     // few rows: the rows with tiles in this share
+    if (few_rows) {
+        const int tiles = (row_cnt + TILE - 1) / TILE;
+        const int lo = c0 - row_lo - SEG_COST, hi = c1 - row_lo - SEG_COST;
+        my_lb = lo < 0 ? 0 : (lo > tiles ? tiles : lo);
+        my_le = hi < 0 ? 0 : (hi > tiles ? tiles : hi);
+        seg_mask = __ballot(lane < rows && my_lb < my_le);
+    }
+    auto seg_range = [&](int r, int &lt_begin, int &lt_end) {
+        if (few_rows) {
+            const int ru = __builtin_amdgcn_readfirstlane(r);
+            lt_begin = __builtin_amdgcn_readlane(my_lb, ru);
+            lt_end = __builtin_amdgcn_readlane(my_le, ru);
+        } else {
+            sh.seg_range(pre, cnt_lds, r, lt_begin, lt_end);
+        }
+    };
+    // first row at or after r with work for this workgroup, or `rows`
+    auto next_seg = [&](int r) {
+        if (few_rows) {
+            const unsigned long long m = r < 64 ? (seg_mask >> r) << r : 0ull;
+            return m ? (int)__ffsll((long long)m) - 1 : rows;
+        }
+        return sh.next_seg(pre, cnt_lds, rows, r);
+    };
+    int r = few_rows ? next_seg(0) : sh.first_seg(pre, cnt_lds, rows);
     if (r >= rows) { STAMP_DUMP(); return; }
 
     bool first_staged = false;               // the first chunk's list, Q and the tile counter are already in LDS
