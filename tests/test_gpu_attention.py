@@ -167,3 +167,22 @@ def test_run_to_run_stability():
     for _ in range(2):
         b, _ = gpu_attention(q, k, v, dev(idx), dev(cnt))
         assert row_rel_err(b, a) <= 1e-5
+
+
+def test_few_rows_and_table_lookups_agree():
+    """Up to 64 rows a workgroup finds its rows with one ballot, beyond that by searching the cost prefix
+    table.  A ninth, empty sequence (rows without kept positions cost nothing, so the shares stay the same)
+    sends the same eight sequences down the other way: same outputs up to the summation order."""
+    w = W.llama8b_layer(seed=21, B=8, n=4096)
+    idx, cnt = _lists_from_mask(_oracle_selection_mask(w))
+    q, k, v = kv_tensors(w)
+    a, a_lse = gpu_attention(q, k, v, dev(idx), dev(cnt))
+    pad = lambda t: torch.cat([t, torch.zeros_like(t[:1])], dim=0)
+    idx9 = np.concatenate([idx, np.zeros((w.H_kv, idx.shape[1]), dtype=np.int32)])
+    cnt9 = np.concatenate([cnt, np.zeros(w.H_kv, dtype=np.int32)])
+    b, b_lse = gpu_attention(pad(q), pad(k), pad(v), dev(idx9), dev(cnt9))
+    assert row_rel_err(b[:8], a) <= 1e-5
+    assert np.abs(b_lse[:8] - a_lse).max() <= 1e-5
+    assert (b[8] == 0).all() and np.isneginf(b_lse[8]).all()
+    ref, _ = oracle_attention(w, _oracle_selection_mask(w))
+    assert row_rel_err(a, ref) <= TOL["bf16"]
