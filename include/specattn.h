@@ -49,6 +49,7 @@ typedef enum specattn_dtype { SPECATTN_F32 = 0, SPECATTN_BF16 = 1, SPECATTN_F16 
 #define SPECATTN_MAX_N (1 << 19)       /* longest row the selection handles */
 #define SPECATTN_SEL_BLOCK 1024        /* positions per entry of block_counts */
 #define SPECATTN_MAX_T 8               /* most verifier queries (gamma + 1) per head */
+#define SPECATTN_STATIC_SCRATCH_BYTES (16u << 20)   /* built-in scratch of specattn_sparse_decode_attn_static */
 
 /*
  * Selection (Section 3.4, Algorithm 2; objective: Appendix A, Eq. 8).
@@ -240,6 +241,20 @@ specattn_status specattn_layer_map(const double *S, int32_t m, int32_t n, int32_
 
 /* Attention alone, over an index list already in device memory. */
 specattn_status specattn_sparse_decode_attn(const specattn_attn_args *attn, void *stream);
+
+/*
+ * For callers that cannot allocate device memory or hand over a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same computation, arguments, checks and results as
+ * specattn_sparse_decode_attn, except that attn->workspace / attn->workspace_bytes are ignored: the split
+ * partials live in a buffer of SPECATTN_STATIC_SCRATCH_BYTES that is part of the library image (one copy per
+ * GPU, held until the process ends).  The call allocates and frees nothing.  A call whose
+ * specattn_workspace_size(NULL, attn) exceeds that size is refused with SPECATTN_EWORKSPACE before anything
+ * is launched.  The buffer belongs to the device that is current when the call is made; `stream` must be a
+ * stream of that device.  All calls on one GPU share the buffer: calls that overlap on one GPU (different
+ * streams, or different threads without stream ordering between them) race on it and give wrong results;
+ * calls ordered on one stream are safe, and nothing has to be cleared between them.
+ */
+specattn_status specattn_sparse_decode_attn_static(const specattn_attn_args *attn, void *stream);
 
 /*
  * Selection + attention without the index list going through HBM: the first

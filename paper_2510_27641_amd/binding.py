@@ -20,7 +20,7 @@ ROW_INVALID, ROW_NEAR_BOUNDARY, ROW_OVERFLOW = 1, 2, 4
 SEL_BLOCK = 1024
 F32, BF16, F16 = 0, 1, 2
 
-EXPORTS = ("specattn_topp_select", "specattn_topp_select_union", "specattn_union_workspace_size", "specattn_sparse_decode_attn", "specattn_fused",
+EXPORTS = ("specattn_topp_select", "specattn_topp_select_union", "specattn_union_workspace_size", "specattn_sparse_decode_attn", "specattn_sparse_decode_attn_static", "specattn_fused",
            "specattn_workspace_size", "specattn_layer_similarity", "specattn_layer_similarity_workspace_size",
            "specattn_layer_map", "specattn_layer_map_workspace_size", "specattn_check_lists", "specattn_stream_read", "specattn_last_error", "specattn_version")
 
@@ -97,6 +97,8 @@ def load() -> C.CDLL:
         lib.specattn_union_workspace_size.argtypes = [C.POINTER(UnionArgs)]
         lib.specattn_sparse_decode_attn.restype = C.c_int
         lib.specattn_sparse_decode_attn.argtypes = [C.POINTER(AttnArgs), C.c_void_p]
+        lib.specattn_sparse_decode_attn_static.restype = C.c_int
+        lib.specattn_sparse_decode_attn_static.argtypes = [C.POINTER(AttnArgs), C.c_void_p]
         lib.specattn_fused.restype = C.c_int
         lib.specattn_fused.argtypes = [C.POINTER(SelectArgs), C.POINTER(AttnArgs), C.c_void_p]
         lib.specattn_workspace_size.restype = C.c_size_t
@@ -294,6 +296,11 @@ def specattn_topp_select_union(args: UnionArgs, workspace: torch.Tensor, stream=
 
 def specattn_sparse_decode_attn(attn: AttnArgs, stream=None) -> None:
     _check(load().specattn_sparse_decode_attn(C.byref(attn), _stream(stream)))
+
+
+def specattn_sparse_decode_attn_static(attn: AttnArgs, stream=None) -> None:
+    """The same call on the library's built-in scratch buffer: allocates nothing, ignores attn.workspace."""
+    _check(load().specattn_sparse_decode_attn_static(C.byref(attn), _stream(stream)))
 
 
 def specattn_layer_similarity(attn_draft: torch.Tensor, attn_verifier: torch.Tensor, S: torch.Tensor,

@@ -5,6 +5,12 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <mutex>
+
+// Scratch memory of specattn_sparse_decode_attn_static: the split partials and the cost prefix of one
+// attention call.  Every GPU the library runs on holds its own copy of this array until the process ends.
+// In host code the name is only a handle for hipGetSymbolAddress; kernels get the address it returns.
+static __device__ __align__(256) unsigned char scratch[SPECATTN_STATIC_SCRATCH_BYTES];
 
 namespace specattn {
 
@@ -393,8 +399,55 @@ size_t specattn_workspace_size(const specattn_select_args *sel, const specattn_a
     return bytes;
 }
 
+// Device address of this GPU's copy of `scratch`, looked up once per device (any thread may call).
+static specattn_status static_scratch(void **out)
+{
+    constexpr int MAX_DEVICES = 64;
+    static std::mutex mu;
+    static void *ptr[MAX_DEVICES] = {nullptr};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) {
+        (void)hipGetLastError();
+        set_error("no current device, or its ordinal is beyond %d", MAX_DEVICES - 1);
+        return SPECATTN_EHIP;
+    }
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[dev]) {
+        void *p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) {
+            (void)hipGetLastError();
+            set_error("hipGetSymbolAddress(scratch) failed on device %d: %s", dev, hipGetErrorString(e));
+            return SPECATTN_EHIP;
+        }
+        ptr[dev] = p;
+    }
+    *out = ptr[dev];
+    return SPECATTN_OK;
+}
+
+specattn_status specattn_sparse_decode_attn_static(const specattn_attn_args *attn, void *stream)
+{
+    clear_error();
+    specattn_status st = check_attn(attn, false);
+    if (st != SPECATTN_OK) return st;
+    const size_t need = specattn_workspace_size(nullptr, attn);
+    if (need == 0 || need > (size_t)SPECATTN_STATIC_SCRATCH_BYTES) {
+        set_error("this call needs %zu bytes of scratch memory; the built-in buffer holds %zu", need,
+                  (size_t)SPECATTN_STATIC_SCRATCH_BYTES);
+        return SPECATTN_EWORKSPACE;
+    }
+    void *ws = nullptr;
+    st = static_scratch(&ws);
+    if (st != SPECATTN_OK) return st;
+    AttnLaunch l = make_attn(attn);
+    l.workspace = ws;
+    l.workspace_bytes = SPECATTN_STATIC_SCRATCH_BYTES;
+    return launch_attn(l, static_cast<hipStream_t>(stream));
+}
+
 const char *specattn_last_error(void) { return g_error; }
 
-int specattn_version(void) { return 1007; }
+int specattn_version(void) { return 1008; }
 
 }  // extern "C"
