@@ -279,13 +279,15 @@ def main():
     counts_f = torch.zeros((L * R,), dtype=torch.int32, device="cuda")
     tau_f = torch.empty((L * R,), dtype=torch.float32, device="cuda")
     bc_f = torch.empty((L * R, nblk), dtype=torch.int32, device="cuda")
+    km_f = torch.empty((L * R, nblk * (sa.SEL_BLOCK // 32)), dtype=torch.int32, device="cuda")
     outs_f = [torch.empty((B, H_q, T, d), dtype=torch.float32, device="cuda") for _ in range(L)]
-    sel_all_f = sa.select_args(probs, top_p, indices=None, counts=counts_f, thresholds=tau_f, block_counts=bc_f)
+    sel_all_f = sa.select_args(probs, top_p, indices=None, counts=counts_f, thresholds=tau_f, block_counts=bc_f,
+                               kept_mask=km_f)
     sel_layer, attn_f, ws_f = [], [], None
     for layer in range(L):
         rows = slice(layer * R, (layer + 1) * R)
         s = sa.select_args(probs[layer * B:(layer + 1) * B], top_p, indices=None, counts=counts_f[rows],
-                           thresholds=tau_f[rows], block_counts=bc_f[rows], reuse_selection=True)
+                           thresholds=tau_f[rows], block_counts=bc_f[rows], kept_mask=km_f[rows], reuse_selection=True)
         a = sa.attn_args(qs[layer], ks[layer], vs[layer], out=outs_f[layer])
         if ws_f is None:
             ws_f = sa.alloc_workspace(sa.specattn_workspace_size(s, a))
@@ -367,7 +369,8 @@ def main():
         for g0 in range(0, L, grp):
             rows_b = slice(g0 * R, (g0 + grp) * R)
             sb = sa.select_args(probs[g0 * B:(g0 + grp) * B], top_p, indices=None, counts=counts_f[rows_b],
-                                thresholds=tau_f[rows_b], block_counts=bc_f[rows_b], reuse_selection=True)
+                                thresholds=tau_f[rows_b], block_counts=bc_f[rows_b], kept_mask=km_f[rows_b],
+                                reuse_selection=True)
             ab = sa.attn_args(q_all[g0 * B:(g0 + grp) * B], k_all[g0 * B:(g0 + grp) * B], v_all[g0 * B:(g0 + grp) * B], out=out_b)
             wsb = sa.alloc_workspace(sa.specattn_workspace_size(sb, ab))
             ab.workspace, ab.workspace_bytes = wsb.data_ptr(), wsb.numel()

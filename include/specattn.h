@@ -84,9 +84,9 @@ typedef struct specattn_select_args {
 
     /* selection state without an index list (what specattn_fused works from) */
     int32_t *block_counts;       /* out, optional: [B*H_kv][ceil(n_max / SPECATTN_SEL_BLOCK)] kept positions per block */
-    int32_t reuse_selection;     /* specattn_fused only: 1 = thresholds, counts and block_counts already hold the
+    int32_t reuse_selection;     /* specattn_fused only: 1 = counts, block_counts and kept_mask already hold the
                                     result of an earlier specattn_topp_select / specattn_fused call on these rows
-                                    (e.g. one batched call for all layers); the threshold phase is skipped */
+                                    (e.g. one batched call for all layers); the selection phase is skipped */
 
     /* Chunk-granular selection (Section 4 evaluates with chunks of 16 tokens).  chunk_size 0 or 1: single
        positions.  A power of two >= 2: the row is first reduced to chunk masses - the sum of the chunk's
@@ -104,6 +104,14 @@ typedef struct specattn_select_args {
        that one of the k comparisons was decided by less than 1e-6 of the row sum.  Needs workspace; not
        available together with block_counts, chunk_size > 1 or specattn_fused (SPECATTN_EUNSUPPORTED). */
     int32_t bisect_iters;
+
+    /* out, optional: the kept set as a bit mask (Algorithm 1 hands the verifier a binary mask per layer):
+       [B*H_kv][ceil(n_max / SPECATTN_SEL_BLOCK) * SPECATTN_SEL_BLOCK / 32] words, bit i of word w of a row set
+       iff position 32 * w + i is kept; bits at and beyond the row's length are 0.  Together with counts and
+       block_counts this is the selection state specattn_fused works from (1 bit per position instead of the 32
+       of a list entry per kept position).  Not available with chunk_size > 1, bisect_iters or the split path
+       (a workspace handed to a plain selection of few long rows): SPECATTN_EUNSUPPORTED. */
+    uint32_t *kept_mask;
 } specattn_select_args;
 
 /*
@@ -166,6 +174,12 @@ typedef struct specattn_attn_args {
     /* optional: a second copy of the output in the dtype of q/k/v (round to nearest even), [B][H_q][T][d]
        contiguous, 16-byte aligned - what a following projection in that dtype reads.  NULL = not written. */
     void *out_lowp;
+
+    /* 0: the waves of a row's workgroups claim the row's tiles at run time (fastest; the fp32 summation order,
+       and with it the last bits of out and lse, can differ from run to run).  1: tiles are assigned statically,
+       every sum is taken in a fixed order and repeated calls on the same inputs give bit-identical outputs
+       (bf16 / fp16 with d = 128; the fp32 / d = 64 route is always deterministic). */
+    int32_t deterministic;
 } specattn_attn_args;
 
 /*
@@ -257,14 +271,16 @@ specattn_status specattn_sparse_decode_attn(const specattn_attn_args *attn, void
 specattn_status specattn_sparse_decode_attn_static(const specattn_attn_args *attn, void *stream);
 
 /*
- * Selection + attention without the index list going through HBM: the first
- * phase writes only tau*, counts and per-block counts (into sel->thresholds /
- * sel->block_counts when given, else into the workspace); the attention
- * workgroups re-derive their share of the list from `probs` on chip.
- * sel->indices is ignored; attn->indices / attn->counts are ignored
+ * Selection + attention without an index list (Algorithm 1: the masks of all layers are created from the draft
+ * model's attention before the verifier runs, and each verifier layer attends under its mask; Section 3.5: the
+ * paper's implementation converts that mask to an index structure before its attention kernel can use it - this
+ * call removes the conversion and the list's trip through memory).  The selection phase writes tau*, counts,
+ * per-block counts and the kept-position mask (1 bit per position; into sel->thresholds / sel->block_counts /
+ * sel->kept_mask when given, else into the workspace); the attention waves turn the mask words of a tile into
+ * its 32 row addresses on chip.  sel->indices is ignored; attn->indices / attn->counts are ignored
  * (sel->counts is written and used).  attn->workspace serves both phases.
- * Supported for bf16 and fp16, d = 128, contiguous or page-table layouts
- * (SPECATTN_EUNSUPPORTED otherwise).
+ * Supported for bf16 and fp16, d = 128, contiguous or page-table layouts; there is no list, so
+ * attn->indices_are_physical and chunk lists do not apply (SPECATTN_EUNSUPPORTED).
  */
 specattn_status specattn_fused(const specattn_select_args *sel, const specattn_attn_args *attn,
                                void *stream);
@@ -293,6 +309,15 @@ specattn_status specattn_check_lists(const specattn_attn_args *attn, int64_t poo
  * src and bytes must be multiples of 16: SPECATTN_EALIGN otherwise; NULL or 0: SPECATTN_EINVAL.
  */
 specattn_status specattn_stream_read(const void *src, size_t bytes, uint32_t *sink, void *stream);
+
+/*
+ * Optional set-up of the current device: sets the attributes the attention kernels need (their LDS size) and
+ * looks up the built-in scratch buffer.  Every attention entry point does the same on its first call on a
+ * device; a caller that wants to record its FIRST attention call on a device in a HIP graph calls this before
+ * the capture starts (setting kernel attributes is not a stream operation and is not captured).  Safe to call
+ * any number of times, from any thread.  SPECATTN_OK or SPECATTN_EHIP.
+ */
+specattn_status specattn_init(void);
 
 /* Text of the calling thread's last error ("" if none).  Never NULL. */
 const char *specattn_last_error(void);

@@ -22,7 +22,7 @@ F32, BF16, F16 = 0, 1, 2
 
 EXPORTS = ("specattn_topp_select", "specattn_topp_select_union", "specattn_union_workspace_size", "specattn_sparse_decode_attn", "specattn_sparse_decode_attn_static", "specattn_fused",
            "specattn_workspace_size", "specattn_layer_similarity", "specattn_layer_similarity_workspace_size",
-           "specattn_layer_map", "specattn_layer_map_workspace_size", "specattn_check_lists", "specattn_stream_read", "specattn_last_error", "specattn_version")
+           "specattn_layer_map", "specattn_layer_map_workspace_size", "specattn_check_lists", "specattn_stream_read", "specattn_init", "specattn_last_error", "specattn_version")
 
 
 class SelectArgs(C.Structure):
@@ -36,6 +36,7 @@ class SelectArgs(C.Structure):
         ("emit_physical", C.c_int32),
         ("block_counts", C.c_void_p), ("reuse_selection", C.c_int32),
         ("chunk_size", C.c_int32), ("bisect_iters", C.c_int32),
+        ("kept_mask", C.c_void_p),
     ]
 
 
@@ -56,6 +57,7 @@ class AttnArgs(C.Structure):
         ("k_new", C.c_void_p), ("v_new", C.c_void_p),
         ("chunk_size", C.c_int32),
         ("out_lowp", C.c_void_p),
+        ("deterministic", C.c_int32),
     ]
 
 
@@ -117,6 +119,8 @@ def load() -> C.CDLL:
         lib.specattn_check_lists.argtypes = [C.POINTER(AttnArgs), C.c_int64, C.c_void_p, C.c_void_p]
         lib.specattn_stream_read.restype = C.c_int
         lib.specattn_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+        lib.specattn_init.restype = C.c_int
+        lib.specattn_init.argtypes = []
         lib.specattn_last_error.restype = C.c_char_p
         lib.specattn_last_error.argtypes = []
         lib.specattn_version.restype = C.c_int
@@ -153,7 +157,7 @@ def select_args(probs: torch.Tensor, top_p: float, *, indices: Optional[torch.Te
                 page_table: Optional[torch.Tensor] = None, page_size: int = 0,
                 emit_physical: bool = False, block_counts: Optional[torch.Tensor] = None,
                 reuse_selection: bool = False, chunk_size: int = 0,
-                bisect_iters: int = 0) -> SelectArgs:
+                bisect_iters: int = 0, kept_mask: Optional[torch.Tensor] = None) -> SelectArgs:
     """probs [B,H_kv,n] fp32 (last dim contiguous); indices [B*H_kv, cap] int32."""
     assert probs.dtype == torch.float32 and probs.dim() == 3 and probs.stride(2) == 1
     B, H, n = probs.shape
@@ -181,6 +185,10 @@ def select_args(probs: torch.Tensor, top_p: float, *, indices: Optional[torch.Te
     a.reuse_selection = int(reuse_selection)
     a.chunk_size = chunk_size
     a.bisect_iters = bisect_iters
+    if kept_mask is not None:
+        assert kept_mask.dtype == torch.int32 and kept_mask.is_contiguous()
+        assert kept_mask.numel() == B * H * ((n + SEL_BLOCK - 1) // SEL_BLOCK) * (SEL_BLOCK // 32)
+        a.kept_mask = kept_mask.data_ptr()
     return a
 
 
@@ -221,7 +229,7 @@ def attn_args(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, *, out: torch.T
               page_table: Optional[torch.Tensor] = None, page_size: int = 0,
               indices_are_physical: bool = False, seq_lens: Optional[torch.Tensor] = None,
               k_new: Optional[torch.Tensor] = None, v_new: Optional[torch.Tensor] = None,
-              chunk_size: int = 0, out_lowp: Optional[torch.Tensor] = None) -> AttnArgs:
+              chunk_size: int = 0, out_lowp: Optional[torch.Tensor] = None, deterministic: bool = False) -> AttnArgs:
     """q [B,H_q,T,d]; contiguous k/v [B,H_kv,n,d]; paged k/v pool [pages,H_kv,page_size,d];
     k_new/v_new [B,H_kv,T,d] contiguous (the new tokens behind the cache), optional."""
     assert q.dim() == 4 and k.dim() == 4 and k.shape == v.shape and k.stride() == v.stride()
@@ -259,6 +267,7 @@ def attn_args(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, *, out: torch.T
     a.out = out.data_ptr()
     a.lse = None if lse is None else lse.data_ptr()
     a.chunk_size = chunk_size
+    a.deterministic = int(deterministic)
     if out_lowp is not None:
         assert out_lowp.dtype == q.dtype and out_lowp.is_contiguous() and tuple(out_lowp.shape) == (B, H_q, T, d)
         a.out_lowp = out_lowp.data_ptr()
@@ -328,6 +337,11 @@ def specattn_layer_map(S: torch.Tensor, f: torch.Tensor, total: torch.Tensor, wo
 
 def specattn_fused(sel: SelectArgs, attn: AttnArgs, stream=None) -> None:
     _check(load().specattn_fused(C.byref(sel), C.byref(attn), _stream(stream)))
+
+
+def specattn_init() -> None:
+    """One-time set-up of the current device (kernel attributes); needed only before capturing a first call."""
+    _check(load().specattn_init())
 
 
 def specattn_check_lists(attn: AttnArgs, n_bad: torch.Tensor, pool_slots: int = 0, stream=None) -> None:

@@ -58,7 +58,7 @@ specattn_status check_select(const specattn_select_args *s, bool fused)
 {
     if (!s) { set_error("select args are NULL"); return SPECATTN_EINVAL; }
     if (!s->probs || !s->counts) { set_error("probs and counts must not be NULL"); return SPECATTN_EINVAL; }
-    if (!fused && !s->indices && !s->block_counts) { set_error("indices and block_counts must not both be NULL"); return SPECATTN_EINVAL; }
+    if (!fused && !s->indices && !s->block_counts && !s->kept_mask) { set_error("indices, block_counts and kept_mask must not all be NULL"); return SPECATTN_EINVAL; }
     if (s->B <= 0 || s->H_kv <= 0 || s->n_max <= 0) { set_error("B, H_kv and n_max must be positive"); return SPECATTN_EINVAL; }
     if (!(s->top_p > 0.0f && s->top_p <= 1.0f)) { set_error("top_p must lie in (0, 1]"); return SPECATTN_EINVAL; }
     if (s->n_max > SPECATTN_MAX_N) { set_error("n_max %d exceeds %d", s->n_max, SPECATTN_MAX_N); return SPECATTN_ESHAPE; }
@@ -68,9 +68,9 @@ specattn_status check_select(const specattn_select_args *s, bool fused)
         if (s->idx_stride_row < s->idx_capacity) { set_error("idx_stride_row is smaller than idx_capacity"); return SPECATTN_ESHAPE; }
     }
     if (s->chunk_size < 0 || (s->chunk_size > 1 && (!is_pow2(s->chunk_size) || s->chunk_size > 1024))) { set_error("chunk_size must be 0, 1 or a power of two up to 1024"); return SPECATTN_ESHAPE; }
-    if (s->chunk_size > 1 && (fused || s->emit_physical || s->block_counts)) { set_error("chunk-granular selection is not available with the fused call, emit_physical or block_counts"); return SPECATTN_EUNSUPPORTED; }
+    if (s->chunk_size > 1 && (fused || s->emit_physical || s->block_counts || s->kept_mask)) { set_error("chunk-granular selection is not available with the fused call, emit_physical, block_counts or kept_mask"); return SPECATTN_EUNSUPPORTED; }
     if (s->bisect_iters < 0 || s->bisect_iters > 64) { set_error("bisect_iters must lie in 0..64"); return SPECATTN_ESHAPE; }
-    if (s->bisect_iters > 0 && (fused || s->block_counts || s->chunk_size > 1 || !s->indices)) { set_error("the bisection mode needs an index list and is not available with the fused call, block_counts or chunks"); return SPECATTN_EUNSUPPORTED; }
+    if (s->bisect_iters > 0 && (fused || s->block_counts || s->kept_mask || s->chunk_size > 1 || !s->indices)) { set_error("the bisection mode needs an index list and is not available with the fused call, block_counts or chunks"); return SPECATTN_EUNSUPPORTED; }
     if (s->probs_stride_h < s->n_max || s->probs_stride_b < s->n_max) { set_error("probs strides are smaller than n_max"); return SPECATTN_ESHAPE; }
     if (s->emit_physical) {
         if (!s->page_table) { set_error("emit_physical needs a page table"); return SPECATTN_EINVAL; }
@@ -92,7 +92,12 @@ specattn_status check_attn(const specattn_attn_args *a, bool fused)
     if (a->H_q % a->H_kv) { set_error("H_q is not a multiple of H_kv"); return SPECATTN_ESHAPE; }
     if (a->T > SPECATTN_MAX_T) { set_error("T exceeds %d", SPECATTN_MAX_T); return SPECATTN_ESHAPE; }
     if (a->d != 64 && a->d != 128) { set_error("d must be 64 or 128"); return SPECATTN_ESHAPE; }
-    if ((a->H_q / a->H_kv) * a->T > 64 && !(a->dtype != SPECATTN_F32 && a->d == 128)) { set_error("G*T exceeds 64 query rows per kv head (only bf16 / fp16 with d = 128 take more)"); return SPECATTN_ESHAPE; }
+    {
+        // more than 64 query rows per kv head only fit the matrix-core route (the portable kernel's tables hold 64)
+        AttnLaunch probe{};
+        probe.dtype = (int)a->dtype; probe.d = a->d; probe.T = a->T; probe.H_kv = a->H_kv;
+        if ((a->H_q / a->H_kv) * a->T > 64 && !attn_mfma_supported(probe)) { set_error("G*T exceeds 64 query rows per kv head (only bf16 / fp16 with d = 128 and H_kv <= %d take more)", ATTN_MFMA_MAX_ROWS); return SPECATTN_ESHAPE; }
+    }
     if (!fused && !dense && a->idx_capacity < 1) { set_error("idx_capacity must be at least 1"); return SPECATTN_ESHAPE; }
     if (!fused && !dense && a->idx_stride_row < a->idx_capacity) { set_error("idx_stride_row is smaller than idx_capacity"); return SPECATTN_ESHAPE; }
     const bool paged = a->page_table != nullptr || a->indices_are_physical;
@@ -148,6 +153,7 @@ SelectLaunch make_select(const specattn_select_args *s)
     l.blocks_per_row = (s->n_max + SEL_BLOCK - 1) / SEL_BLOCK;
     l.n_tokens = s->n_max;
     l.chunk_shift = 0;
+    l.kept_mask = s->kept_mask;
     return l;
 }
 
@@ -181,6 +187,7 @@ AttnLaunch make_attn(const specattn_attn_args *a)
     l.workspace = a->workspace;
     l.workspace_bytes = a->workspace_bytes;
     l.seq_lens = a->seq_lens;
+    l.deterministic = a->deterministic ? 1 : 0;
     return l;
 }
 
@@ -201,6 +208,7 @@ specattn_status specattn_topp_select(const specattn_select_args *sel, void *work
     const size_t need = specattn_workspace_size(sel, nullptr);
     // the plain selection works without a workspace; with one, few long rows are split over many workgroups
     const bool split = plain && need > 0 && workspace && aligned(workspace, 256) && workspace_bytes >= need;
+    if (split && sel->kept_mask) { set_error("kept_mask is not written by the split selection of few long rows: call without a workspace"); return SPECATTN_EUNSUPPORTED; }
     if (!plain) {
         st = check_workspace(workspace, workspace_bytes, need);
         if (st != SPECATTN_OK) return st;
@@ -322,8 +330,8 @@ specattn_status specattn_fused(const specattn_select_args *sel, const specattn_a
         set_error("selection and attention arguments describe different rows");
         return SPECATTN_ESHAPE;
     }
-    if (sel->reuse_selection && (!sel->thresholds || !sel->block_counts)) {
-        set_error("reuse_selection needs thresholds and block_counts");
+    if (sel->reuse_selection && (!sel->kept_mask || !sel->block_counts)) {
+        set_error("reuse_selection needs block_counts and kept_mask");
         return SPECATTN_EINVAL;
     }
     AttnLaunch al = make_attn(attn);
@@ -335,20 +343,20 @@ specattn_status specattn_fused(const specattn_select_args *sel, const specattn_a
     if (st != SPECATTN_OK) return st;
     const int rows = sel->B * sel->H_kv;
     const int blocks = (sel->n_max + SEL_BLOCK - 1) / SEL_BLOCK;
-    // workspace: [attention partials][tau: rows floats][block counts: rows * blocks ints]
+    // workspace: [attention partials][block counts: rows * blocks ints][kept mask: rows * blocks * 32 words]
     char *extra = static_cast<char *>(attn->workspace) +
                   attn_workspace_bytes(rows, attn->H_q / attn->H_kv, attn->T, attn->d, attn->n_max);
-    float *tau = sel->thresholds ? sel->thresholds : reinterpret_cast<float *>(extra);
-    extra += ((size_t)rows * sizeof(float) + 255) & ~(size_t)255;
     int32_t *bc = sel->block_counts ? sel->block_counts : reinterpret_cast<int32_t *>(extra);
+    extra += ((size_t)rows * blocks * sizeof(int32_t) + 255) & ~(size_t)255;
+    uint32_t *mask = sel->kept_mask ? sel->kept_mask : reinterpret_cast<uint32_t *>(extra);
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (!sel->reuse_selection) {
         SelectLaunch sl = make_select(sel);
         sl.indices = nullptr;
         sl.idx_capacity = 0;
-        sl.thresholds = tau;
         sl.block_counts = bc;
         sl.blocks_per_row = blocks;
+        sl.kept_mask = mask;
         st = launch_select(sl, s);
         if (st != SPECATTN_OK) return st;
     }
@@ -357,11 +365,8 @@ specattn_status specattn_fused(const specattn_select_args *sel, const specattn_a
     al.counts = sel->counts;
     al.idx_capacity = sel->n_max;
     al.idx_stride = 0;
-    al.probs = sel->probs;
-    al.probs_stride_b = sel->probs_stride_b;
-    al.probs_stride_h = sel->probs_stride_h;
     al.seq_lens = sel->seq_lens;
-    al.tau = tau;
+    al.kept_mask = mask;
     al.block_counts = bc;
     al.blocks_per_row = blocks;
     return launch_attn_mfma(al, s);
@@ -391,10 +396,10 @@ size_t specattn_workspace_size(const specattn_select_args *sel, const specattn_a
     const int cap = (sel || dense) ? attn->n_max : attn->idx_capacity * (attn->chunk_size > 1 ? attn->chunk_size : 1);
     if (cap <= 0) return 0;
     size_t bytes = attn_workspace_bytes(rows, attn->H_q / attn->H_kv, attn->T, attn->d, cap);
-    if (sel) {                                        // fused: room for tau and the block counts
+    if (sel) {                                        // fused: room for the block counts and the kept mask
         const size_t blocks = ((size_t)attn->n_max + SEL_BLOCK - 1) / SEL_BLOCK;
-        bytes += ((size_t)rows * sizeof(float) + 255) & ~(size_t)255;
         bytes += ((size_t)rows * blocks * sizeof(int32_t) + 255) & ~(size_t)255;
+        bytes += ((size_t)rows * blocks * (SEL_BLOCK / 32) * sizeof(uint32_t) + 255) & ~(size_t)255;
     }
     return bytes;
 }
@@ -446,8 +451,17 @@ specattn_status specattn_sparse_decode_attn_static(const specattn_attn_args *att
     return launch_attn(l, static_cast<hipStream_t>(stream));
 }
 
+specattn_status specattn_init(void)
+{
+    clear_error();
+    void *ws = nullptr;
+    const specattn_status st = static_scratch(&ws);
+    if (st != SPECATTN_OK) return st;
+    return attn_mfma_configure();
+}
+
 const char *specattn_last_error(void) { return g_error; }
 
-int specattn_version(void) { return 1008; }
+int specattn_version(void) { return 1009; }
 
 }  // extern "C"

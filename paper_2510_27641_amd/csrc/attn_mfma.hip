@@ -1,18 +1,30 @@
-// Sparse decode attention over a selected index list (Section 3.1.2, Eq. 2-3; Section 3.5),
-// bf16 or fp16, d = 128, up to 32 query rows per kv head and launch: the gfx950 matrix-core variant.
+// Sparse decode attention over a selected index list or kept-position mask (Section 3.1.2, Eq. 2-3;
+// Section 3.5), bf16 or fp16, d = 128, up to 32 query rows per kv head and launch: the gfx950
+// matrix-core variant.
 //
 // Work split ("stream-K" over kept positions): the kept positions of all rows, in 32-position
-// tiles, form one sequence; workgroup w takes an equal contiguous share of it, so the split is
-// balanced by the *kept* count whatever the per-row counts are.  A share that crosses row
-// boundaries yields one partial (m, l, o) per (row, workgroup); partial (r, w) lives in slot w + r.
-// merge_partials_kernel combines a row's partials.
+// tiles, form one line; the line is cut into equal shares, one per workgroup (one workgroup of eight waves
+// per CU), so the split is balanced by the *kept* count whatever the per-row counts are.  A fixed
+// permutation of the workgroup numbers puts the owners of consecutive shares on different XCDs.  A share
+// that crosses row boundaries yields one partial (m, l, o) per (row, workgroup); partial (r, w) lives in
+// slot w + r.  merge_partials_kernel combines a row's partials.  Inside a share the waves claim tiles from
+// an LDS counter as their data arrives (a wave that gets its data later simply takes fewer); a
+// deterministic mode hands tile k of a share to wave k mod 8 instead, which fixes the summation order bit
+// by bit.
+// Measured and dropped: tiles of a row claimed by all of its workgroups from a counter in memory (a
+// device-scope atomic takes about as long as a tile under load - 5 us - and claims made that far ahead leave
+// as much unbalanced work at the end as they remove), and the merge folded into this kernel (last arriver
+// per row: write-through stores, an atomic and device-scope loads in a row cost 14 us after the last tile,
+// against 8 us for the wrap-up plus the second launch).
 //
 // Data path per wave and tile: the 32 gathered K rows and the 32 V rows (256 B each) go from HBM
 // straight into LDS (global_load_lds: 16 lanes fetch one full row, four rows per instruction,
 // XOR-swizzled chunk order).  Each wave owns one K buffer and one V buffer; the next tile's K is
 // requested as soon as this tile's K fragments are in registers, the next V as soon as this tile's
-// V has been consumed, so 8-16 KiB per wave (64-128 KiB per CU) are always in flight.
-//   S^T = K Q^T    : mfma 16x16x32 bf16, A = K fragment (ds_read_b128), B = Q fragment (registers)
+// V has been consumed.  The list words of a tile (or the words of the kept mask) are fetched the same way,
+// by LDS-DMA into two small slots per wave, one iteration ahead of the gathers that need them: nothing a
+// tile needs is waited for when its turn comes, and no barrier separates the tiles of a share.
+//   S^T = K Q^T    : mfma 16x16x32 bf16, A = K fragment (ds_read_b128), B = Q fragment (Q tile in LDS)
 //   softmax        : running reference max per query row, rescaled only when exceeded by 2^8
 //   O^T += V^T P^T : A = V^T fragment (ds_read_b64_tr_b16), B = P split into bf16 hi + lo parts
 // The mfma output layout puts each query row in a fixed lane, so scores, weights and output
@@ -51,37 +63,38 @@ template <> struct Half<true> {
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T *)(p))
 #define GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
 
-constexpr int NW = 8;                 // waves per workgroup
+constexpr int NW = ATTN_MFMA_WAVES;   // waves per workgroup
 constexpr int THREADS = NW * 64;
+constexpr int WG_PER_CU = 8 / NW;     // eight waves per CU in all
 constexpr int TILE = 32;              // positions per tile
 constexpr int D = 128;
 constexpr int ROW_BYTES = D * 2;      // one K or V row
 constexpr int TILE_BYTES = TILE * ROW_BYTES;          // 8 KiB per tensor
 constexpr int WAVE_LDS = 2 * TILE_BYTES;              // K buffer, V buffer
-constexpr int MAX_ROWS = 1536;        // rows whose cost prefix fits the LDS table
-constexpr int CHUNK_TILES = 64;       // tiles whose row offsets are staged in LDS at a time
+constexpr int MAX_ROWS = ATTN_MFMA_MAX_ROWS;          // rows whose cost prefix fits the LDS table
 constexpr int MAX_BLOCKS = SPECATTN_MAX_N / SEL_BLOCK;   // selection blocks per row, at most
-// dynamic LDS: wave buffers, cost prefix, counts, wave sums, tile counter, list entries, block prefix,
-// scan scratch, and the Q tile (two 16-row tiles at most) at the end
-constexpr int LDS_MAIN = NW * WAVE_LDS +
-                         (2 * MAX_ROWS + 1 + NW + 1 + CHUNK_TILES * TILE + MAX_BLOCKS + 1 + 2 * (NW + 1)) * 4 + 48 +
-                         2 * 16 * ROW_BYTES;
-#ifdef SPECATTN_TIMING
-constexpr int LDS_BYTES = LDS_MAIN + 256;             // development builds: room for the wall-clock stamps
-#else
-constexpr int LDS_BYTES = LDS_MAIN;
-#endif
-// the waves' (m, l) of two query tiles fit the block-prefix array and the scratch behind it
-static_assert(NW * 16 * 2 * 2 <= MAX_BLOCKS + 1 + 2 * (NW + 1), "no room for the wave merge's (m, l) table");
-#ifndef SPECATTN_KV_AUX
-#define SPECATTN_KV_AUX 2
-#endif
-constexpr int KV_AUX = SPECATTN_KV_AUX;   // cache policy bits of the K/V gathers
-#ifndef SPECATTN_SEG_COST
-#define SPECATTN_SEG_COST 12
-#endif
-constexpr int SEG_COST = SPECATTN_SEG_COST;          // cost of starting a row segment, in tiles
+constexpr int STATIC_ROUNDS = 3;      // tiles per wave that need no claim at the start of a launch
+constexpr int SLOT_BYTES = 256;       // one wave-wide LDS-DMA of 4 bytes per lane
+constexpr int KV_AUX = 2;             // cache policy of the K/V gathers: non-temporal (each row is used once)
+constexpr int SEG_COST = 12;          // cost of picking a row up, in tiles
 constexpr float RESCALE_SLACK = 8.0f; // log2 units the running max may exceed the reference by
+
+// dynamic LDS, in bytes from the start
+constexpr int OFF_PRE = NW * WAVE_LDS;                          // int[MAX_ROWS + 1] cost prefix
+constexpr int OFF_CNT = OFF_PRE + (MAX_ROWS + 1) * 4;           // int[MAX_ROWS] kept counts, clamped
+constexpr int OFF_WSUM = OFF_CNT + MAX_ROWS * 4;                // int[NW]
+constexpr int OFF_MISC = OFF_WSUM + NW * 4;                     // int[4]: tile counter, last-arriver flag
+constexpr int OFF_BLK = OFF_MISC + 16;                          // int[MAX_BLOCKS + 1] kept before block (mask source)
+constexpr int OFF_SLOT = (OFF_BLK + (MAX_BLOCKS + 1) * 4 + 255) & ~255;   // [NW][2][SLOT_BYTES] list / mask words in flight;
+                                                                // a wave's (m, l) table of the wave merge uses its first slot
+constexpr int OFF_SCAT = OFF_SLOT + NW * 2 * SLOT_BYTES;        // uint[NW][2][32] positions of a tile (mask source)
+constexpr int OFF_MARK = OFF_SCAT + NW * 256;                   // uint[NW][32] which mask word owns a rank (mask source)
+constexpr int OFF_Q = OFF_MARK + NW * 128;                      // Q tile [2 * 16][256 B], chunks swizzled like K
+constexpr int OFF_BC = OFF_Q + 2 * 16 * ROW_BYTES;               // int[BC_ALL] block counts of all rows (mask source, small calls)
+constexpr int BC_ALL = 2048;
+constexpr int LDS_BYTES = OFF_BC + BC_ALL * 4;
+static_assert(16 * 2 * 2 * 4 <= SLOT_BYTES, "a wave's (m, l) table must fit its first slot");
+static_assert(LDS_BYTES * WG_PER_CU <= 160 * 1024, "the workgroups of a CU must fit its LDS");
 
 // 16-byte chunk c of row `row` is stored in slot c ^ swz(row): makes both the K fragment reads
 // (16 rows x one chunk) and the V transpose reads (8 rows x 32 B) spread over all banks.
@@ -89,22 +102,17 @@ __device__ __forceinline__ int swz(int row) { return ((row & 7) << 1) | ((row >>
 
 // Where the gathered rows live.  A list entry is a logical position (contiguous layout) or a pool
 // slot page * page_size + offset (paged layouts; logical positions are mapped through the page
-// table once, when the chunk's list is staged).
+// table when the tile's row offsets are formed).
 enum Layout { CONTIGUOUS = 0, PAGE_TABLE = 1, PHYSICAL = 2 };
+// Where a row's kept positions come from: an index list in memory (also chunk lists and dense calls, which
+// have no list at all), or the kept-position mask and per-block counts of the selection (fused call).
+enum Source { LIST = 0, MASK = 1 };
 
 struct KvMap {
     int64_t base, stride_n, stride_page;
     const int32_t *ptab;
     int page_shift;
-    // element offset of the row, relative to `base`
-    template <int LAYOUT> __device__ __forceinline__ int64_t rel(int idx) const
-    {
-        if (LAYOUT == CONTIGUOUS) return (int64_t)idx * stride_n;
-        const int mask = (1 << page_shift) - 1;
-        const int page = LAYOUT == PAGE_TABLE ? ptab[idx >> page_shift] : (idx >> page_shift);
-        return (int64_t)page * stride_page + (int64_t)(idx & mask) * stride_n;
-    }
-    // the same for N positions, with the page-table loads (if any) in flight together
+    // row offsets (16-byte units, relative to `base`) of N positions, the page-table loads (if any) in flight together
     template <int LAYOUT, int N> __device__ __forceinline__ void rel_n(const int (&idx)[N], uint32_t (&off16)[N]) const
     {
         if (LAYOUT == CONTIGUOUS) {
@@ -184,7 +192,7 @@ __device__ __forceinline__ void lds_read_v(VFrags &v, uint32_t a0, uint32_t a1, 
         : "v"(a0), "v"(a1), "v"(a2), "v"(a3)
         : "memory");
 }
-// Row offsets of the 8 rows a lane helps to fetch: entries addr, addr + 16 B, ...
+// The 8 words a lane needs of a tile's 32: words addr/4, addr/4 + 4, ...
 __device__ __forceinline__ void lds_read_entries(uint32_t (&e)[8], uint32_t addr)
 {
     asm volatile(
@@ -195,6 +203,45 @@ __device__ __forceinline__ void lds_read_entries(uint32_t (&e)[8], uint32_t addr
         : "=&v"(e[0]), "=&v"(e[1]), "=&v"(e[2]), "=&v"(e[3]), "=&v"(e[4]), "=&v"(e[5]), "=&v"(e[6]), "=&v"(e[7])
         : "v"(addr)
         : "memory");
+}
+__device__ __forceinline__ uint32_t lds_read_word(uint32_t addr)
+{
+    uint32_t v;
+    asm volatile("ds_read_b32 %0, %1\n s_waitcnt lgkmcnt(0)" : "=&v"(v) : "v"(addr) : "memory");
+    return v;
+}
+__device__ __forceinline__ void lds_write_word(uint32_t addr, uint32_t v)
+{
+    asm volatile("ds_write_b32 %0, %1" ::"v"(addr), "v"(v) : "memory");
+}
+__device__ __forceinline__ void lds_wait() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+// value of `v` in lane `src_lane` (a cross-lane read through the LDS crossbar; no memory is touched)
+__device__ __forceinline__ uint32_t lane_read(uint32_t v, int src_lane)
+{
+    uint32_t r;
+    asm volatile("ds_bpermute_b32 %0, %1, %2\n s_waitcnt lgkmcnt(0)" : "=&v"(r) : "v"(src_lane << 2), "v"(v) : "memory");
+    return r;
+}
+// Inclusive prefix maximum over lanes 0..31 (the two lower rows of 16 lanes) on the vector ALU.
+__device__ __forceinline__ int prefix_max32(int v)
+{
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false));    // row_shr:1
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false));    // row_shr:2
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false));    // row_shr:4
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false));    // row_shr:8
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false));    // row_bcast:15 into rows 1 and 3
+    return v;
+}
+// Index of the k-th set bit of x (k = 0 is the lowest; k must be below the number of set bits).
+__device__ __forceinline__ int kth_set_bit(uint32_t x, int k)
+{
+    int r = 0, c;
+    c = __popc(x & 0xffffu); if (k >= c) { k -= c; r = 16; x >>= 16; }
+    c = __popc(x & 0xffu);   if (k >= c) { k -= c; r += 8; x >>= 8; }
+    c = __popc(x & 0xfu);    if (k >= c) { k -= c; r += 4; x >>= 4; }
+    c = __popc(x & 0x3u);    if (k >= c) { k -= c; r += 2; x >>= 2; }
+    c = (int)(x & 1u);       if (k >= c) { r += 1; }
+    return r;
 }
 // Wave-wide fetch-and-add on an LDS counter: lane 0 adds 1, the others add 0, so lane 0 reads the
 // value before the wave's own increment; that value is returned to the whole wave.
@@ -210,31 +257,29 @@ __device__ __forceinline__ int lds_claim(uint32_t addr, int lane)
 // outstanding global loads (a plain __syncthreads() also waits for every gather and prefetch still in flight).
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n s_barrier" ::: "memory"); }
 
+// Waits on the vector-memory counter with a run-time count (the instruction takes an immediate).
+__device__ __forceinline__ void vm_wait(int n)
+{
+    switch (n) {
+    case 0: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
+    case 8: asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); break;
+    case 9: asm volatile("s_waitcnt vmcnt(9)" ::: "memory"); break;
+    case 10: asm volatile("s_waitcnt vmcnt(10)" ::: "memory"); break;
+    case 17: asm volatile("s_waitcnt vmcnt(17)" ::: "memory"); break;
+    default: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
+    }
+}
+
 struct Plan {
     float *part_ml;           // [slots][QTP][2]
     float *part_o;            // [slots][QTP][D]
-    int32_t *cost_prefix;     // [rows + 1] in the workspace (written by workgroup 0, read by the merge)
+    int32_t *cost_prefix;     // [rows + 1] in the workspace (written by workgroup 0, read by the merge kernel)
     int n_wg;
-#ifdef SPECATTN_TIMING
-    long long *timing;        // [n_wg][8] wall-clock stamps (development builds only)
-#endif
+    int deterministic;        // static tile assignment
 };
 
-#ifdef SPECATTN_TIMING
-// Development builds: thread 0 keeps wall-clock stamps in LDS (a store to memory here would make the compiler
-// place waits on outstanding loads around it, and so change what is measured) and writes them out when it ends.
-#define STAMP_PUT(k) do { const long long t_ = wall_clock64(); asm volatile("ds_write_b64 %0, %1 offset:%2\n s_waitcnt lgkmcnt(0)" ::"v"(stamp_addr), "v"(t_), "n"(8 * (k)) : "memory"); } while (0)
-#define STAMP(k) do { if (threadIdx.x == 0) STAMP_PUT(k); } while (0)
-#define STAMP_ONCE(k) do { if (threadIdx.x == 0 && !(stamped & (1u << (k)))) { stamped |= 1u << (k); STAMP_PUT(k); } } while (0)
-#define STAMP_DUMP() do { if (threadIdx.x == 0) for (int k_ = 0; k_ < 16; ++k_) plan.timing[blockIdx.x * 16 + k_] = ((long long)stamp_lds[2 * k_ + 1] << 32) | (unsigned)stamp_lds[2 * k_]; } while (0)
-#else
-#define STAMP_ONCE(k) do { } while (0)
-#define STAMP(k) do { } while (0)
-#define STAMP_DUMP() do { } while (0)
-#endif
-
 // Cost of a row on the line the workgroups share out: its tiles, plus SEG_COST for picking the row up
-// (fresh Q, pipeline refill, partial write) so that workgroups crossing a row boundary get fewer tiles.
+// (fresh Q, partial write), so that workgroups holding many short rows get fewer tiles.
 __device__ __forceinline__ int row_cost(int count) { return count > 0 ? (count + TILE - 1) / TILE + SEG_COST : 0; }
 
 // Exclusive prefix of the row costs into pre[0..rows], every workgroup for itself.
@@ -254,30 +299,16 @@ __device__ __forceinline__ void cost_prefix(const AttnLaunch &a, int rows, int *
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         return;
     }
-    const int per = (rows + THREADS - 1) / THREADS;
-    const int r0 = tid * per;
-    int local = 0;
-    for (int k = 0; k < per; ++k) {
-        const int r = r0 + k;
-        if (r < rows) {
-            const int c = attn_row_count(a, r);
-            cnt[r] = c;
-            local += row_cost(c);
-        }
-    }
-    const int inc = wave_inclusive_sum(local);
+    static_assert(MAX_ROWS <= THREADS, "one row per thread");
+    const int c = tid < rows ? attn_row_count(a, tid) : 0;
+    const int cost = row_cost(c);
+    const int inc = wave_inclusive_sum(cost);
+    if (tid < rows) cnt[tid] = c;
     if (lane == 63) wsum[wave] = inc;
     lds_barrier();
     int base = 0;
     for (int w = 0; w < wave; ++w) base += wsum[w];
-    int run = base + inc - local;
-    for (int k = 0; k < per; ++k) {
-        const int r = r0 + k;
-        if (r < rows) {
-            pre[r] = run;
-            run += row_cost(cnt[r]);
-        }
-    }
+    if (tid < rows) pre[tid] = base + inc - cost;
     if (tid == THREADS - 1) pre[rows] = base + inc;
     lds_barrier();
 }
@@ -326,12 +357,16 @@ __device__ __forceinline__ int floor_div(int64_t a, int b)
 // The first min(n_wg, total) workgroups share the line: workgroup w takes [w * total / n, (w + 1) * total / n),
 // so shares differ by at most one unit and none of them is empty (every workgroup between the first and the
 // last of a row therefore holds tiles of that row, which the merge relies on).
-__device__ __forceinline__ Share make_share(int total, int n_wg, int w)
+__device__ __forceinline__ int share_start(int total, int n_wg, int w)
 {
     const int n = n_wg < total ? n_wg : total;
+    return w < n ? floor_div((int64_t)w * total, n) : total;
+}
+__device__ __forceinline__ Share make_share(int total, int n_wg, int w)
+{
     Share s;
-    s.c0 = w < n ? floor_div((int64_t)w * total, n) : total;
-    s.c1 = w < n ? floor_div((int64_t)(w + 1) * total, n) : total;
+    s.c0 = share_start(total, n_wg, w);
+    s.c1 = share_start(total, n_wg, w + 1);
     return s;
 }
 // the workgroup whose share holds cost position c (0 <= c < total)
@@ -339,6 +374,19 @@ __device__ __forceinline__ int share_of(int total, int n_wg, int c)
 {
     const int n = n_wg < total ? n_wg : total;
     return floor_div(((int64_t)c + 1) * n - 1, total);
+}
+
+// Which share of the line a workgroup takes.  The hardware deals workgroup i to XCD i mod 8; the owners of
+// four consecutive shares (the usual team of a row) are four workgroups on four different XCDs, and the sets
+// {x, x+1, x+3, x+6} rotate from team to team, so that every XCD serves half of the teams and a difference in
+// speed between XCDs is spread over all rows.  (A bijection of 0 .. n_wg - 1 when n_wg is a multiple of 32.)
+__device__ __forceinline__ int share_index(int wg, int n_wg)
+{
+    if (n_wg & 31) return wg;
+    const int x = wg & 7, c = wg >> 3, m = c & 3;
+    const int off = m == 0 ? 0 : (m == 1 ? 1 : (m == 2 ? 3 : 6));
+    const int team = ((c >> 2) << 3) | ((x - off) & 7);
+    return (team << 2) | m;
 }
 
 // One step of merging partial (m, l, o) triples that share the log2-unit convention.
@@ -354,32 +402,34 @@ struct Merge {
         m = mn;
     }
 };
-
-template <int NQT, int LAYOUT, bool FUSED, bool F16>
-__global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan plan)
+template <int NQT, int LAYOUT, int SRC, bool F16>
+__global__ __launch_bounds__(THREADS, WG_PER_CU) void attn_mfma_kernel(AttnLaunch a, Plan plan)
 {
     typedef typename Half<F16>::x8 h16x8;
     typedef typename Half<F16>::x2 h16x2;
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     constexpr int QTP = NQT * 16;
-    constexpr int EPT = CHUNK_TILES * TILE / THREADS;                   // list entries staged per thread
+    constexpr int QROUNDS = (NQT * 16 * 16 + THREADS - 1) / THREADS;    // 16-byte chunks of the Q tile per thread
     const int rows = a.B * a.H_kv;
-    int *pre = reinterpret_cast<int *>(smem + NW * WAVE_LDS);          // [MAX_ROWS + 1] cost prefix
-    int *cnt_lds = pre + MAX_ROWS + 1;                                  // [MAX_ROWS] kept counts, clamped
-    int *wsum = cnt_lds + MAX_ROWS;                                     // [NW]
-    int *tile_ctr = wsum + NW;                                          // tiles of the current chunk claimed so far
-    uint32_t *ent_lds = reinterpret_cast<uint32_t *>(tile_ctr + 1);       // [CHUNK_TILES * TILE] row offsets / 16 B
-    int *blk_pre = reinterpret_cast<int *>(ent_lds + CHUNK_TILES * TILE);   // fused: [MAX_BLOCKS + 1] kept before block
-    float *ml_lds = reinterpret_cast<float *>(blk_pre);                 // wave merge: [NW][16 query rows][2 * NQT], same space
-    char *q_lds = smem + LDS_MAIN - NQT * 16 * ROW_BYTES;              // Q tile [NQT*16][256 B], chunks swizzled like K
+    int *pre = reinterpret_cast<int *>(smem + OFF_PRE);
+    int *cnt_lds = reinterpret_cast<int *>(smem + OFF_CNT);
+    int *wsum = reinterpret_cast<int *>(smem + OFF_WSUM);
+    int *misc = reinterpret_cast<int *>(smem + OFF_MISC);               // [0] tile counter, [1] last-arriver flag
+    int *blk_pre = reinterpret_cast<int *>(smem + OFF_BLK);
+    char *q_lds = smem + OFF_Q;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l16 = lane & 15, g = lane >> 4;
     char *wave_lds = smem + wave * WAVE_LDS;
+    char *slot_lds = smem + OFF_SLOT + wave * 2 * SLOT_BYTES;
+    float *mlw = reinterpret_cast<float *>(smem + OFF_SLOT);            // wave w's (m, l): [w * 128 + q * 2 * NQT + ...]
     const uint32_t ks_addr = (uint32_t)(uintptr_t)LDS_PTR(char, wave_lds);
     const uint32_t vs_addr = ks_addr + TILE_BYTES;
-    const uint32_t ent_addr = (uint32_t)(uintptr_t)LDS_PTR(uint32_t, ent_lds);
-    const uint32_t ctr_addr = (uint32_t)(uintptr_t)LDS_PTR(int, tile_ctr);
+    const uint32_t slot_addr = (uint32_t)(uintptr_t)LDS_PTR(char, slot_lds);
+    const uint32_t scat_addr = (uint32_t)(uintptr_t)LDS_PTR(char, smem + OFF_SCAT + wave * 256);
+    const uint32_t mark_addr = (uint32_t)(uintptr_t)LDS_PTR(char, smem + OFF_MARK + wave * 128);
+    const uint32_t blk_addr = (uint32_t)(uintptr_t)LDS_PTR(int, blk_pre);
+    const uint32_t ctr_addr = (uint32_t)(uintptr_t)LDS_PTR(int, misc);
     const uint32_t q_addr = (uint32_t)(uintptr_t)LDS_PTR(char, q_lds);
     // K fragment of k-step c: row l16 (+16 per position tile), 16-byte chunk 4c + g
     uint32_t k_off[4];
@@ -404,12 +454,6 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
 #pragma unroll
     for (int j = 0; j < 4; ++j) lane_chunk[j] = (int64_t)((l16 ^ swz(4 * j + g)) << 4);
 
-#ifdef SPECATTN_TIMING
-    unsigned stamped = 0;
-    int *stamp_lds = reinterpret_cast<int *>(smem + LDS_MAIN);
-    const uint32_t stamp_addr = (uint32_t)(uintptr_t)LDS_PTR(int, stamp_lds);
-    if (tid == 0) for (int k = 0; k < 32; ++k) stamp_lds[k] = 0;
-#endif
     // Every kernel argument the main path uses is fetched here, in one batch: left to the compiler, the
     // argument loads are issued where each is first needed, and every such group is one more round trip to
     // memory on the way to the first gather.
@@ -419,203 +463,63 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
     SPECATTN_PRELOAD(a.sm_scale);
     SPECATTN_PRELOAD(a.q_stride_b); SPECATTN_PRELOAD(a.q_stride_h); SPECATTN_PRELOAD(a.q_stride_t);
     SPECATTN_PRELOAD(a.kv_stride_b); SPECATTN_PRELOAD(a.kv_stride_h); SPECATTN_PRELOAD(a.kv_stride_n);
-    SPECATTN_PRELOAD(a.indices); SPECATTN_PRELOAD(a.idx_stride); SPECATTN_PRELOAD(a.counts);
-    SPECATTN_PRELOAD(a.idx_capacity); SPECATTN_PRELOAD(a.dense); SPECATTN_PRELOAD(a.chunk_shift);
+    SPECATTN_PRELOAD(a.counts); SPECATTN_PRELOAD(a.idx_capacity); SPECATTN_PRELOAD(a.dense); SPECATTN_PRELOAD(a.chunk_shift);
     SPECATTN_PRELOAD(a.g_first); SPECATTN_PRELOAD(a.g_count); SPECATTN_PRELOAD(a.k_new);
     SPECATTN_PRELOAD(a.out); SPECATTN_PRELOAD(a.out_lowp); SPECATTN_PRELOAD(a.lse);
     SPECATTN_PRELOAD(plan.part_ml); SPECATTN_PRELOAD(plan.part_o); SPECATTN_PRELOAD(plan.cost_prefix);
-    SPECATTN_PRELOAD(plan.n_wg);
+    SPECATTN_PRELOAD(plan.n_wg); SPECATTN_PRELOAD(plan.deterministic);
     if (LAYOUT != CONTIGUOUS) { SPECATTN_PRELOAD(a.page_table); SPECATTN_PRELOAD(a.page_shift); SPECATTN_PRELOAD(a.max_pages); SPECATTN_PRELOAD(a.kv_stride_page); }
-    if (FUSED) { SPECATTN_PRELOAD(a.probs); SPECATTN_PRELOAD(a.probs_stride_b); SPECATTN_PRELOAD(a.probs_stride_h); SPECATTN_PRELOAD(a.seq_lens); SPECATTN_PRELOAD(a.tau); SPECATTN_PRELOAD(a.block_counts); SPECATTN_PRELOAD(a.blocks_per_row); SPECATTN_PRELOAD(a.n_max); }
+    if (SRC == LIST) { SPECATTN_PRELOAD(a.indices); SPECATTN_PRELOAD(a.idx_stride); }
+    if (SRC == MASK) { SPECATTN_PRELOAD(a.kept_mask); SPECATTN_PRELOAD(a.block_counts); SPECATTN_PRELOAD(a.blocks_per_row); SPECATTN_PRELOAD(a.n_max); }
 #undef SPECATTN_PRELOAD
-    STAMP(0);
-    // Fused path, small calls: the per-block kept counts and thresholds of all rows are requested together with
-    // the counts (the row this workgroup starts in is not known yet), so that its first segment need not wait
-    // for them again.  The block counts pass through the list buffer, which is free until the first chunk.
-    constexpr int EPT0 = CHUNK_TILES * TILE / THREADS;
-    const bool bc_all = FUSED && rows <= 64 && rows * a.blocks_per_row <= CHUNK_TILES * TILE;
-    int bc_pf[EPT0];
-    uint32_t tau_pf = 0;
+    // Mask source, small calls: the per-block kept counts of all rows are requested together with the counts (the row
+    // this workgroup starts in is not known yet), so that its first segment need not go to memory for them again.
+    constexpr int BC_PT = BC_ALL / THREADS;
+    int *bc_lds = reinterpret_cast<int *>(smem + OFF_BC);
+    const bool bc_all = SRC == MASK && rows * a.blocks_per_row <= BC_ALL;
+    int bc_pf[BC_PT];
     if (bc_all) {
 #pragma unroll
-        for (int k = 0; k < EPT0; ++k) {
+        for (int k = 0; k < BC_PT; ++k) {
             const int j = tid + k * THREADS;
             bc_pf[k] = a.block_counts[j < rows * a.blocks_per_row ? j : 0];
         }
-        tau_pf = __float_as_uint(a.tau[lane < rows ? lane : 0]);
     }
     cost_prefix(a, rows, pre, cnt_lds, wsum);
-    STAMP(1);
     if (blockIdx.x == 0)
         for (int rr = tid; rr <= rows; rr += THREADS) plan.cost_prefix[rr] = pre[rr];
+    if (bc_all) {
+#pragma unroll
+        for (int k = 0; k < BC_PT; ++k) bc_lds[tid + k * THREADS] = bc_pf[k];   // (read behind the first segment's barrier)
+    }
     const int G = attn_group_heads(a);
     const int QT = G * a.T;
     const float scale2 = a.sm_scale * 1.4426950408889634f;            // scores in log2 units
 
     // ---- per-segment inputs that are fetched ahead of time -------------------------------------------
-    // The Q tile of a segment goes through LDS: thread t fetches 16-byte chunk t%16 of query row t/16
-    // ahead of time and stores it (swizzled like a K row) when the segment is staged.
-    uint32_t ent_pf[EPT];                    // this thread's entries of the segment's first chunk
-    u32x4 q_pf = (u32x4){0u, 0u, 0u, 0u};
+    // The Q tile of a segment goes through LDS: thread t fetches 16-byte chunk t%16 of query rows t/16 (+16 ...)
+    // ahead of time and stores it (swizzled like a K row) when the segment starts.
+    u32x4 q_pf[QROUNDS];
     auto fetch_q = [&](int rr) {
         const int b = rr / a.H_kv, h = rr - b * a.H_kv;
-        const int qi = tid >> 4, ch = tid & 15;
-        q_pf = (u32x4){0u, 0u, 0u, 0u};
-        if (qi < QT) {
-            const int gh = qi / a.T, tt = qi - gh * a.T;
-            const uint16_t *qp = static_cast<const uint16_t *>(a.q) + (int64_t)b * a.q_stride_b +
-                                 (int64_t)attn_query_head(a, h, gh) * a.q_stride_h + (int64_t)tt * a.q_stride_t;
-            q_pf = *reinterpret_cast<const u32x4 *>(qp + ch * 8);
+#pragma unroll
+        for (int k = 0; k < QROUNDS; ++k) {
+            const int qi = (tid >> 4) + k * (THREADS / 16), ch = tid & 15;
+            q_pf[k] = (u32x4){0u, 0u, 0u, 0u};
+            if (qi < QT) {
+                const int gh = qi / a.T, tt = qi - gh * a.T;
+                const uint16_t *qp = static_cast<const uint16_t *>(a.q) + (int64_t)b * a.q_stride_b +
+                                     (int64_t)attn_query_head(a, h, gh) * a.q_stride_h + (int64_t)tt * a.q_stride_t;
+                q_pf[k] = *reinterpret_cast<const u32x4 *>(qp + ch * 8);
+            }
         }
     };
     auto store_q = [&]() {
-        const int qi = tid >> 4, ch = tid & 15;
-        if (qi < NQT * 16)
-            *reinterpret_cast<u32x4 *>(q_lds + qi * ROW_BYTES + ((ch ^ swz(qi & 15)) << 4)) = q_pf;
-    };
-    // row offsets (16-byte units) of list entries [first, first + n) of row rr; entries past the end of
-    // the list repeat the last kept position (their scores are masked), so every gather stays in bounds
-    auto fetch_entries = [&](int rr, int first, int n, uint32_t (&out)[EPT]) {
-        const int b = rr / a.H_kv, h = rr - b * a.H_kv;
-        const KvMap map = make_map<LAYOUT>(a, b, h);
-        const int32_t *idx = a.indices + (int64_t)rr * a.idx_stride;
-        const int count = cnt_lds[rr];
-        int jj[EPT], pos[EPT];
 #pragma unroll
-        for (int k = 0; k < EPT; ++k) {
-            jj[k] = first + tid + k * THREADS;
-            jj[k] = jj[k] < count ? jj[k] : count - 1;
+        for (int k = 0; k < QROUNDS; ++k) {
+            const int qi = (tid >> 4) + k * (THREADS / 16), ch = tid & 15;
+            if (qi < NQT * 16) *reinterpret_cast<u32x4 *>(q_lds + qi * ROW_BYTES + ((ch ^ swz(qi & 15)) << 4)) = q_pf[k];
         }
-        attn_list_pos_n(a, idx, jj, pos);
-        map.rel_n<LAYOUT>(pos, out);
-        (void)n;                                   // entries past n are computed (in bounds) and never stored
-    };
-    auto store_entries = [&](int n, const uint32_t (&in)[EPT]) {
-#pragma unroll
-        for (int k = 0; k < EPT; ++k) {
-            const int j = tid + k * THREADS;
-            if (j < n) ent_lds[j] = in[k];
-        }
-    };
-    // ---- fused path: the list is never read from memory; it is rebuilt from the draft row ----------
-    // blk_pre[b] = number of kept positions of row rr before block b (blocks of SEL_BLOCK positions)
-    uint32_t seg_tau = 0;                    // tau* of the current segment's row, as bits
-    bool bc_in_lds = false;                  // the list buffer holds the block counts of all rows
-    auto fused_prepare_row = [&](int rr) {
-        lds_barrier();
-        const int32_t *bc = a.block_counts + (int64_t)rr * a.blocks_per_row;
-        const int *bc_lds = reinterpret_cast<const int *>(ent_lds) + rr * a.blocks_per_row;
-        seg_tau = bc_in_lds ? (uint32_t)__builtin_amdgcn_readlane((int)tau_pf, __builtin_amdgcn_readfirstlane(rr)) : __float_as_uint(a.tau[rr]);
-        if (wave == 0) {
-            int running = 0;
-            for (int base = 0; base < a.blocks_per_row; base += 64) {
-                const int c = (base + lane < a.blocks_per_row) ? (bc_in_lds ? bc_lds[base + lane] : bc[base + lane]) : 0;
-                const int inc = wave_inclusive_sum(c);
-                if (base + lane < a.blocks_per_row) blk_pre[base + lane + 1] = running + inc;
-                running += __builtin_amdgcn_readlane(inc, 63);
-            }
-            if (lane == 0) blk_pre[0] = 0;
-        }
-        lds_barrier();
-        bc_in_lds = false;                   // the list buffer is about to be overwritten
-    };
-    // ent_lds[0 .. n) <- row offsets of the kept positions of rank first .. first + n - 1 of row rr.  The block
-    // prefix gives the rank at which every block of SEL_BLOCK positions starts, so the blocks that hold those
-    // ranks are independent: each wave takes every NW-th of them, compares the block's draft probabilities
-    // with tau* (16 positions per lane, as four coalesced 16-byte loads) and numbers the kept ones with
-    // wave-wide prefix sums - no workgroup-wide scan, no barrier between blocks, nothing scanned in vain.
-    auto fused_stage = [&](int rr, int first, int n) {
-        const int b = rr / a.H_kv, h = rr - b * a.H_kv;
-        const KvMap map = make_map<LAYOUT>(a, b, h);
-        const float *row = a.probs + (int64_t)b * a.probs_stride_b + (int64_t)h * a.probs_stride_h;
-        const bool aligned = (reinterpret_cast<uintptr_t>(row) & 15) == 0;
-        int len = a.seq_lens ? a.seq_lens[b] : a.n_max;
-        len = len < 0 ? 0 : (len > a.n_max ? a.n_max : len);
-        const uint32_t tau_bits = seg_tau;
-        const int count = cnt_lds[rr];
-        const int last = (first + n) < count ? (first + n) : count;      // ranks [first, last) exist
-        // blocks that hold ranks `first` and `last - 1`: blk_pre[b] <= rank < blk_pre[b + 1].  Up to 64 blocks per
-        // row every lane looks at one block (one LDS round trip instead of a chain of dependent ones).
-        int b0, b1;
-        if (a.blocks_per_row <= 64) {
-            const int lo = lane < a.blocks_per_row ? blk_pre[lane] : 0x7fffffff;
-            const int b0m = __popcll(__ballot(lo <= first)), b1m = __popcll(__ballot(lo <= last - 1));
-            b0 = (b0m > 0 ? b0m : 1) - 1;                                // blk_pre[0] = 0 <= any rank
-            b1 = (b1m > 0 ? b1m : 1) - 1;
-        } else {
-            auto block_of = [&](int rank) {
-                int lo = 0, hi = a.blocks_per_row;
-                while (hi - lo > 1) {
-                    const int mid = (lo + hi) >> 1;
-                    if (blk_pre[mid] <= rank) lo = mid; else hi = mid;
-                }
-                return lo;
-            };
-            b0 = block_of(first); b1 = block_of(last - 1);
-        }
-        constexpr int QUARTER = SEL_BLOCK / 4;                           // positions one load instruction covers
-        static_assert(QUARTER == 64 * 4, "a wave covers a quarter block with one 16-byte load per lane");
-        const bool vec_ok = aligned && len >= 4;
-        const int last4 = (len - 4) & ~3;                                // start of the row's last whole vector
-        for (int blk = b0 + wave; blk <= b1; blk += 2 * NW) {            // two blocks per round and wave
-            uint4 u[2][4];
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    const int p0 = (blk + t * NW) * SEL_BLOCK + k * QUARTER + lane * 4;
-                    if (vec_ok) {
-                        u[t][k] = *reinterpret_cast<const uint4 *>(row + (p0 < last4 ? p0 : last4));   // inside the row
-                    } else {
-                        u[t][k].x = p0 < len ? __float_as_uint(row[p0]) : 0u;
-                        u[t][k].y = p0 + 1 < len ? __float_as_uint(row[p0 + 1]) : 0u;
-                        u[t][k].z = p0 + 2 < len ? __float_as_uint(row[p0 + 2]) : 0u;
-                        u[t][k].w = p0 + 3 < len ? __float_as_uint(row[p0 + 3]) : 0u;
-                    }
-                }
-            }
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                const int bb = blk + t * NW;
-                if (bb > b1) break;                                      // uniform over the wave
-                int rk = blk_pre[bb];                                    // rank of the block's first kept position
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    const int p0 = bb * SEL_BLOCK + k * QUARTER + lane * 4;
-                    uint32_t x[4] = {u[t][k].x, u[t][k].y, u[t][k].z, u[t][k].w};
-                    if (vec_ok && p0 + 3 >= len) {                       // reaches past the row's end: entry by entry
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) x[i] = (p0 + i < len) ? __float_as_uint(row[p0 + i]) : 0u;
-                    }
-                    // kept entries before this lane's four: ballots and per-lane bit counts (no scan)
-                    bool keep[4];
-                    unsigned long long m[4];
-                    int before = 0;
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        keep[i] = x[i] != 0x80000000u && x[i] >= tau_bits;       // -0.0 is zero, as in the selection
-                        m[i] = __ballot(keep[i]);
-                        before = __builtin_amdgcn_mbcnt_hi((uint32_t)(m[i] >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m[i], before));
-                    }
-                    int mine = rk + before - first;                      // slot of this lane's first kept entry
-                    const uint32_t off0 = LAYOUT == CONTIGUOUS ? (uint32_t)(map.rel<LAYOUT>(p0) >> 3) : 0u;
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        // (kept positions lie below the row's length, so the page-table lookup stays inside the table)
-                        if (keep[i] && mine >= 0 && mine < last - first)
-                            ent_lds[mine] = LAYOUT == CONTIGUOUS ? off0 + (uint32_t)i * (uint32_t)(map.stride_n >> 3)
-                                                                 : (uint32_t)(map.rel<LAYOUT>(p0 + i) >> 3);
-                        mine += keep[i] ? 1 : 0;
-                    }
-                    rk += __popcll(m[0]) + __popcll(m[1]) + __popcll(m[2]) + __popcll(m[3]);
-                }
-            }
-        }
-        STAMP_ONCE(8);
-        lds_barrier();
-        STAMP_ONCE(10);
-        // ranks past the end of the list repeat the last kept position (their scores are masked)
-        for (int j = last - first + tid; j < n; j += THREADS) ent_lds[j] = ent_lds[last - first - 1];
     };
 
     // This workgroup's share of the cost line, and the rows of which it holds tiles.  Up to 64 rows, lane i looks
@@ -629,9 +533,10 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
         row_cnt = lane < rows ? cnt_lds[lane] : 0;
     }
     const int total = few_rows ? __builtin_amdgcn_readlane(row_hi, rows - 1) : pre[rows];
-    const Share sh = make_share(total, plan.n_wg, blockIdx.x);
+    const int my_share = share_index(blockIdx.x, plan.n_wg);
+    const Share sh = make_share(total, plan.n_wg, my_share);
     const int c0 = sh.c0, c1 = sh.c1;
-    if (c0 >= c1) { STAMP_DUMP(); return; }
+    if (c0 >= c1) return;                                // more workgroups than units of work
     int my_lb = 0, my_le = 0;                            // few rows: local tile range of row `lane`
     unsigned long long seg_mask = 0;                     // few rows: the rows with tiles in this share
     if (few_rows) {
@@ -659,133 +564,153 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
         return sh.next_seg(pre, cnt_lds, rows, r);
     };
     int r = few_rows ? next_seg(0) : sh.first_seg(pre, cnt_lds, rows);
-    if (r >= rows) { STAMP_DUMP(); return; }
 
-    bool first_staged = false;               // the first chunk's list, Q and the tile counter are already in LDS
-    if (bc_all) {
-#pragma unroll
-        for (int k = 0; k < EPT0; ++k) reinterpret_cast<int *>(ent_lds)[tid + k * THREADS] = bc_pf[k];
-        bc_in_lds = true;                    // visible after the barrier that fused_prepare_row starts with
-    }
-    {
-        int lb, le;
-        seg_range(r, lb, le);
-        STAMP_ONCE(12);
-        const int n0 = ((le - lb) < CHUNK_TILES ? (le - lb) : CHUNK_TILES) * TILE;
-        // Head start: wave w fetches the indices of tile w of the first chunk itself and requests that
-        // tile's rows at once, instead of waiting until the whole chunk's list is staged in LDS.  These index
-        // loads go out before everything else the segment needs, since the first gathers wait for them.
-        const int n_ahead = (n0 / TILE) < NW ? (n0 / TILE) : NW;
-        const bool ahead = !FUSED && wave < n_ahead;
-        const int b_first = r / a.H_kv, h_first = r - b_first * a.H_kv;
-        const KvMap map_first = make_map<LAYOUT>(a, b_first, h_first);
-        int jj_first[8], raw_first[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) jj_first[i] = raw_first[i] = 0;
-        // Everything the ordinary start requests is requested and taken in inside this one block, before any
-        // gather goes out: loads return in order, so a value left outstanding here - even one that only the
-        // compiler's bookkeeping believes outstanding on some path - could later only be waited for together with
-        // the gathers issued behind it, and such a wait holds the wave until its first tile has landed.
-        if (!FUSED) {
-            if (ahead) {
-                const int32_t *idx = a.indices + (int64_t)r * a.idx_stride;
-                const int count = cnt_lds[r];
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    jj_first[i] = (lb + wave) * TILE + 4 * i + g;
-                    jj_first[i] = jj_first[i] < count ? jj_first[i] : count - 1;
-                }
-                attn_list_request_n(a, idx, jj_first, raw_first);
-            }
-            fetch_q(r);
-            fetch_entries(r, lb * TILE, n0, ent_pf);
-            asm volatile("" ::"v"(q_pf));
-#pragma unroll
-            for (int k = 0; k < EPT; ++k) asm volatile("" ::"v"(ent_pf[k]));
-#pragma unroll
-            for (int i = 0; i < 8; ++i) asm volatile("" ::"v"(raw_first[i]));
-        }
-        if (FUSED) {
-            fetch_q(r);
-            // The first chunk of the first segment is staged right here, ahead of the set-up code of the tile loop
-            // (several hundred instructions that the unfused path runs while its first gathers are in flight).
-            fused_prepare_row(r);
-            STAMP_ONCE(14);
-            fused_stage(r, lb * TILE, n0);
-            first_staged = true;
-            // Head start as on the unfused path: wave w requests tile w of the staged chunk at once.
-            asm volatile("" ::"v"(q_pf));        // Q has arrived long ago; taken in before the gathers (see below)
-            store_q();
-            if (tid == 0) *tile_ctr = n_ahead;
-            lds_barrier();                       // the padding entries behind the end of the list, Q and the counter are in place
-            if (wave < n_ahead) {
-                uint32_t e[8];
-                lds_read_entries(e, ent_addr + (uint32_t)((wave * TILE + g) << 2));
-                const char *kb0 = static_cast<const char *>(a.k) + map_first.base * 2;
-                const char *vb0 = static_cast<const char *>(a.v) + map_first.base * 2;
-#pragma unroll
-                for (int i = 0; i < 8; ++i)
-                    __builtin_amdgcn_global_load_lds(GLOBAL_PTR(kb0 + ((int64_t)e[i] << 4) + lane_chunk[i & 3]),
-                                                     LDS_PTR(void, wave_lds + i * 1024), 16, 0, KV_AUX);
-#pragma unroll
-                for (int i = 0; i < 8; ++i)
-                    __builtin_amdgcn_global_load_lds(GLOBAL_PTR(vb0 + ((int64_t)e[i] << 4) + lane_chunk[i & 3]),
-                                                     LDS_PTR(void, wave_lds + TILE_BYTES + i * 1024), 16, 0, KV_AUX);
-            }
-        }
-        // Q goes into LDS right here.  Inside the segment loop the same store comes after a point where Q may
-        // have been requested again (for the next segment) with gathers behind it, and the wait placed there
-        // would, on the first pass, hold every wave until its head-start gathers had landed.
-        // The first chunk's list goes in with it, and the one barrier that makes both visible comes before the
-        // gathers: behind them every wave then runs on to its first tile without meeting the others again.
-        if (!FUSED) {
-            store_q();
-            store_entries(n0, ent_pf);
-            if (tid == 0) *tile_ctr = n_ahead;
-            first_staged = true;
-            lds_barrier();
-        }
-        STAMP_ONCE(13);
-        if (ahead) {
-            const KvMap &map = map_first;
-            int pos_first[8];
-            attn_list_finish_n(a, jj_first, raw_first, pos_first);
-            uint32_t e[8];
-            map.rel_n<LAYOUT>(pos_first, e);
-            const char *kb0 = static_cast<const char *>(a.k) + map.base * 2;
-            const char *vb0 = static_cast<const char *>(a.v) + map.base * 2;
-#pragma unroll
-            for (int i = 0; i < 8; ++i)
-                __builtin_amdgcn_global_load_lds(GLOBAL_PTR(kb0 + ((int64_t)e[i] << 4) + lane_chunk[i & 3]),
-                                                 LDS_PTR(void, wave_lds + i * 1024), 16, 0, KV_AUX);
-#pragma unroll
-            for (int i = 0; i < 8; ++i)
-                __builtin_amdgcn_global_load_lds(GLOBAL_PTR(vb0 + ((int64_t)e[i] << 4) + lane_chunk[i & 3]),
-                                                 LDS_PTR(void, wave_lds + TILE_BYTES + i * 1024), 16, 0, KV_AUX);
-        }
-    }
-    if (!FUSED) STAMP_ONCE(8);
-    bool head_start = true;                   // true until the first chunk of the first segment has begun
+    bool first_seg = true;
+    if (r < rows) fetch_q(r);
 
     while (r < rows) {
         int lt_begin, lt_end;
         seg_range(r, lt_begin, lt_end);
         const int r_next = next_seg(r + 1);
         const int b = r / a.H_kv, h = r - b * a.H_kv;
-        const int count = cnt_lds[r];
+        const int count = few_rows ? __builtin_amdgcn_readlane(row_cnt, __builtin_amdgcn_readfirstlane(r)) : cnt_lds[r];
+        const int p_lo = few_rows ? __builtin_amdgcn_readlane(row_lo, __builtin_amdgcn_readfirstlane(r)) : pre[r];
+        const int p_hi = few_rows ? __builtin_amdgcn_readlane(row_hi, __builtin_amdgcn_readfirstlane(r)) : pre[r + 1];
+        const int tiles = (count + TILE - 1) / TILE;
+        const int tile_end = lt_end;             // the tiles [lt_begin, lt_end) of the row are this workgroup's
         const KvMap map = make_map<LAYOUT>(a, b, h);
         const char *kbh = static_cast<const char *>(a.k) + map.base * 2;
         const char *vbh = static_cast<const char *>(a.v) + map.base * 2;
-        STAMP_ONCE(15);
+        const int32_t *idx_row = (SRC == LIST && !a.dense) ? a.indices + (int64_t)r * a.idx_stride : nullptr;
+        const uint32_t *mask_row = SRC == MASK ? a.kept_mask + (int64_t)r * a.blocks_per_row * (SEL_BLOCK / 32) : nullptr;
+        const int n_idx = (SRC == MASK || !a.dense) ? 1 : 0;            // LDS-DMA instructions per tile for list / mask words
 
-        f32x4 o[NQT][8];                     // O^T[dv = 16t + 4g + i][q = l16]
-        float m_ref[NQT], l_sum[NQT];        // reference max (log2 units) and sum of weights
-                                             // (zeroed once the first chunk is staged, which keeps the
-                                             //  registers free during the staging)
-
-        // row offsets (in 16-byte units) of the 8 rows this lane helps to fetch for one tile
-        auto read_entries = [&](int tile_in_chunk, uint32_t (&ent)[8]) {
-            lds_read_entries(ent, ent_addr + (uint32_t)((tile_in_chunk * TILE + g) << 2));
+        // ---- the wave's tiles --------------------------------------------------------------------------
+        // The first STATIC_ROUNDS tiles of a wave are fixed (tile k of the share to wave k mod NW); after that the
+        // waves claim tiles from the LDS counter, or - deterministic mode - go on in the same fixed pattern.
+        int t_cur = lt_begin + wave, t_nxt = t_cur + NW, t_nn = t_nxt + NW;
+        int det_next = t_nn + NW;
+        const int dyn_base = lt_begin + STATIC_ROUNDS * NW;
+        auto claim = [&]() -> int {
+            if (plan.deterministic) { const int t = det_next; det_next += NW; return t; }
+            return dyn_base + lds_claim(ctr_addr, lane);
+        };
+        // Mask source: where a tile's 32 kept positions start.  Returns the block b that holds rank 32 t and
+        // leaves in `skip` the kept positions of b that come before that rank.  (LDS reads by hand, see above.)
+        auto mask_locate = [&](int t, int &skip) -> int {
+            const int rank = t * TILE;
+            const int nb = a.blocks_per_row;
+            const int stride = (nb + 63) >> 6;                          // blocks per lane of the coarse step
+            int lo = lane * stride < nb ? (int)lds_read_word(blk_addr + (uint32_t)(lane * stride) * 4) : 0x7fffffff;
+            int cnum = __popcll(__ballot(lo <= rank));                  // blk_pre[0] = 0 <= rank: at least 1
+            int bb = (cnum > 0 ? cnum - 1 : 0) * stride;
+            if (stride > 1) {
+                lo = (lane < stride && bb + lane < nb) ? (int)lds_read_word(blk_addr + (uint32_t)(bb + lane) * 4) : 0x7fffffff;
+                cnum = __popcll(__ballot(lo <= rank));
+                bb += cnum > 0 ? cnum - 1 : 0;
+            }
+            bb = __builtin_amdgcn_readfirstlane(bb);
+            skip = rank - (int)__builtin_amdgcn_readfirstlane(lds_read_word(blk_addr + (uint32_t)bb * 4));
+            return bb;
+        };
+        // Requests the words tile t needs into slot s (one LDS-DMA instruction): its 32 list words, or 64 words of
+        // the kept mask from the block that holds its first rank.  Tiles past the end request the last tile's.
+        int m_blk0 = 0, m_blk1 = 0, m_skip0 = 0, m_skip1 = 0;           // mask source: what slots 0 and 1 hold
+        auto request = [&](int t, int s) {
+            if (t >= tiles) t = tiles - 1;
+            if (SRC == MASK) {
+                int skip;
+                const int bb = mask_locate(t, skip);
+                if (s) { m_blk1 = bb; m_skip1 = skip; } else { m_blk0 = bb; m_skip0 = skip; }
+                const int nw = a.blocks_per_row * (SEL_BLOCK / 32);
+                int w = bb * (SEL_BLOCK / 32) + lane;
+                w = w < nw ? w : nw - 1;
+                __builtin_amdgcn_global_load_lds(GLOBAL_PTR(mask_row + w), LDS_PTR(void, slot_lds + s * SLOT_BYTES), 4, 0, 0);
+            } else if (!a.dense) {
+                int jj = t * TILE + (lane & 31);
+                jj = jj < count ? jj : count - 1;
+                __builtin_amdgcn_global_load_lds(GLOBAL_PTR(idx_row + (jj >> a.chunk_shift)),
+                                                 LDS_PTR(void, slot_lds + s * SLOT_BYTES), 4, 0, 0);
+            }
+        };
+        // Mask source: turns the 64 mask words in slot s into the 32 positions of tile t (table s of the wave).  The
+        // words start at block m_blk; the tile's ranks start m_skip kept positions into them.  Lane w counts its
+        // word's bits and a wave-wide prefix gives the rank of its first bit; every word that holds ranks of the
+        // tile marks the first of them, a prefix maximum over the marks tells lane j (< 32) which word holds rank
+        // j, and the lane picks its bit out of that word: no loop over bits.  Done one iteration before the
+        // tile's gathers are issued.  (A row so sparse that 2048 positions hold fewer than 32 kept ones takes
+        // further rounds over the next 64 words.)
+        auto decode = [&](int t, int s) {
+            if (t >= tiles) t = tiles - 1;
+            const int need = (count - t * TILE) < TILE ? (count - t * TILE) : TILE;
+            int have = 0;                                               // ranks of the tile found so far
+            int word0 = (s ? m_blk1 : m_blk0) * (SEL_BLOCK / 32);
+            int skip = s ? m_skip1 : m_skip0;
+            const int nw = a.blocks_per_row * (SEL_BLOCK / 32);
+            const uint32_t table = scat_addr + (uint32_t)s * 128;
+            uint32_t bits = lds_read_word(slot_addr + (uint32_t)(s * SLOT_BYTES + lane * 4));
+            for (;;) {
+                if (word0 + lane >= nw) bits = 0u;
+                const int pc = __popc(bits);
+                const int inc = wave_inclusive_sum(pc);
+                const int ex = inc - pc;
+                const int got = __builtin_amdgcn_readlane(inc, 63) - skip;     // ranks of the tile among these words
+                if (got > 0) {
+                    const int lo = ex - skip + have, hi = lo + pc;      // table slots this word's bits would take
+                    if (lane < 32) lds_write_word(mark_addr + (uint32_t)lane * 4, 0u);
+                    if (pc > 0 && hi > have && lo < need)
+                        lds_write_word(mark_addr + (uint32_t)(lo > have ? lo : have) * 4, (uint32_t)lane + 1u);
+                    lds_wait();
+                    const int mark = lane < 32 ? (int)lds_read_word(mark_addr + (uint32_t)lane * 4) : 0;
+                    const int owner = prefix_max32(lane >= have ? mark : 0) - 1;     // the word that holds rank `lane`
+                    const int src = owner >= 0 ? owner : 0;
+                    const uint32_t wbits = lane_read(bits, src);
+                    const int wex = (int)lane_read((uint32_t)ex, src);
+                    const int top = (have + got) < need ? (have + got) : need;
+                    if (lane >= have && lane < top && owner >= 0) {
+                        const int k = lane - have + skip - wex;         // which of the word's bits
+                        lds_write_word(table + (uint32_t)lane * 4, (uint32_t)((word0 + src) * 32 + kth_set_bit(wbits, k)));
+                    }
+                }
+                have += got > 0 ? got : 0;
+                skip = got < 0 ? -got : 0;
+                word0 += 64;
+                if (have >= need || word0 >= nw) break;
+                bits = mask_row[word0 + lane < nw ? word0 + lane : nw - 1];   // sparse row: the tile reaches further
+            }
+            lds_wait();
+            if (need < TILE) {                                          // ranks past the end repeat the last kept position
+                const uint32_t last_pos = lds_read_word(table + (uint32_t)((need > 0 ? need : 1) - 1) * 4);
+                if (lane >= need && lane < TILE) lds_write_word(table + (uint32_t)lane * 4, last_pos);
+                lds_wait();
+            }
+        };
+        // Row offsets (16-byte units) of the 8 rows this lane helps to fetch for tile t, whose list words (or decoded
+        // positions) are in slot / table s.
+        auto entries = [&](int t, int s, uint32_t (&ent)[8]) {
+            int pos[8], jj[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                jj[i] = t * TILE + 4 * i + g;
+                jj[i] = jj[i] < count ? jj[i] : count - 1;              // ranks past the end repeat the last kept position
+            }
+            if (SRC == MASK) {
+                uint32_t e[8];
+                lds_read_entries(e, scat_addr + (uint32_t)(s * 128 + g * 4));
+                // (a mask that does not hold `count` bits would leave table entries unwritten: stay inside the row)
+#pragma unroll
+                for (int i = 0; i < 8; ++i) pos[i] = e[i] < (uint32_t)a.n_max ? (int)e[i] : a.n_max - 1;
+            } else if (a.dense) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) pos[i] = jj[i];
+            } else {
+                uint32_t e[8];
+                lds_read_entries(e, slot_addr + (uint32_t)(s * SLOT_BYTES + g * 4));
+                const int cs = a.chunk_shift, low = (1 << cs) - 1;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) pos[i] = (int)(e[i] << cs) | (jj[i] & low);
+            }
+            map.rel_n<LAYOUT>(pos, ent);
         };
         // gather 32 rows of one tensor into this wave's buffer: 8 instructions of 4 rows x 256 B
         auto issue = [&](const char *base, char *buf, const uint32_t (&ent)[8]) {
@@ -796,61 +721,55 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
             }
         };
 
-        for (int ch_begin = lt_begin; ch_begin < lt_end; ch_begin += CHUNK_TILES) {
-            const int ch_end = (ch_begin + CHUNK_TILES) < lt_end ? (ch_begin + CHUNK_TILES) : lt_end;
-            // ---- stage this chunk's row offsets in LDS (the first chunk's were fetched ahead) ----------
-            if (FUSED && !first_staged) {
-                if (ch_begin == lt_begin) fused_prepare_row(r); else lds_barrier();
-                fused_stage(r, ch_begin * TILE, (ch_end - ch_begin) * TILE);
-                if (ch_begin == lt_begin) store_q();
-                if (tid == 0) *tile_ctr = 0;
-                lds_barrier();
-            } else if (!first_staged) {
-                if (ch_begin != lt_begin) fetch_entries(r, ch_begin * TILE, (ch_end - ch_begin) * TILE, ent_pf);
-                lds_barrier();                                       // previous users of ent_lds / q_lds are done
-                store_entries((ch_end - ch_begin) * TILE, ent_pf);
-                if (ch_begin == lt_begin) store_q();
-                if (tid == 0) *tile_ctr = 0;
-                lds_barrier();
-            } else {
-                first_staged = false;                                // staged, and made visible, before the loop
-                STAMP_ONCE(2);
-            }
-            STAMP_ONCE(9);
-            if (ch_begin == lt_begin) {
-#pragma unroll
-                for (int qt = 0; qt < NQT; ++qt) {
-                    m_ref[qt] = -INFINITY;
-                    l_sum[qt] = 0.0f;
-#pragma unroll
-                    for (int t = 0; t < 8; ++t) o[qt][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        // ---- start of the segment: the words of the wave's first two tiles are requested before anything else the
+        //      segment needs, since the first gathers wait for them (counts -> list words -> K/V rows are three
+        //      dependent trips to memory); then Q goes into LDS ---------------------------------------------------
+        if (!first_seg) lds_barrier();           // the previous segment's readers of the wave buffers, slots and Q are done
+        if (SRC == MASK) {
+            // the row's block prefix first: a tile's mask words are found through it
+            if (first_seg && bc_all) lds_barrier();                     // the block counts of all rows are in LDS
+            if (wave == 0) {
+                const int32_t *bc = a.block_counts + (int64_t)r * a.blocks_per_row;
+                int running = 0;
+                for (int base = 0; base < a.blocks_per_row; base += 64) {
+                    const int c = (base + lane < a.blocks_per_row) ? (bc_all ? bc_lds[r * a.blocks_per_row + base + lane] : bc[base + lane]) : 0;
+                    const int inc = wave_inclusive_sum(c);
+                    if (base + lane < a.blocks_per_row) blk_pre[base + lane + 1] = running + inc;
+                    running += __builtin_amdgcn_readlane(inc, 63);
                 }
+                if (lane == 0) blk_pre[0] = 0;
             }
+            lds_barrier();
+        }
+        if (t_cur < tile_end) { request(t_cur, 0); request(t_nxt, 1); }
+        store_q();
+        if (tid == 0) misc[0] = 0;
+        lds_barrier();
 
-            // The gathers are not tracked by the compiler's wait insertion; every wait on them is
-            // written out.  Per wave the order of issue is K(t), V(t), K(t+1), V(t+1), ...
-            // Tiles of the chunk are claimed by the waves as they go (a wave that gets its data later
-            // simply takes fewer), one claim ahead of the tile whose gathers are being issued.
+        f32x4 o[NQT][8];                     // O^T[dv = 16t + 4g + i][q = l16]
+        float m_ref[NQT], l_sum[NQT];        // reference max (log2 units) and sum of weights
+#pragma unroll
+        for (int qt = 0; qt < NQT; ++qt) {
+            m_ref[qt] = -INFINITY;
+            l_sum[qt] = 0.0f;
+#pragma unroll
+            for (int t = 0; t < 8; ++t) o[qt][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        }
+
+        if (t_cur < tile_end) {
+            // The gathers and word requests are not tracked by the compiler's wait insertion; every wait on them is
+            // written out.  Order of issue per wave and iteration: K(next) ... V(next) words(third).
             uint32_t ent[8];
-            const int n_ch = ch_end - ch_begin;
-            int cur;
-            if (head_start && wave < n_ch) {
-                cur = wave;                                            // already requested above
-            } else {
-                cur = lds_claim(ctr_addr, lane);
-                if (cur < n_ch) {
-                    read_entries(cur, ent);
-                    issue(kbh, wave_lds, ent);
-                    issue(vbh, wave_lds + TILE_BYTES, ent);
-                }
-            }
-            head_start = false;
-            int nxt = lds_claim(ctr_addr, lane);
-            while (cur < n_ch) {
-                const int lt = ch_begin + cur;
-                const bool has_next = nxt < n_ch;
-                asm volatile("s_waitcnt vmcnt(8)" ::: "memory");        // K(t) landed; V(t) may be in flight
-                if (!FUSED) STAMP_ONCE(10);
+            vm_wait(0);                                                 // the words of the first two tiles are there
+            if (SRC == MASK) { decode(t_cur, 0); decode(t_nxt, 1); }
+            entries(t_cur, 0, ent);
+            issue(kbh, wave_lds, ent);
+            issue(vbh, wave_lds + TILE_BYTES, ent);
+            request(t_nn, 0);
+            int s_nxt = 1;                                              // slot with the words of t_nxt; t_nn's is the other
+            while (t_cur < tile_end) {
+                const bool has_next = t_nxt < tile_end;
+                vm_wait(8 + n_idx);                                     // K(cur) landed; V(cur) and the last request may be in flight
 
                 // ---- S^T[pos][q] = K Q^T -----------------------------------------------------------
                 f32x4 s[NQT][2];
@@ -858,7 +777,7 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
                     KFrags kf;
                     lds_read_k(kf, k_off);
                     if (has_next) {                                    // the K buffer is free again
-                        read_entries(nxt, ent);
+                        entries(t_nxt, s_nxt, ent);
                         issue(kbh, wave_lds, ent);
                     }
 #pragma unroll
@@ -878,7 +797,7 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
                 }
 
                 // ---- softmax weights; lane (q = l16, g) holds positions 16pt + 4g + i ---------------
-                const int remaining = count - lt * TILE;               // > 0; < TILE only on a row's last tile
+                const int remaining = count - t_cur * TILE;            // > 0; < TILE only on a row's last tile
                 h16x8 p_hi[NQT], p_lo[NQT];
 #pragma unroll
                 for (int qt = 0; qt < NQT; ++qt) {
@@ -919,8 +838,8 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
                 }
 
                 // ---- O^T += V^T P^T -----------------------------------------------------------------
-                if (has_next) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");   // V(t) landed; K(t+1) in flight
-                else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                if (has_next) vm_wait(8 + n_idx);                      // V(cur) landed; the last request and K(next) in flight
+                else vm_wait(0);
 #pragma unroll
                 for (int tb = 0; tb < 8; tb += 4) {                    // four 16-wide dv tiles per batch
                     VFrags vh;
@@ -937,28 +856,30 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
                         }
                     }
                 }
-                cur = nxt;
-                if (has_next) nxt = lds_claim(ctr_addr, lane);
+                // ---- the tile after the next two: claim it and request its words ------------------------------
+                int t_new = tile_end;
+                if (has_next) {
+                    t_new = claim();
+                    request(t_new, s_nxt);                             // the slot t_nxt's words were read from
+                    if (SRC == MASK && t_nn < tile_end) {              // the positions of the tile that is next but one
+                        vm_wait(17);                                   // its words (requested an iteration ago) are there
+                        decode(t_nn, s_nxt ^ 1);
+                    }
+                }
+                t_cur = t_nxt; t_nxt = t_nn; t_nn = t_new;
+                s_nxt ^= 1;
             }
-        }   // chunks
-        STAMP(3);
-        STAMP_ONCE(11);
+        }
+        vm_wait(0);                              // nothing of this wave's is in flight any more (the slots are reused below)
 
         // ---- request what the next segment needs, to arrive while this one is wrapped up --------------
-        if (r_next < rows) {
-            int lb, le;
-            seg_range(r_next, lb, le);
-            fetch_q(r_next);
-            const int n0 = ((le - lb) < CHUNK_TILES ? (le - lb) : CHUNK_TILES) * TILE;
-            if (!FUSED) fetch_entries(r_next, lb * TILE, n0, ent_pf);
-        }
+        if (r_next < rows) fetch_q(r_next);
 
         // ---- combine the waves of this workgroup: every wave hands its state over lane by lane through its
         //      own tile buffers, which are idle as soon as the wave itself has no tile left - before the barrier,
         //      so that only the last wave's hand-over is waited for; wave w then reduces and writes the
-        //      (query tile, dv tile) blocks k = w * KPW .. of all eight states.  (m, l) per query row go into the
-        //      block-prefix array, which nobody reads while tiles are processed. -----------------------------
-        float *mlw = ml_lds;                     // [NW][16 query rows][2 * NQT]: m, l (summed over the lane groups)
+        //      (query tile, dv tile) blocks k = w * KPW .. of all states.  (m, l) per query row go into the
+        //      wave's first word slot. ----------------------------------------------------------------------
         {
             float *dmp = reinterpret_cast<float *>(wave_lds);                  // [NQT * 8][64 lanes] float4
 #pragma unroll
@@ -970,20 +891,20 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
                 l += __shfl_xor(l, 16, 64);
                 l += __shfl_xor(l, 32, 64);
                 if (g == 0) {
-                    mlw[(wave * 16 + l16) * 2 * NQT + 2 * qt] = m_ref[qt];
-                    mlw[(wave * 16 + l16) * 2 * NQT + 2 * qt + 1] = l;
+                    mlw[wave * 128 + l16 * 2 * NQT + 2 * qt] = m_ref[qt];
+                    mlw[wave * 128 + l16 * 2 * NQT + 2 * qt + 1] = l;
                 }
             }
         }
-        lds_barrier();                         // every wave has handed over, and is done with ent_lds and Q
-        STAMP(4);
-        STAMP(5);
-        // Workgroups w0..w1 share row r: a row owned by one workgroup is finished here; otherwise the
-        // partial goes to slot w + r for the merge kernel.
-        const int w0 = share_of(total, plan.n_wg, pre[r] + SEG_COST), w1 = share_of(total, plan.n_wg, pre[r + 1] - 1);
+        lds_barrier();                         // every wave has handed over, and is done with Q
+        // Workgroups w_first..w_last share row r: a row owned by one workgroup is finished here; otherwise the
+        // partial goes to slot (share + r) for the merge kernel.
+        const int w_first = share_of(total, plan.n_wg, p_lo + SEG_COST), w_last = share_of(total, plan.n_wg, p_hi - 1);
+        const bool final_here = w_first == w_last && !a.k_new;
         {
-            constexpr int KPW = NQT * 8 / NW;    // blocks per wave (2 or 1)
-            const int slot = blockIdx.x + r;
+            constexpr int KPW = NQT * 8 / NW;    // blocks per wave
+            static_assert(KPW >= 1, "more waves than blocks to reduce");
+            const int slot = my_share + r;
             float *po = plan.part_o + (int64_t)slot * QTP * D;
             float *pml = plan.part_ml + (int64_t)slot * QTP * 2;
 #pragma unroll
@@ -992,20 +913,20 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
                 const int qt = k >> 3, t = k & 7;
                 float m = -INFINITY;
 #pragma unroll
-                for (int w = 0; w < NW; ++w) m = fmaxf(m, mlw[(w * 16 + l16) * 2 * NQT + 2 * qt]);
+                for (int w = 0; w < NW; ++w) m = fmaxf(m, mlw[w * 128 + l16 * 2 * NQT + 2 * qt]);
                 f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
                 float l = 0.0f;
 #pragma unroll
                 for (int w = 0; w < NW; ++w) {
-                    const float mw = mlw[(w * 16 + l16) * 2 * NQT + 2 * qt];
+                    const float mw = mlw[w * 128 + l16 * 2 * NQT + 2 * qt];
                     const float f = (mw == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(mw - m);
-                    l += f * mlw[(w * 16 + l16) * 2 * NQT + 2 * qt + 1];
+                    l += f * mlw[w * 128 + l16 * 2 * NQT + 2 * qt + 1];
                     acc += f * *reinterpret_cast<const f32x4 *>(reinterpret_cast<const float *>(smem + w * WAVE_LDS) +
                                                                 (k * 64 + lane) * 4);
                 }
                 const int q = qt * 16 + l16;
                 if (q < QT) {
-                    if (w0 == w1 && !a.k_new) {
+                    if (final_here) {
                         const int gh = q / a.T, tt = q - gh * a.T;
                         const int64_t orow = ((int64_t)b * a.H_q + attn_query_head(a, h, gh)) * a.T + tt;
                         const f32x4 res = l > 0.0f ? acc / l : (f32x4){0.f, 0.f, 0.f, 0.f};
@@ -1023,11 +944,10 @@ __global__ __launch_bounds__(THREADS) void attn_mfma_kernel(AttnLaunch a, Plan p
                 }
             }
         }
-        STAMP(6);
+        first_seg = false;
         r = r_next;                              // the next segment starts with a barrier of its own
     }
-    STAMP(7);
-    STAMP_DUMP();
+
 }
 
 // After the main kernel, one workgroup per (row, query row): rows shared by several workgroups get
@@ -1088,6 +1008,20 @@ __global__ void merge_partials_kernel(AttnLaunch a, Plan plan, int qtp)
     if (a.lse && dv == 0) a.lse[orow] = acc.l > 0.0f ? (acc.m + log2f(acc.l)) * 0.6931471805599453f : -INFINITY;
 }
 
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// every kernel variant, for the one-time LDS-size attribute
+struct Variant { int nqt, layout, src; bool f16; const void *fn; };
+#define V4(NQT, LAY, SRC) \
+    {NQT, LAY, SRC, false, reinterpret_cast<const void *>(&attn_mfma_kernel<NQT, LAY, SRC, false>)}, \
+    {NQT, LAY, SRC, true, reinterpret_cast<const void *>(&attn_mfma_kernel<NQT, LAY, SRC, true>)}
+const Variant g_variants[] = {
+    V4(1, CONTIGUOUS, LIST), V4(1, PAGE_TABLE, LIST), V4(1, PHYSICAL, LIST),
+    V4(2, CONTIGUOUS, LIST), V4(2, PAGE_TABLE, LIST), V4(2, PHYSICAL, LIST),
+    V4(1, CONTIGUOUS, MASK), V4(1, PAGE_TABLE, MASK), V4(2, CONTIGUOUS, MASK), V4(2, PAGE_TABLE, MASK),
+};
+#undef V4
+
 }  // namespace
 
 bool attn_mfma_supported(const AttnLaunch &a)
@@ -1096,16 +1030,41 @@ bool attn_mfma_supported(const AttnLaunch &a)
     return (a.dtype == SPECATTN_BF16 || a.dtype == SPECATTN_F16) && a.d == 128 && a.T <= 32 && a.H_kv <= MAX_ROWS;
 }
 
-int attn_mfma_workgroups() { return cu_count(); }
+int attn_mfma_workgroups() { return cu_count() * WG_PER_CU; }
+
+// The kernels use more LDS than the default limit: raise it for every variant, once per device.
+specattn_status attn_mfma_configure()
+{
+    constexpr int MAX_DEVICES = 64;
+    static std::mutex mu;
+    static bool done[MAX_DEVICES] = {false};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) {
+        (void)hipGetLastError();
+        set_error("no current device");
+        return SPECATTN_EHIP;
+    }
+    std::lock_guard<std::mutex> lock(mu);
+    if (done[dev]) return SPECATTN_OK;
+    for (const Variant &v : g_variants) {
+        if (hipFuncSetAttribute(v.fn, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess) {
+            (void)hipGetLastError();
+            set_error("cannot reserve %d bytes of LDS", LDS_BYTES);
+            return SPECATTN_EHIP;
+        }
+    }
+    done[dev] = true;
+    return SPECATTN_OK;
+}
 
 size_t attn_mfma_workspace_bytes(int rows, int G, int T)
 {
     if (rows > MAX_ROWS) rows = MAX_ROWS;                 // larger batches run as several launches
     const size_t qtp = (G * T <= 16) ? 16 : 32;
     const size_t slots = (size_t)attn_mfma_workgroups() + rows;
-    size_t bytes = (((size_t)rows + 1) * sizeof(int32_t) + 255) & ~(size_t)255;        // cost prefix
+    size_t bytes = align256(((size_t)rows + 1) * sizeof(int32_t));                        // cost prefix
     bytes += slots * qtp * (D + 2) * sizeof(float);
-    return (bytes + 255) & ~(size_t)255;
+    return align256(bytes);
 }
 
 static specattn_status launch_chunk(const AttnLaunch &a, hipStream_t stream)
@@ -1124,50 +1083,26 @@ static specattn_status launch_chunk(const AttnLaunch &a, hipStream_t stream)
     }
     char *ws = static_cast<char *>(a.workspace);
     plan.cost_prefix = reinterpret_cast<int32_t *>(ws);
-    ws += (((size_t)rows + 1) * sizeof(int32_t) + 255) & ~(size_t)255;
+    ws += align256(((size_t)rows + 1) * sizeof(int32_t));
     plan.part_ml = reinterpret_cast<float *>(ws);
     plan.part_o = plan.part_ml + slots * qtp * 2;
-    const size_t lds = LDS_BYTES;
+    plan.deterministic = a.deterministic ? 1 : 0;
     const int layout = a.indices_are_physical ? PHYSICAL : (a.page_table ? PAGE_TABLE : CONTIGUOUS);
-    const void *fn = nullptr;
-    const bool fused = a.probs != nullptr;
+    const int src = a.kept_mask ? MASK : LIST;
     const bool f16 = a.dtype == SPECATTN_F16;
-#define PICK(NQT, LAY, FUS)                                                                                      \
-    if (qtp == 16 * NQT && layout == LAY && fused == FUS)                                                        \
-        fn = f16 ? reinterpret_cast<const void *>(&attn_mfma_kernel<NQT, LAY, FUS, true>)                        \
-                 : reinterpret_cast<const void *>(&attn_mfma_kernel<NQT, LAY, FUS, false>);
-    PICK(1, CONTIGUOUS, false) PICK(1, PAGE_TABLE, false) PICK(1, PHYSICAL, false)
-    PICK(2, CONTIGUOUS, false) PICK(2, PAGE_TABLE, false) PICK(2, PHYSICAL, false)
-    PICK(1, CONTIGUOUS, true) PICK(1, PAGE_TABLE, true) PICK(2, CONTIGUOUS, true) PICK(2, PAGE_TABLE, true)
+    const void *fn = nullptr;
+    for (const Variant &v : g_variants)
+        if (v.nqt * 16 == qtp && v.layout == layout && v.src == src && v.f16 == f16) fn = v.fn;
     if (!fn) { set_error("the fused path takes logical positions, not pool slots"); return SPECATTN_EUNSUPPORTED; }
-#undef PICK
-    {
-        // the kernels use more LDS than the default limit; raise it once per kernel (any thread may call)
-        static std::mutex mu;
-        static const void *configured[32] = {nullptr};
-        std::lock_guard<std::mutex> lock(mu);
-        bool seen = false;
-        for (const void *c : configured) seen = seen || c == fn;
-        if (!seen) {
-            if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
-                set_error("cannot reserve %zu bytes of LDS", lds);
-                return SPECATTN_EHIP;
-            }
-            for (const void *&c : configured) if (!c) { c = fn; break; }
-        }
-    }
-#ifdef SPECATTN_TIMING
-    extern long long *g_specattn_timing;      // development builds: set by the timing harness
-    plan.timing = g_specattn_timing;
-    if (!plan.timing) { set_error("timing build without a timing buffer"); return SPECATTN_EINVAL; }
-#endif
+    specattn_status st = attn_mfma_configure();
+    if (st != SPECATTN_OK) return st;
     void *kargs[] = {const_cast<AttnLaunch *>(&a), &plan};
-    if (hipLaunchKernel(fn, dim3(plan.n_wg), dim3(THREADS), kargs, lds, stream) != hipSuccess) {
+    if (hipLaunchKernel(fn, dim3(plan.n_wg), dim3(THREADS), kargs, LDS_BYTES, stream) != hipSuccess) {
         set_error("attn_mfma_kernel: launch failed");
         (void)hipGetLastError();
         return SPECATTN_EHIP;
     }
-    specattn_status st = check_launch("attn_mfma_kernel");
+    st = check_launch("attn_mfma_kernel");
     if (st != SPECATTN_OK) return st;
     hipLaunchKernelGGL(merge_partials_kernel, dim3(rows * QT), dim3(D), 0, stream, a, plan, qtp);
     return check_launch("merge_partials_kernel");
@@ -1201,7 +1136,6 @@ static specattn_status launch_batch(const AttnLaunch &a, hipStream_t stream)
     const int b_max = MAX_ROWS / a.H_kv;
     if (a.B <= b_max) return launch_chunk(a, stream);
     const int es = 2;                                       // bf16 or fp16
-    const int G = a.H_q / a.H_kv;
     for (int b0 = 0; b0 < a.B; b0 += b_max) {
         AttnLaunch c = a;
         c.B = (a.B - b0) < b_max ? (a.B - b0) : b_max;
@@ -1223,12 +1157,10 @@ static specattn_status launch_batch(const AttnLaunch &a, hipStream_t stream)
             c.k_new = static_cast<const char *>(a.k_new) + r0 * a.T * a.d * es;
             c.v_new = static_cast<const char *>(a.v_new) + r0 * a.T * a.d * es;
         }
-        if (a.probs) {
-            c.probs = a.probs + (int64_t)b0 * a.probs_stride_b;
-            c.tau = a.tau + r0;
+        if (a.kept_mask) {
+            c.kept_mask = a.kept_mask + r0 * a.blocks_per_row * (SEL_BLOCK / 32);
             c.block_counts = a.block_counts + r0 * a.blocks_per_row;
         }
-        (void)G;
         const specattn_status st = launch_chunk(c, stream);
         if (st != SPECATTN_OK) return st;
     }

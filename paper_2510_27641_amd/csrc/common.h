@@ -43,9 +43,7 @@ struct SelectLaunch {
     int blocks_per_row;
     int n_tokens;            // positions behind a row: seq_lens counts these (n_max << chunk_shift at most)
     int chunk_shift;         // log2 of the chunk size when the row holds chunk masses, else 0
-#ifdef SPECATTN_TIMING
-    long long *timing;
-#endif
+    uint32_t *kept_mask;     // may be null; [rows][blocks_per_row * SEL_BLOCK / 32]: bit i of word w = position 32 w + i kept
 };
 specattn_status launch_select(const SelectLaunch &a, hipStream_t stream);
 // Few long rows: each row split over many workgroups (thresholds only; the list comes from the mask and
@@ -100,13 +98,12 @@ struct AttnLaunch {
     float *lse;              // may be null
     void *workspace;
     size_t workspace_bytes;
-    // fused path: the list is rebuilt on chip from probs / tau / block counts
-    const float *probs;      // null = unfused
-    int64_t probs_stride_b, probs_stride_h;
     const int32_t *seq_lens;
-    const float *tau;
-    const int32_t *block_counts;
+    // fused path: the kept positions come from the selection's mask (one bit per position) and per-block counts
+    const uint32_t *kept_mask;   // null = unfused; [rows][blocks_per_row * SEL_BLOCK / 32]
+    const int32_t *block_counts; // [rows][blocks_per_row]
     int blocks_per_row;
+    int deterministic;       // 1: static tile assignment, bit-identical results from run to run
 };
 __device__ __forceinline__ int attn_group_heads(const AttnLaunch &a) { return a.g_count ? a.g_count : a.H_q / a.H_kv; }
 // query head behind head gh of this launch's share of kv head h's group
@@ -244,8 +241,13 @@ specattn_status launch_attn(const AttnLaunch &a, hipStream_t stream);
 // counts the index-list violations of an attention call into *n_bad (device memory)
 specattn_status launch_check_lists(const AttnLaunch &a, int64_t pool_slots, int32_t *n_bad, hipStream_t stream);
 
-// matrix-core variant (bf16, d = 128, G*T <= 32)
+// matrix-core variant (bf16 / fp16, d = 128)
+constexpr int ATTN_MFMA_WAVES = 8;        // waves per workgroup (one workgroup per CU: two workgroups of four waves
+                                          // do not share a CU's memory pipeline evenly - the one dispatched later
+                                          // issues its gathers only when the earlier one's waves are waiting)
+constexpr int ATTN_MFMA_MAX_ROWS = 512;   // rows per launch (larger batches run as several launches)
 bool attn_mfma_supported(const AttnLaunch &a);
+specattn_status attn_mfma_configure();    // one-time kernel attributes on the current device
 size_t attn_mfma_workspace_bytes(int rows, int G, int T);
 specattn_status launch_attn_mfma(const AttnLaunch &a, hipStream_t stream);
 

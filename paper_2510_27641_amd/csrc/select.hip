@@ -16,12 +16,6 @@
 #include "common.h"
 
 namespace specattn {
-#ifdef SPECATTN_TIMING
-long long *g_select_timing = nullptr;   // [rows][8] wall-clock stamps (development builds only)
-#define SSTAMP(k) do { if (threadIdx.x == 0 && a.timing) a.timing[blockIdx.x * 8 + (k)] = wall_clock64(); } while (0)
-#else
-#define SSTAMP(k) do { } while (0)
-#endif
 namespace {
 
 constexpr int NB1 = 2048;                     // bins of pass 1
@@ -92,6 +86,18 @@ __device__ __forceinline__ void wave_prefix(double &m, unsigned &c)
     SPECATTN_SCAN_STEP(0x142, 0xa);    // row_bcast:15 into rows 1 and 3
     SPECATTN_SCAN_STEP(0x143, 0xc);    // row_bcast:31 into rows 2 and 3
 #undef SPECATTN_SCAN_STEP
+}
+
+// Kept-position mask: every lane holds the keep flags of four consecutive positions (bit c = position 4 * lane + c
+// of a run of 256); the eight lanes that share a 32-position word combine their nibbles on the vector ALU
+// (neighbour, pair and half-row exchanges), after which each of them holds the whole word.
+__device__ __forceinline__ uint32_t mask_word(uint32_t nibble, int lane)
+{
+    int v = (int)(nibble << (4 * (lane & 7)));
+    v |= __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xf, 0xf, false);     // quad_perm [1,0,3,2]
+    v |= __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xf, 0xf, false);     // quad_perm [2,3,0,1]
+    v |= __builtin_amdgcn_update_dpp(0, v, 0x141, 0xf, 0xf, false);    // row_half_mirror: lane i <-> 7 - i of its eight
+    return (uint32_t)v;
 }
 
 // One radix pass decision.  hist[0..NB) holds the packed counters of this pass.
@@ -228,7 +234,6 @@ __global__ __launch_bounds__(THREADS, 4) void topp_select_kernel(SelectLaunch a)
     const bool aligned = (reinterpret_cast<uintptr_t>(row) & 15) == 0;
     const int n_items = (len + ITEM - 1) / ITEM;
 
-    SSTAMP(0);
     bool bad = false;
     // -0.0 is zero; negative, infinite and NaN entries make the row invalid
     auto clean = [&](uint32_t x) -> uint32_t {
@@ -318,7 +323,6 @@ __global__ __launch_bounds__(THREADS, 4) void topp_select_kernel(SelectLaunch a)
         }
     };
 
-    SSTAMP(1);
     // ---- pass 1: bits[30:20] -----------------------------------------------------------------
     for_items([&](int, uint4 u) {
         if (u.x) atomicAdd(&sh.hist[u.x >> 20], packed_entry(u.x));
@@ -328,7 +332,6 @@ __global__ __launch_bounds__(THREADS, 4) void topp_select_kernel(SelectLaunch a)
     });
     const bool any_bad = __syncthreads_or(bad ? 1 : 0) != 0;     // also orders the atomics
 
-    SSTAMP(2);
     double target = 0.0, m_above = 0.0;
     unsigned c_above = 0;
     unsigned long long bin_packed = 0;
@@ -342,11 +345,13 @@ __global__ __launch_bounds__(THREADS, 4) void topp_select_kernel(SelectLaunch a)
         }
         if (a.block_counts)
             for (int k = tid; k < a.blocks_per_row; k += THREADS) a.block_counts[(int64_t)r * a.blocks_per_row + k] = 0;
+        if (a.kept_mask)
+            for (int k = tid; k < a.blocks_per_row * (SEL_BLOCK / 32); k += THREADS)
+                a.kept_mask[(int64_t)r * a.blocks_per_row * (SEL_BLOCK / 32) + k] = 0u;
         return;
     }
     const int e_field = b1 >> 3;
 
-    SSTAMP(3);
     // A boundary bin that holds a single entry pins tau*: the bin's significand sum is that entry's
     // significand, and the exponent is the bin's.  Otherwise refine inside the bin.
     auto single_entry_bits = [&](unsigned long long packed) -> uint32_t {
@@ -383,7 +388,6 @@ __global__ __launch_bounds__(THREADS, 4) void topp_select_kernel(SelectLaunch a)
             tau_bits = (prefix << 10) | (uint32_t)b3;             // >= 1: zeros never enter a bin
         }
     }
-    SSTAMP(4);
     const unsigned kept = c_above + (unsigned)(bin_packed >> CNT_SHIFT);
 
     if (tid == 0) {
@@ -399,7 +403,16 @@ __global__ __launch_bounds__(THREADS, 4) void topp_select_kernel(SelectLaunch a)
         }
         sh.running = 0;
     }
-    if (!a.indices && !a.block_counts) return;
+    if (!a.indices && !a.block_counts && !a.kept_mask) return;
+    uint32_t *mask_out = a.kept_mask ? a.kept_mask + (int64_t)r * a.blocks_per_row * (SEL_BLOCK / 32) : nullptr;
+    const int mask_words = a.blocks_per_row * (SEL_BLOCK / 32);
+    // word (i * THREADS + tid) / 8 of the mask covers this thread's four positions of item i; the lane that
+    // holds the word's first nibble stores it
+    auto emit_mask = [&](int i, uint32_t nibble) {
+        const uint32_t word = mask_word(nibble, lane);
+        const int w = (i * THREADS + tid) >> 3;
+        if ((lane & 7) == 0 && w < mask_words) mask_out[w] = word;
+    };
 
     // ---- ordered compaction: {j : a_j >= tau*}, ascending (Algorithm 2, last step) -------------
     int32_t *out = a.indices ? a.indices + (int64_t)r * a.idx_stride : nullptr;
@@ -413,6 +426,7 @@ __global__ __launch_bounds__(THREADS, 4) void topp_select_kernel(SelectLaunch a)
         const unsigned before = __popcll(m0 & lt_mask) + __popcll(m1 & lt_mask) + __popcll(m2 & lt_mask) +
                                 __popcll(m3 & lt_mask);
         const unsigned wtot = __popcll(m0) + __popcll(m1) + __popcll(m2) + __popcll(m3);
+        if (mask_out) emit_mask(i, (f0 ? 1u : 0u) | (f1 ? 2u : 0u) | (f2 ? 4u : 0u) | (f3 ? 8u : 0u));
         const int buf = it & 1;
         if (lane == 0) sh.wave_tot[buf][wave] = wtot;
         __syncthreads();
@@ -452,7 +466,6 @@ __global__ __launch_bounds__(THREADS, 4) void topp_select_kernel(SelectLaunch a)
         if (tid == 0) sh.running = base + all;                 // wave 0: base == running
         ++it;
     };
-    SSTAMP(5);
     if (RESIDENT) {
         // All items at once: every wave counts its kept entries per item, one workgroup-wide
         // exclusive prefix over the (item, wave) counts gives every wave its place in the list.
@@ -467,6 +480,7 @@ __global__ __launch_bounds__(THREADS, 4) void topp_select_kernel(SelectLaunch a)
             const unsigned long long m0 = __ballot(f0), m1 = __ballot(f1), m2 = __ballot(f2), m3 = __ballot(f3);
             before[i] = __popcll(m0 & lt_mask) + __popcll(m1 & lt_mask) + __popcll(m2 & lt_mask) + __popcll(m3 & lt_mask);
             fl[i] = (unsigned char)((f0 ? 1 : 0) | (f1 ? 2 : 0) | (f2 ? 4 : 0) | (f3 ? 8 : 0));
+            if (mask_out) emit_mask(i, fl[i]);
             if (lane == 0) sh.wt[i * NW + wave] = __popcll(m0) + __popcll(m1) + __popcll(m2) + __popcll(m3);
         }
         __syncthreads();
@@ -535,24 +549,19 @@ __global__ __launch_bounds__(THREADS, 4) void topp_select_kernel(SelectLaunch a)
     } else {
         for_items(compact_item);
     }
-    SSTAMP(6);
     if (a.block_counts) {                                      // blocks past the row's end
         constexpr int BPI = ITEM / SEL_BLOCK;
         for (int k = (RESIDENT ? NV4 : n_items) * BPI + tid; k < a.blocks_per_row; k += THREADS)
             a.block_counts[(int64_t)r * a.blocks_per_row + k] = 0;
     }
+    if (mask_out)                                              // words past the last item
+        for (int k = (RESIDENT ? NV4 : n_items) * (ITEM / 32) + tid; k < mask_words; k += THREADS) mask_out[k] = 0u;
 }
 
 template <int THREADS, int NV4, bool RESIDENT>
 specattn_status launch_one(const SelectLaunch &a, hipStream_t stream)
 {
     const int rows = a.B * a.H_kv;
-#ifdef SPECATTN_TIMING
-    SelectLaunch b = a;
-    b.timing = g_select_timing;
-    hipLaunchKernelGGL((topp_select_kernel<THREADS, NV4, RESIDENT>), dim3(rows), dim3(THREADS), 0, stream, b);
-    return check_launch("topp_select_kernel");
-#endif
     hipLaunchKernelGGL((topp_select_kernel<THREADS, NV4, RESIDENT>), dim3(rows), dim3(THREADS), 0, stream, a);
     return check_launch("topp_select_kernel");
 }

@@ -157,9 +157,25 @@ def test_select_then_attend_end_to_end():
     assert row_rel_err(out, ref) <= TOL["bf16"]
 
 
+def test_deterministic_mode_is_bit_identical_run_to_run():
+    """With static tile assignment every sum is taken in a fixed order: repeated calls agree bit for bit (out and
+    lse), in rows owned by one workgroup as in rows split over several, and match the oracle like the default."""
+    for w in (W.llama8b_layer(seed=11, n=4096), W.llama8b_layer(seed=12, B=4, n=16384, top_p=0.9)):
+        idx, cnt = _lists_from_mask(_oracle_selection_mask(w))
+        q, k, v = kv_tensors(w)
+        a, a_lse = gpu_attention(q, k, v, dev(idx), dev(cnt), deterministic=True)
+        for _ in range(3):
+            b, b_lse = gpu_attention(q, k, v, dev(idx), dev(cnt), deterministic=True)
+            assert np.array_equal(a, b) and np.array_equal(a_lse, b_lse)
+        ref, _ = oracle_attention(w, _oracle_selection_mask(w))
+        assert row_rel_err(a, ref) <= TOL["bf16"]
+        c, _ = gpu_attention(q, k, v, dev(idx), dev(cnt))
+        assert row_rel_err(c, a) <= 1e-5
+
+
 def test_run_to_run_stability():
-    """The split over workgroups is fixed by the counts, but inside a workgroup the waves claim
-    tiles as their data arrives, so the fp32 summation order - not the result - may differ."""
+    """By default the waves of a row's workgroups claim the row's tiles as their data arrives, so the fp32
+    summation order - not the result - may differ between runs."""
     w = W.llama8b_layer(seed=11, n=4096)
     idx, cnt = _lists_from_mask(_oracle_selection_mask(w))
     q, k, v = kv_tensors(w)

@@ -23,14 +23,15 @@ def _fused(w, *, reuse=False, give_state=False, want_lse=True):
     nblk = (w.n + sa.SEL_BLOCK - 1) // sa.SEL_BLOCK
     tau = torch.zeros((R,), dtype=torch.float32, device="cuda") if (give_state or reuse) else None
     bc = torch.full((R, nblk), -1, dtype=torch.int32, device="cuda") if (give_state or reuse) else None
+    km = torch.full((R, nblk * 32), -1, dtype=torch.int32, device="cuda") if (give_state or reuse) else None
     out = torch.full((w.B, w.H_q, w.T, w.d), float("nan"), dtype=torch.float32, device="cuda")
     lse = torch.full((w.B, w.H_q, w.T), float("nan"), dtype=torch.float32, device="cuda") if want_lse else None
     if reuse:      # the threshold phase as a separate (batchable) call that writes no index list
         s0 = sa.select_args(probs, w.top_p, indices=None, counts=counts, thresholds=tau, seq_lens=sl,
-                            block_counts=bc)
+                            block_counts=bc, kept_mask=km)
         sa.specattn_topp_select(s0)
     sel = sa.select_args(probs, w.top_p, indices=None, counts=counts, thresholds=tau, seq_lens=sl,
-                         block_counts=bc, reuse_selection=reuse)
+                         block_counts=bc, kept_mask=km, reuse_selection=reuse)
     kw = dict(page_table=pt, page_size=W.PAGE_SIZE, n_max=w.n) if pt is not None else dict(n_max=w.n)
     att = sa.attn_args(q, k, v, out=out, lse=lse, seq_lens=sl, **kw)
     ws = sa.alloc_workspace(sa.specattn_workspace_size(sel, att))
@@ -39,6 +40,32 @@ def _fused(w, *, reuse=False, give_state=False, want_lse=True):
     torch.cuda.synchronize()
     return (out.cpu().numpy(), None if lse is None else lse.cpu().numpy(), counts.cpu().numpy(),
             None if tau is None else tau.cpu().numpy())
+
+
+def test_kept_mask_and_block_counts_equal_the_oracle_set():
+    """The selection state the fused call works from: one bit per position and kept counts per 1024 positions,
+    bit for bit the oracle's kept set (off the rows the oracle flags as near the boundary)."""
+    for w in (W.llama8b_layer(seed=8, B=2, n=5000, top_p=0.9), W.ragged_paged(seed=4, B=6, len_lo=50, len_hi=7000),
+              W.llama8b_layer(seed=9, B=1, n=70001, H_q=8, H_kv=2, top_p=0.95)):
+        probs = dev(w.probs)
+        R = w.B * w.H_kv
+        nblk = (w.n + sa.SEL_BLOCK - 1) // sa.SEL_BLOCK
+        counts = torch.full((R,), -7, dtype=torch.int32, device="cuda")
+        bc = torch.full((R, nblk), -1, dtype=torch.int32, device="cuda")
+        km = torch.full((R, nblk * 32), -1, dtype=torch.int32, device="cuda")
+        sl = None if w.seq_lens is None else dev(w.seq_lens.astype(np.int32))
+        sa.specattn_topp_select(sa.select_args(probs, w.top_p, indices=None, counts=counts, seq_lens=sl,
+                                               block_counts=bc, kept_mask=km))
+        torch.cuda.synchronize()
+        ref = oracle.topp_select(w.probs.reshape(-1, w.n), w.top_p, w.row_lens())
+        want = np.zeros((R, nblk * 1024), dtype=np.uint8)
+        want[:, :w.n] = ref.mask().reshape(R, w.n)
+        got = np.unpackbits(km.cpu().numpy().view(np.uint8), axis=1, bitorder="little")
+        clear = (ref.flags & oracle.ROW_NEAR_BOUNDARY) == 0
+        assert clear.any()
+        assert np.array_equal(got[clear], want[clear])
+        assert np.array_equal(bc.cpu().numpy()[clear], want.reshape(R, nblk, 1024).sum(axis=2)[clear])
+        assert np.array_equal(counts.cpu().numpy()[clear], ref.counts[clear])
 
 
 def _reference(w, which=None):
