@@ -279,8 +279,12 @@ specattn_status specattn_sparse_decode_attn_static(const specattn_attn_args *att
  * sel->kept_mask when given, else into the workspace); the attention waves turn the mask words of a tile into
  * its 32 row addresses on chip.  sel->indices is ignored; attn->indices / attn->counts are ignored
  * (sel->counts is written and used).  attn->workspace serves both phases.
- * Supported for bf16 and fp16, d = 128, contiguous or page-table layouts; there is no list, so
- * attn->indices_are_physical and chunk lists do not apply (SPECATTN_EUNSUPPORTED).
+ * The kept set stays on chip for bf16 and fp16 with d = 128 and single positions, contiguous or page-table
+ * layouts.  For what the two separate calls take beyond that - fp32, d = 64, chunk-granular selection
+ * (sel->chunk_size > 1; attn->chunk_size is ignored) - the same entry point runs the selection into a list inside
+ * attn->workspace and the attention over that list: same results, one call, nothing caller-visible in between;
+ * reuse_selection, block_counts and kept_mask are not available then (SPECATTN_EUNSUPPORTED).  There is never a
+ * caller-visible list, so attn->indices_are_physical does not apply (SPECATTN_EUNSUPPORTED; pass the page table).
  */
 specattn_status specattn_fused(const specattn_select_args *sel, const specattn_attn_args *attn,
                                void *stream);
@@ -288,6 +292,19 @@ specattn_status specattn_fused(const specattn_select_args *sel, const specattn_a
 /* Bytes of workspace needed: selection alone (attn NULL), attention alone (sel NULL), or the
    fused call (both).  0 is returned for invalid arguments. */
 size_t specattn_workspace_size(const specattn_select_args *sel, const specattn_attn_args *attn);
+
+/*
+ * CSR form of the lists a selection call wrote (Section 3.5: in the paper the selection reaches the attention
+ * kernel as a CSR structure).  indices [rows][idx_stride] and counts [rows] as written by specattn_topp_select /
+ * specattn_topp_select_union (positions, chunk numbers or pool slots alike); counts above idx_capacity count as
+ * idx_capacity, negative ones as 0.  indptr [rows + 1] (device, int64, out): indptr[0] = 0, indptr[r + 1] =
+ * indptr[r] + length of list r.  packed (device, out, optional - NULL skips it): the entries of all lists back to
+ * back, list r at packed[indptr[r] ...]; the caller sizes it for rows * idx_capacity entries or for the sum of the
+ * counts it knows.  Asynchronous on stream; SPECATTN_EINVAL / SPECATTN_ESHAPE before anything is launched.
+ */
+specattn_status specattn_lists_to_csr(const int32_t *indices, int64_t idx_stride_row, int32_t idx_capacity,
+                                      const int32_t *counts, int32_t rows, int64_t *indptr, int32_t *packed,
+                                      void *stream);
 
 /*
  * Debugging aid: checks, on the device and without touching K/V, the index lists that

@@ -22,7 +22,7 @@ F32, BF16, F16 = 0, 1, 2
 
 EXPORTS = ("specattn_topp_select", "specattn_topp_select_union", "specattn_union_workspace_size", "specattn_sparse_decode_attn", "specattn_sparse_decode_attn_static", "specattn_fused",
            "specattn_workspace_size", "specattn_layer_similarity", "specattn_layer_similarity_workspace_size",
-           "specattn_layer_map", "specattn_layer_map_workspace_size", "specattn_check_lists", "specattn_stream_read", "specattn_init", "specattn_last_error", "specattn_version")
+           "specattn_layer_map", "specattn_layer_map_workspace_size", "specattn_check_lists", "specattn_lists_to_csr", "specattn_stream_read", "specattn_init", "specattn_last_error", "specattn_version")
 
 
 class SelectArgs(C.Structure):
@@ -119,6 +119,8 @@ def load() -> C.CDLL:
         lib.specattn_check_lists.argtypes = [C.POINTER(AttnArgs), C.c_int64, C.c_void_p, C.c_void_p]
         lib.specattn_stream_read.restype = C.c_int
         lib.specattn_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+        lib.specattn_lists_to_csr.restype = C.c_int
+        lib.specattn_lists_to_csr.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
         lib.specattn_init.restype = C.c_int
         lib.specattn_init.argtypes = []
         lib.specattn_last_error.restype = C.c_char_p
@@ -337,6 +339,16 @@ def specattn_layer_map(S: torch.Tensor, f: torch.Tensor, total: torch.Tensor, wo
 
 def specattn_fused(sel: SelectArgs, attn: AttnArgs, stream=None) -> None:
     _check(load().specattn_fused(C.byref(sel), C.byref(attn), _stream(stream)))
+
+
+def specattn_lists_to_csr(indices: Optional[torch.Tensor], counts: torch.Tensor, indptr: torch.Tensor,
+                          packed: Optional[torch.Tensor] = None, capacity: Optional[int] = None, stream=None) -> None:
+    """indptr [rows + 1] int64 <- exclusive prefix of the list lengths; packed (optional) <- the lists back to back."""
+    assert counts.dtype == torch.int32 and indptr.dtype == torch.int64 and indptr.numel() == counts.numel() + 1
+    stride = 0 if indices is None else indices.stride(0)
+    cap = capacity if capacity is not None else (indices.shape[1] if indices is not None else 2 ** 31 - 1)
+    _check(load().specattn_lists_to_csr(_ptr(indices), stride, cap, _ptr(counts), counts.numel(), _ptr(indptr), _ptr(packed),
+                                        _stream(stream)))
 
 
 def specattn_init() -> None:

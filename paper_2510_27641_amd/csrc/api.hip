@@ -68,7 +68,7 @@ specattn_status check_select(const specattn_select_args *s, bool fused)
         if (s->idx_stride_row < s->idx_capacity) { set_error("idx_stride_row is smaller than idx_capacity"); return SPECATTN_ESHAPE; }
     }
     if (s->chunk_size < 0 || (s->chunk_size > 1 && (!is_pow2(s->chunk_size) || s->chunk_size > 1024))) { set_error("chunk_size must be 0, 1 or a power of two up to 1024"); return SPECATTN_ESHAPE; }
-    if (s->chunk_size > 1 && (fused || s->emit_physical || s->block_counts || s->kept_mask)) { set_error("chunk-granular selection is not available with the fused call, emit_physical, block_counts or kept_mask"); return SPECATTN_EUNSUPPORTED; }
+    if (s->chunk_size > 1 && (s->emit_physical || s->block_counts || s->kept_mask)) { set_error("chunk-granular selection is not available with emit_physical, block_counts or kept_mask"); return SPECATTN_EUNSUPPORTED; }
     if (s->bisect_iters < 0 || s->bisect_iters > 64) { set_error("bisect_iters must lie in 0..64"); return SPECATTN_ESHAPE; }
     if (s->bisect_iters > 0 && (fused || s->block_counts || s->kept_mask || s->chunk_size > 1 || !s->indices)) { set_error("the bisection mode needs an index list and is not available with the fused call, block_counts or chunks"); return SPECATTN_EUNSUPPORTED; }
     if (s->probs_stride_h < s->n_max || s->probs_stride_b < s->n_max) { set_error("probs strides are smaller than n_max"); return SPECATTN_ESHAPE; }
@@ -107,7 +107,7 @@ specattn_status check_attn(const specattn_attn_args *a, bool fused)
         if (a->kv_stride_page <= 0) { set_error("kv_stride_page must be positive"); return SPECATTN_ESHAPE; }
     }
     if (a->chunk_size < 0 || (a->chunk_size > 1 && (!is_pow2(a->chunk_size) || a->chunk_size > 1024))) { set_error("chunk_size must be 0, 1 or a power of two up to 1024"); return SPECATTN_ESHAPE; }
-    if (a->chunk_size > 1 && (fused || dense || a->indices_are_physical)) { set_error("chunk lists are not available with the fused call, dense calls or physical indices"); return SPECATTN_EUNSUPPORTED; }
+    if (a->chunk_size > 1 && !fused && (dense || a->indices_are_physical)) { set_error("chunk lists are not available with dense calls or physical indices"); return SPECATTN_EUNSUPPORTED; }
     if (a->out_lowp && !aligned(a->out_lowp, 16)) { set_error("out_lowp must be 16-byte aligned"); return SPECATTN_EALIGN; }
     if ((a->k_new == nullptr) != (a->v_new == nullptr)) { set_error("k_new and v_new must both be given or both be NULL"); return SPECATTN_EINVAL; }
     if (a->k_new && (!aligned(a->k_new, 16) || !aligned(a->v_new, 16))) { set_error("k_new and v_new must be 16-byte aligned"); return SPECATTN_EALIGN; }
@@ -129,6 +129,17 @@ specattn_status check_workspace(const void *ws, size_t have, size_t need)
     if (have < need) { set_error("workspace has %zu bytes, %zu needed", have, need); return SPECATTN_EWORKSPACE; }
     return SPECATTN_OK;
 }
+
+// The fused call keeps the kept set on chip (mask source of the matrix-core kernel) for bf16 / fp16 with d = 128
+// and single positions.  Everything else the two separate calls take (fp32, d = 64, chunk-granular selection)
+// runs as those two calls with the list in the caller's workspace instead of caller-visible memory.
+bool fused_on_chip(const specattn_select_args *s, const specattn_attn_args *a)
+{
+    AttnLaunch probe{};
+    probe.dtype = (int)a->dtype; probe.d = a->d; probe.T = a->T; probe.H_kv = a->H_kv;
+    return attn_mfma_supported(probe) && s->chunk_size <= 1;
+}
+size_t a256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 SelectLaunch make_select(const specattn_select_args *s)
 {
@@ -309,6 +320,16 @@ specattn_status specattn_sparse_decode_attn(const specattn_attn_args *attn, void
     return launch_attn(make_attn(attn), static_cast<hipStream_t>(stream));
 }
 
+specattn_status specattn_lists_to_csr(const int32_t *indices, int64_t idx_stride_row, int32_t idx_capacity,
+                                      const int32_t *counts, int32_t rows, int64_t *indptr, int32_t *packed, void *stream)
+{
+    clear_error();
+    if (!counts || !indptr || (packed && !indices)) { set_error("counts and indptr must not be NULL, and packed needs indices"); return SPECATTN_EINVAL; }
+    if (rows <= 0) { set_error("rows must be positive"); return SPECATTN_EINVAL; }
+    if (idx_capacity < 1 || (packed && idx_stride_row < idx_capacity)) { set_error("idx_capacity must be at least 1 and idx_stride_row no smaller"); return SPECATTN_ESHAPE; }
+    return launch_csr(indices, idx_stride_row, counts, rows, idx_capacity, indptr, packed, static_cast<hipStream_t>(stream));
+}
+
 specattn_status specattn_check_lists(const specattn_attn_args *attn, int64_t pool_slots, int32_t *n_bad, void *stream)
 {
     clear_error();
@@ -334,14 +355,44 @@ specattn_status specattn_fused(const specattn_select_args *sel, const specattn_a
         set_error("reuse_selection needs block_counts and kept_mask");
         return SPECATTN_EINVAL;
     }
-    AttnLaunch al = make_attn(attn);
-    if (!attn_mfma_supported(al) || attn->indices_are_physical) {
-        set_error("the fused path is built for bf16 / fp16, d = 128, logical positions");
+    if (attn->indices_are_physical) {
+        set_error("the fused call has no index list: indices_are_physical does not apply (pass the page table)");
         return SPECATTN_EUNSUPPORTED;
     }
     st = check_workspace(attn->workspace, attn->workspace_bytes, specattn_workspace_size(sel, attn));
     if (st != SPECATTN_OK) return st;
     const int rows = sel->B * sel->H_kv;
+    if (!fused_on_chip(sel, attn)) {
+        // selection into the workspace, then attention over that list
+        if (sel->reuse_selection || sel->block_counts || sel->kept_mask) {
+            set_error("reuse_selection, block_counts and kept_mask belong to the on-chip fused path (bf16 / fp16, d = 128, single positions)");
+            return SPECATTN_EUNSUPPORTED;
+        }
+        const int chunk = sel->chunk_size > 1 ? sel->chunk_size : 1;
+        const int cap = (sel->n_max + chunk - 1) / chunk;
+        char *ws = static_cast<char *>(attn->workspace);
+        const size_t attn_bytes = attn_workspace_bytes(rows, attn->H_q / attn->H_kv, attn->T, attn->d, attn->n_max);
+        specattn_select_args s2 = *sel;
+        s2.indices = reinterpret_cast<int32_t *>(ws + attn_bytes);
+        s2.idx_stride_row = cap;
+        s2.idx_capacity = cap;
+        s2.emit_physical = 0;
+        const size_t list_bytes = a256((size_t)rows * cap * sizeof(int32_t));
+        const size_t sel_bytes = specattn_workspace_size(&s2, nullptr);
+        st = specattn_topp_select(&s2, sel_bytes ? ws + attn_bytes + list_bytes : nullptr, sel_bytes, stream);
+        if (st != SPECATTN_OK) return st;
+        specattn_attn_args a2 = *attn;
+        a2.indices = s2.indices;
+        a2.idx_stride_row = cap;
+        a2.idx_capacity = cap;
+        a2.counts = sel->counts;
+        a2.chunk_size = sel->chunk_size;
+        a2.indices_are_physical = 0;
+        a2.seq_lens = sel->seq_lens;
+        a2.workspace_bytes = attn_bytes;
+        return specattn_sparse_decode_attn(&a2, stream);
+    }
+    AttnLaunch al = make_attn(attn);
     const int blocks = (sel->n_max + SEL_BLOCK - 1) / SEL_BLOCK;
     // workspace: [attention partials][block counts: rows * blocks ints][kept mask: rows * blocks * 32 words]
     char *extra = static_cast<char *>(attn->workspace) +
@@ -396,6 +447,15 @@ size_t specattn_workspace_size(const specattn_select_args *sel, const specattn_a
     const int cap = (sel || dense) ? attn->n_max : attn->idx_capacity * (attn->chunk_size > 1 ? attn->chunk_size : 1);
     if (cap <= 0) return 0;
     size_t bytes = attn_workspace_bytes(rows, attn->H_q / attn->H_kv, attn->T, attn->d, cap);
+    if (sel && !fused_on_chip(sel, attn)) {           // fused by way of a list in the workspace
+        if (sel->n_max <= 0) return 0;
+        const int chunk = sel->chunk_size > 1 ? sel->chunk_size : 1;
+        const int lcap = (sel->n_max + chunk - 1) / chunk;
+        specattn_select_args s2 = *sel;
+        s2.indices = reinterpret_cast<int32_t *>(0x1000);      // (only tested for NULL by the size query)
+        bytes = a256(bytes) + a256((size_t)rows * lcap * sizeof(int32_t)) + specattn_workspace_size(&s2, nullptr);
+        return bytes;
+    }
     if (sel) {                                        // fused: room for the block counts and the kept mask
         const size_t blocks = ((size_t)attn->n_max + SEL_BLOCK - 1) / SEL_BLOCK;
         bytes += ((size_t)rows * blocks * sizeof(int32_t) + 255) & ~(size_t)255;

@@ -241,6 +241,10 @@ specattn_status launch_attn(const AttnLaunch &a, hipStream_t stream);
 // counts the index-list violations of an attention call into *n_bad (device memory)
 specattn_status launch_check_lists(const AttnLaunch &a, int64_t pool_slots, int32_t *n_bad, hipStream_t stream);
 
+// CSR row pointers (and, optionally, the packed entries) of padded index lists
+specattn_status launch_csr(const int32_t *indices, int64_t idx_stride, const int32_t *counts, int rows, int capacity,
+                           int64_t *indptr, int32_t *packed, hipStream_t stream);
+
 // matrix-core variant (bf16 / fp16, d = 128)
 constexpr int ATTN_MFMA_WAVES = 8;        // waves per workgroup (one workgroup per CU: two workgroups of four waves
                                           // do not share a CU's memory pipeline evenly - the one dispatched later

@@ -471,16 +471,20 @@ __global__ __launch_bounds__(THREADS, 4) void topp_select_kernel(SelectLaunch a)
         // exclusive prefix over the (item, wave) counts gives every wave its place in the list.
         constexpr int NE = NV4 * NW;
         static_assert(NE <= 256 && NE <= THREADS, "prefix table too small");
-        unsigned before[NV4];
-        unsigned char fl[NV4];
+        // per item: the keep flags of the thread's four entries (4 bits) and the number of kept entries of the
+        // lanes before it (at most 252), two items to a register
+        uint32_t note[(NV4 + 1) / 2];
+#pragma unroll
+        for (int i = 0; i < (NV4 + 1) / 2; ++i) note[i] = 0u;
 #pragma unroll
         for (int i = 0; i < NV4; ++i) {
             const uint4 u = data[i];
             const bool f0 = u.x >= tau_bits, f1 = u.y >= tau_bits, f2 = u.z >= tau_bits, f3 = u.w >= tau_bits;
             const unsigned long long m0 = __ballot(f0), m1 = __ballot(f1), m2 = __ballot(f2), m3 = __ballot(f3);
-            before[i] = __popcll(m0 & lt_mask) + __popcll(m1 & lt_mask) + __popcll(m2 & lt_mask) + __popcll(m3 & lt_mask);
-            fl[i] = (unsigned char)((f0 ? 1 : 0) | (f1 ? 2 : 0) | (f2 ? 4 : 0) | (f3 ? 8 : 0));
-            if (mask_out) emit_mask(i, fl[i]);
+            const unsigned before = __popcll(m0 & lt_mask) + __popcll(m1 & lt_mask) + __popcll(m2 & lt_mask) + __popcll(m3 & lt_mask);
+            const unsigned fl = (f0 ? 1u : 0u) | (f1 ? 2u : 0u) | (f2 ? 4u : 0u) | (f3 ? 8u : 0u);
+            note[i >> 1] |= (before | (fl << 9)) << (16 * (i & 1));
+            if (mask_out) emit_mask(i, fl);
             if (lane == 0) sh.wt[i * NW + wave] = __popcll(m0) + __popcll(m1) + __popcll(m2) + __popcll(m3);
         }
         __syncthreads();
@@ -493,56 +497,51 @@ __global__ __launch_bounds__(THREADS, 4) void topp_select_kernel(SelectLaunch a)
                 a.block_counts[(int64_t)r * a.blocks_per_row + blk] = (int32_t)c;
             }
         }
-        unsigned v = tid < NE ? sh.wt[tid] : 0u, inc = v;
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            const unsigned o = __shfl_up(inc, off, 64);
-            if (lane >= off) inc += o;
-        }
-        if (lane == 63) sh.wave_c[wave] = inc;
-        __syncthreads();
-        if (tid < NE) {
-            unsigned base = 0;
-            for (int w = 0; w < wave; ++w) base += sh.wave_c[w];
-            sh.wt[tid] = base + inc - v;
-        }
-        __syncthreads();
         if (out) {
-            // Per item the wave's kept entries are consecutive in the list: gather them in LDS in
-            // list order, then store them with whole-wave contiguous writes.  Several items go through
-            // buffers of their own at a time, so that the stores and reads of one item do not each wait
-            // for the round trip of the item before (a wave's LDS accesses are served in order).
-            constexpr int SLOTS = 32 / NW;
-            int32_t *wb = sh.wbuf[wave * SLOTS];
+            unsigned v = tid < NE ? sh.wt[tid] : 0u, inc = v;
 #pragma unroll
-            for (int i0 = 0; i0 < NV4; i0 += SLOTS) {
+            for (int off = 1; off < 64; off <<= 1) {
+                const unsigned o = __shfl_up(inc, off, 64);
+                if (lane >= off) inc += o;
+            }
+            if (lane == 63) sh.wave_c[wave] = inc;
+            __syncthreads();
+            if (tid < NE) {
+                unsigned base = 0;
+                for (int w = 0; w < wave; ++w) base += sh.wave_c[w];
+                sh.wt[tid] = base + inc - v;
+            }
+            __syncthreads();
+            // The row's list is put together in LDS, in list order (every thread knows the rank of each of its
+            // kept entries), and goes out with contiguous stores over the whole workgroup: whole cache lines,
+            // whatever the kept counts of the single waves are.  Lists longer than the buffer take several rounds.
+            constexpr unsigned CH = 32 * 256;
+            int32_t *stage = &sh.wbuf[0][0];
+            const unsigned cap = kept < (unsigned)a.idx_capacity ? kept : (unsigned)a.idx_capacity;
+            for (unsigned c0 = 0; c0 < cap; c0 += CH) {
+                if (c0) __syncthreads();                               // the round before has been read out
 #pragma unroll
-                for (int sl = 0; sl < SLOTS; ++sl) {
-                    const int i = i0 + sl;
-                    if (i < NV4 && i < n_items) {
-                        unsigned o = before[i];
+                for (int i = 0; i < NV4; ++i) {
+                    const unsigned nt = (note[i >> 1] >> (16 * (i & 1))) & 0xffffu;
+                    const unsigned before = nt & 0x1ffu, fl = nt >> 9;
+                    if (fl) {
+                        unsigned o = sh.wt[i * NW + wave] + before - c0;                  // (wraps around below c0: not in this round)
                         const int p = (i * THREADS + tid) * 4;
 #pragma unroll
                         for (int c = 0; c < 4; ++c) {
-                            if (fl[i] & (1 << c)) {
-                                const int pos = p + c;
-                                int32_t val = pos;
-                                if (ptab) val = (ptab[pos >> a.page_shift] << a.page_shift) | (pos & ((1 << a.page_shift) - 1));
-                                wb[sl * 256 + o++] = val;
+                            if (fl & (1u << c)) {
+                                if (o < CH) stage[o] = p + c;
+                                ++o;
                             }
                         }
                     }
                 }
-#pragma unroll
-                for (int sl = 0; sl < SLOTS; ++sl) {
-                    const int i = i0 + sl;
-                    if (i < NV4 && i < n_items) {
-                        const unsigned base = sh.wt[i * NW + wave];
-                        const unsigned next = (i * NW + wave + 1 < NE) ? sh.wt[i * NW + wave + 1] : kept;
-                        const unsigned cnt_w = next - base;            // wave-uniform, at most 256
-                        for (unsigned k = lane; k < cnt_w; k += 64)
-                            if (base + k < (unsigned)a.idx_capacity) out[base + k] = wb[sl * 256 + k];
-                    }
+                __syncthreads();
+                const unsigned nround = (cap - c0) < CH ? (cap - c0) : CH;
+                for (unsigned k = tid; k < nround; k += THREADS) {
+                    int32_t val = stage[k];
+                    if (ptab) val = (ptab[val >> a.page_shift] << a.page_shift) | (val & ((1 << a.page_shift) - 1));
+                    out[c0 + k] = val;
                 }
             }
         }

@@ -225,3 +225,41 @@ def test_layer_mapping_argument_errors_and_sizes():
     assert lib.specattn_layer_map(0x1000, 2, 2, 0x2000, 0x3000, None, 0, None) == sa.EWORKSPACE
     assert lib.specattn_layer_map(0x1000, 2, 2, 0x2000, 0x3000, 0x10000, 8, None) == sa.EWORKSPACE
     assert sa.last_error() != ""
+
+
+def test_large_query_groups_need_the_matrix_core_route():
+    """More than 64 query rows per kv head only fit the matrix-core kernel, which also bounds H_kv (512 rows per
+    launch): anything else must be refused on the host, not run on the portable kernel whose tables hold 64 rows."""
+    lib = sa.load()
+    H_kv, T, d = 1024, 5, 128
+    a = _attn(B=1, H_q=16 * H_kv, H_kv=H_kv, q_stride_b=16 * H_kv * T * d, q_stride_h=T * d,
+              kv_stride_b=H_kv * 4096 * d, workspace=0x10000, workspace_bytes=1 << 40)
+    assert lib.specattn_sparse_decode_attn(C.byref(a), None) == sa.ESHAPE
+    assert "query rows" in sa.last_error()
+
+
+def test_csr_argument_errors_and_static_entry_checks():
+    lib = sa.load()
+    assert lib.specattn_lists_to_csr(0x1000, 64, 64, None, 4, 0x2000, None, None) == sa.EINVAL       # no counts
+    assert lib.specattn_lists_to_csr(None, 64, 64, 0x1000, 4, 0x2000, 0x3000, None) == sa.EINVAL     # packed without lists
+    assert lib.specattn_lists_to_csr(0x1000, 8, 64, 0x1000, 4, 0x2000, 0x3000, None) == sa.ESHAPE    # stride < capacity
+    assert lib.specattn_lists_to_csr(0x1000, 64, 64, 0x1000, 0, 0x2000, None, None) == sa.EINVAL     # no rows
+    # the entry point without a workspace validates like the one with, before it touches the device
+    assert lib.specattn_sparse_decode_attn_static(C.byref(_attn(q=None)), None) == sa.EINVAL
+    assert lib.specattn_sparse_decode_attn_static(C.byref(_attn(d=96)), None) == sa.ESHAPE
+
+
+def test_fused_entry_refuses_what_has_no_meaning_without_a_list():
+    lib = sa.load()
+    ws = dict(workspace=0x10000, workspace_bytes=1 << 40)
+    s = _sel(B=2, H_kv=8, n_max=4096, probs_stride_b=8 * 4096, probs_stride_h=4096, indices=None)
+    assert lib.specattn_fused(C.byref(s), C.byref(_attn(indices_are_physical=1, page_size=16, kv_stride_page=8 * 16 * 128, **ws)), None) == sa.EUNSUPPORTED
+    s2 = _sel(B=2, H_kv=8, n_max=4096, probs_stride_b=8 * 4096, probs_stride_h=4096, indices=None, reuse_selection=1)
+    assert lib.specattn_fused(C.byref(s2), C.byref(_attn(**ws)), None) == sa.EINVAL                  # nothing to reuse
+    s3 = _sel(B=2, H_kv=8, n_max=4096, probs_stride_b=8 * 4096, probs_stride_h=4096, indices=None, chunk_size=16, block_counts=0x7000)
+    assert lib.specattn_fused(C.byref(s3), C.byref(_attn(**ws)), None) == sa.EUNSUPPORTED
+    # sizes: the on-chip route adds block counts + mask, the list route adds the list
+    on_chip = sa.specattn_workspace_size(s, _attn())
+    assert on_chip >= sa.specattn_workspace_size(None, _attn()) + 2 * 8 * 4 * 4 + 2 * 8 * 4 * 32 * 4
+    s4 = _sel(B=2, H_kv=8, n_max=4096, probs_stride_b=8 * 4096, probs_stride_h=4096, indices=None, chunk_size=16)
+    assert sa.specattn_workspace_size(s4, _attn()) >= sa.specattn_workspace_size(None, _attn()) + 2 * 8 * 256 * 4

@@ -142,8 +142,52 @@ def test_top_p_one_selects_everything():
     assert row_rel_err(out, o) <= TOL["bf16"]
 
 
-def test_unsupported_shapes_fail_loudly():
+def test_tiny_fp32_workload_through_the_fused_entry():
+    """fp32, d = 64: the fused entry runs the selection into its workspace and attends over that list."""
     w = W.tiny_f32()
+    out, lse, counts, _ = _fused(w)
+    ref, o, l = _reference(w)
+    _check_counts(counts, ref)
+    assert row_rel_err(out, o) <= TOL["f32"]
+    assert np.abs(lse - l).max() <= 1e-4
+    with pytest.raises(sa.SpecAttnError) as e:          # the on-chip selection state does not exist on this route
+        _fused(w, give_state=True)
+    assert e.value.status == sa.EUNSUPPORTED
+
+
+@pytest.mark.parametrize("chunk", [16, 64])
+def test_chunk_granular_selection_through_the_fused_entry(chunk):
+    """sel.chunk_size > 1: top-p over chunk masses, attention over every position of the kept chunks."""
+    w = W.llama8b_layer(seed=13, B=2, n=5000, top_p=0.9)
+    q, k, v = kv_tensors(w)
+    probs = dev(w.probs)
+    R = w.B * w.H_kv
+    counts = torch.full((R,), -7, dtype=torch.int32, device="cuda")
+    out = torch.full((w.B, w.H_q, w.T, w.d), float("nan"), dtype=torch.float32, device="cuda")
+    sel = sa.select_args(probs, w.top_p, indices=None, counts=counts, chunk_size=chunk)
+    att = sa.attn_args(q, k, v, out=out, n_max=w.n)
+    ws = sa.alloc_workspace(sa.specattn_workspace_size(sel, att))
+    att.workspace, att.workspace_bytes = ws.data_ptr(), ws.numel()
+    sa.specattn_fused(sel, att)
+    torch.cuda.synchronize()
+    ref = oracle.topp_select_chunks(w.probs.reshape(-1, w.n), w.top_p, chunk)
+    clear = (ref.flags & oracle.ROW_NEAR_BOUNDARY) == 0
+    assert np.array_equal(counts.cpu().numpy()[clear], ref.counts[clear])
+    mask = oracle.chunk_token_mask(ref, chunk, w.n, np.full(R, w.n, dtype=np.int32)).reshape(w.B, w.H_kv, w.n)
+    o, _ = oracle_attention(w, mask)
+    assert row_rel_err(out.cpu().numpy(), o) <= TOL["bf16"]
+
+
+def test_physical_indices_do_not_apply_to_the_fused_entry():
+    w = W.ragged_paged(seed=4, B=2, len_lo=50, len_hi=900)
+    q, k, v = kv_tensors(w)
+    probs = dev(w.probs)
+    counts = torch.zeros((w.B * w.H_kv,), dtype=torch.int32, device="cuda")
+    out = torch.zeros((w.B, w.H_q, w.T, w.d), dtype=torch.float32, device="cuda")
+    sel = sa.select_args(probs, w.top_p, indices=None, counts=counts, seq_lens=dev(w.seq_lens.astype(np.int32)))
+    att = sa.attn_args(q, k, v, out=out, page_size=W.PAGE_SIZE, n_max=w.n, indices_are_physical=True)
+    ws = sa.alloc_workspace(1 << 24)
+    att.workspace, att.workspace_bytes = ws.data_ptr(), ws.numel()
     with pytest.raises(sa.SpecAttnError) as e:
-        _fused(w)
+        sa.specattn_fused(sel, att)
     assert e.value.status == sa.EUNSUPPORTED
