@@ -38,6 +38,7 @@ def parse():
     ap.add_argument("--context", type=int, default=32768)
     ap.add_argument("--top-p", type=float, default=0.9)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-configs", action="store_true", help="skip the bounded summary of the other configurations")
     ap.add_argument("--path", choices=["both", "unfused", "fused"], default="both")
     ap.add_argument("--workload", choices=["headline", "side"], default="headline",
                     help="headline: the 32-layer verify step (one JSON line).  side: the other workloads and calls "
@@ -203,6 +204,99 @@ def side_workloads(torch, sa, W):
         emit(f"union over {steps} draft steps x {hd // H_kv} draft heads per kv head", member_rows=B * hd * steps, n=n,
              probs_MB=round(B * hd * steps * n * 4 / 1e6, 1), union_us=round(t, 1),
              union_fraction=round(float(cu.float().mean().item()) / n, 4))
+
+
+def compare_lists(ref, idx, cnt, tau):
+    """Rows the oracle flags as near the boundary, and rows whose device result (count, tau*, list) differs from the
+    oracle's: (flagged, mismatched among the flagged, mismatched among the others)."""
+    NEAR = 2
+    flagged = mism_flagged = mism_clear = 0
+    for r in range(ref.counts.size):
+        c = int(ref.counts[r])
+        same = int(cnt[r]) == c and tau[r] == ref.tau[r] and np.array_equal(idx[r, :c], ref.indices[r, :c])
+        if ref.flags[r] & NEAR:
+            flagged += 1
+            mism_flagged += 0 if same else 1
+        else:
+            mism_clear += 0 if same else 1
+    return flagged, mism_flagged, mism_clear
+
+
+def other_configs(torch, sa, W, oracle):
+    """The workload's other configurations, bounded so that the default run stays short: selection and attention
+    times (HIP events, mean of 10 after 2 warm-up calls), kept fraction, and the device lists against the oracle's."""
+    H_q, H_kv, T, d = 32, 8, 5, 128
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(7)
+
+    def timed(fn, reps=10, warm=2):
+        for _ in range(warm):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps * 1e3          # us
+
+    def pair(w, dtype, *, paged=False, copies=1, physical=False):
+        B, H, n = w.probs.shape
+        R = B * H
+        p = torch.from_numpy(w.probs).cuda()
+        sl = None if w.seq_lens is None else torch.from_numpy(w.seq_lens.astype(np.int32)).cuda()
+        pt = torch.from_numpy(w.page_table).cuda() if paged else None
+        idx = torch.zeros((R, n), dtype=torch.int32, device="cuda")
+        cnt = torch.zeros(R, dtype=torch.int32, device="cuda")
+        tau = torch.zeros(R, dtype=torch.float32, device="cuda")
+        s = sa.select_args(p, w.top_p, indices=idx, counts=cnt, thresholds=tau, seq_lens=sl)
+        need = sa.specattn_workspace_size(s, None)
+        ws_s = sa.alloc_workspace(need) if need else None
+        t_sel = timed(lambda: sa.specattn_topp_select(s, ws_s))
+        ref = oracle.topp_select(w.probs.reshape(R, n), w.top_p, None if w.seq_lens is None else np.repeat(w.seq_lens, H))
+        flagged, mf, mc = compare_lists(ref, idx.cpu().numpy(), cnt.cpu().numpy(), tau.cpu().numpy())
+        H_qw = w.H_q
+        out = torch.empty((B, H_qw, w.T, w.d), dtype=torch.float32, device="cuda")
+        calls = []
+        for _ in range(copies):
+            q = torch.randn((B, H_qw, w.T, w.d), generator=gen, device="cuda").to(dtype)
+            shape = (w.n_pool_pages, H, W.PAGE_SIZE, w.d) if paged else (B, H, n, w.d)
+            k = torch.randn(shape, generator=gen, device="cuda", dtype=torch.float32).to(dtype) if dtype == torch.float32 else \
+                torch.empty(shape, device="cuda", dtype=dtype).normal_(generator=gen)
+            v = torch.empty(shape, device="cuda", dtype=dtype).normal_(generator=gen)
+            extra = dict(page_table=pt, page_size=W.PAGE_SIZE, n_max=n) if paged else {}
+            a = sa.attn_args(q, k, v, out=out, indices=idx, counts=cnt, **extra)
+            ws = sa.alloc_workspace(sa.specattn_workspace_size(None, a))
+            a.workspace, a.workspace_bytes = ws.data_ptr(), ws.numel()
+            calls.append((a, ws, q, k, v))
+        state = {"i": 0}
+
+        def attend():
+            sa.specattn_sparse_decode_attn(calls[state["i"] % copies][0])
+            state["i"] += 1
+        t_att = timed(attend)
+        kept = int(cnt.sum().item())
+        total = int(w.seq_lens.sum()) * H if w.seq_lens is not None else R * n
+        row_bytes = 2 * w.d * (4 if dtype == torch.float32 else 2)
+        return dict(rows=R, n=n, top_p=w.top_p, kept_fraction=round(kept / total, 5), select_us=round(t_sel, 1),
+                    attention_us=round(t_att, 1), kept_kv_MB=round(kept * row_bytes / 1e6, 2),
+                    attention_GBps=round(kept * row_bytes / t_att / 1e3, 1),
+                    pct_hbm_peak=round(kept * row_bytes / t_att / 1e3 / HBM_PEAK_GBPS * 100, 2),
+                    flagged_rows=flagged, mismatched_flagged_rows=mf, mismatched_rows=mc)
+
+    res = {}
+    res["config1 tiny fp32 (B=1, H=8, n=1024, d=64, p=0.9)"] = pair(W.tiny_f32(), torch.float32)
+    res["config2 llama3-8b layer (B=1, n=8192, p=0.95; 11 MB kept: cache-resident)"] = \
+        pair(W.llama8b_layer(seed=1, with_kv=False), torch.bfloat16, copies=4)
+    for clip in (None, 8.0):
+        for tp in (0.8, 0.9, 0.95, 0.99):
+            w = W.long_context(seed=3, B=4, n=131072, top_p=tp, logit_clip=clip, with_kv=False)
+            res[f"config4 long context (B=4, n=131072), logits {'literal' if clip is None else 'clipped to +-8'}, p={tp}"] = \
+                pair(w, torch.bfloat16)
+    w = W.ragged_paged(seed=0, B=64, with_kv=False)
+    res["config5 ragged paged (B=64, lens 4096..65536, 16-token pages, p=0.95)"] = pair(w, torch.bfloat16, paged=True)
+    return res
 
 
 def main():
@@ -420,12 +514,24 @@ def main():
     best_name = [k for k in ("fused", "unfused") if results.get(k) == best][0]
     value = sel_bytes_step / (best * 1e-3) / 1e9
 
-    traffic = None                       # HBM bytes per launch from rocprofv3 --pmc, if a summary is committed
+    # HBM bytes per launch from rocprofv3 --pmc: taken from the committed summary only if that summary was made
+    # from the kernel sources this run is built from (it records their hash); otherwise null
+    traffic, traffic_source = None, None
     pmc = os.path.join(ROOT, "profiles", "sparse_decode_attn_config3_pmc.txt")
     if os.path.exists(pmc):
+        import hashlib
+        src = os.path.join(ROOT, "paper_2510_27641_amd", "csrc", "attn_mfma.hip")
+        digest = hashlib.sha256(open(src, "rb").read()).hexdigest()[:16]
+        found, val = None, None
         for ln in open(pmc):
             if ln.startswith("traffic_bytes_per_launch:"):
-                traffic = float(ln.split(":")[1])
+                val = float(ln.split(":")[1])
+            if ln.startswith("attn_mfma_hip_sha256_16:"):
+                found = ln.split(":")[1].strip()
+        if val is not None and found == digest:
+            traffic, traffic_source = val, "profiles/sparse_decode_attn_config3_pmc.txt (same kernel source, sha256/16 " + digest + ")"
+        else:
+            traffic_source = "profiles/sparse_decode_attn_config3_pmc.txt was made from other kernel sources: not quoted"
     line = {
         "metric": "selected_kv_GBps_topp_select_plus_sparse_decode_attn_32k",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -455,11 +561,18 @@ def main():
                                              "unfused_GBps": round(sel_bytes_step / (ms_step_b * 1e-3) / 1e9, 1),
                                              "fused_ms": None if ms_step_bf is None else round(ms_step_bf, 4),
                                              "fused_GBps": None if ms_step_bf is None else round(sel_bytes_step / (ms_step_bf * 1e-3) / 1e9, 1)}},
-        "roofline": {"bound": "hbm", "kernel": "specattn_sparse_decode_attn = attn_mfma_kernel + merge_partials_kernel, one layer",
+        "roofline": {"bound": "hbm", "kernel": "specattn_sparse_decode_attn = attn_mfma_kernel + merge_partials_kernel, one layer (HIP events around the layer loop)",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic, "traffic_source": traffic_source,
                      "algorithmic_bytes_per_launch": int(bytes_launch), "launch_us": round(ms_attn * 1e3, 2),
                      "frac_of_stream_read": round(achieved / stream_gbps, 4)},
+        "roofline_select": {"bound": "hbm", "kernel": "specattn_topp_select = topp_select_kernel, the rows of all layers in one launch",
+                            "algorithmic_bytes_per_launch": int(L * R * n * 4 + float(cnt.sum()) * 4),
+                            "achieved": round((L * R * n * 4 + float(cnt.sum()) * 4) / (ms_sel * 1e-3) / 1e9, 1),
+                            "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                            "frac": round((L * R * n * 4 + float(cnt.sum()) * 4) / (ms_sel * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                            "launch_us": round(ms_sel * 1e3, 1),
+                            "what": "4 B per context position read once + 4 B per kept position written"},
         "input_generation_s": round(t_gen, 1),
     }
     if not fused_ok:
@@ -474,6 +587,10 @@ def main():
         t_sel = t_att = 0.0
         samp_bytes = 0.0
         worst = 0.0
+        flagged = mism_flagged = mism_clear = 0
+        sa.specattn_topp_select(sel_all)
+        torch.cuda.synchronize()
+        idx_h, cnt_h, tau_h = idx.cpu().numpy(), counts.cpu().numpy(), tau.cpu().numpy()
         for layer in range(L):
             if t_sel + t_att > budget_s:
                 break
@@ -482,6 +599,9 @@ def main():
             t0 = time.time()
             ref = oracle.topp_select(rows_s, top_p)
             t_sel += time.time() - t0
+            rs = slice(layer * R, (layer + 1) * R)
+            f_, mf_, mc_ = compare_lists(ref, idx_h[rs], cnt_h[rs], tau_h[rs])
+            flagged += f_; mism_flagged += mf_; mism_clear += mc_
             mask = ref.mask().reshape(B, H_kv, n)
             q0 = qs[layer].view(torch.int16).cpu().numpy().view(np.uint16)
             k0 = ks[layer].view(torch.int16).cpu().numpy().view(np.uint16)
@@ -500,6 +620,13 @@ def main():
                       f"oracle selection {t_sel:.2f} s + masked dense attention {t_att:.2f} s wall on {cores} threads; "
                       f"rate = kept K/V bytes of the sample / that time"}
         line["full_size_check_row_rel_err"] = worst
+        line["selection_check"] = {"rows_checked": n_samp * R, "flagged_rows": flagged,
+                                   "mismatched_flagged_rows": mism_flagged, "mismatched_rows": mism_clear,
+                                   "what": "device lists, counts and tau* of the checked layers against the oracle's: rows whose "
+                                           "kept or strictly-above mass lies within 1e-6 of the target are flagged and counted; "
+                                           "mismatches are counted separately among them and among the others"}
+        if not args.no_other_configs:
+            line["other_configs"] = other_configs(torch, sa, W, oracle)
 
     print(json.dumps(line))
 

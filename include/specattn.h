@@ -121,7 +121,9 @@ typedef struct specattn_select_args {
  *                  (q[b][h_q][t] . k[b][h_kv][j]) * sm_scale, times v.
  * All T queries of all G query heads of a kv head share that head's list.
  * A row with count 0 gives out = 0 and lse = -inf.  Accumulation is fp32;
- * `out` is fp32 whatever the input dtype.
+ * `out` is fp32 whatever the input dtype.  Every sum is taken in a fixed order
+ * (tiles are assigned to waves and workgroups by the counts alone), so repeated
+ * calls on the same inputs give bit-identical out and lse.
  *
  * Shapes: bf16 and fp16 with d = 128 run on the matrix cores for any G = H_q / H_kv (up to 32 query rows
  * G*T per pass; larger groups are taken in equal shares of heads, each streaming the kept K/V
@@ -174,12 +176,6 @@ typedef struct specattn_attn_args {
     /* optional: a second copy of the output in the dtype of q/k/v (round to nearest even), [B][H_q][T][d]
        contiguous, 16-byte aligned - what a following projection in that dtype reads.  NULL = not written. */
     void *out_lowp;
-
-    /* 0: the waves of a row's workgroups claim the row's tiles at run time (fastest; the fp32 summation order,
-       and with it the last bits of out and lse, can differ from run to run).  1: tiles are assigned statically,
-       every sum is taken in a fixed order and repeated calls on the same inputs give bit-identical outputs
-       (bf16 / fp16 with d = 128; the fp32 / d = 64 route is always deterministic). */
-    int32_t deterministic;
 } specattn_attn_args;
 
 /*

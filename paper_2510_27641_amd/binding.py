@@ -57,7 +57,6 @@ class AttnArgs(C.Structure):
         ("k_new", C.c_void_p), ("v_new", C.c_void_p),
         ("chunk_size", C.c_int32),
         ("out_lowp", C.c_void_p),
-        ("deterministic", C.c_int32),
     ]
 
 
@@ -231,7 +230,7 @@ def attn_args(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, *, out: torch.T
               page_table: Optional[torch.Tensor] = None, page_size: int = 0,
               indices_are_physical: bool = False, seq_lens: Optional[torch.Tensor] = None,
               k_new: Optional[torch.Tensor] = None, v_new: Optional[torch.Tensor] = None,
-              chunk_size: int = 0, out_lowp: Optional[torch.Tensor] = None, deterministic: bool = False) -> AttnArgs:
+              chunk_size: int = 0, out_lowp: Optional[torch.Tensor] = None) -> AttnArgs:
     """q [B,H_q,T,d]; contiguous k/v [B,H_kv,n,d]; paged k/v pool [pages,H_kv,page_size,d];
     k_new/v_new [B,H_kv,T,d] contiguous (the new tokens behind the cache), optional."""
     assert q.dim() == 4 and k.dim() == 4 and k.shape == v.shape and k.stride() == v.stride()
@@ -269,7 +268,6 @@ def attn_args(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, *, out: torch.T
     a.out = out.data_ptr()
     a.lse = None if lse is None else lse.data_ptr()
     a.chunk_size = chunk_size
-    a.deterministic = int(deterministic)
     if out_lowp is not None:
         assert out_lowp.dtype == q.dtype and out_lowp.is_contiguous() and tuple(out_lowp.shape) == (B, H_q, T, d)
         a.out_lowp = out_lowp.data_ptr()

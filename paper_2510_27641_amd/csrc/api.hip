@@ -198,7 +198,6 @@ AttnLaunch make_attn(const specattn_attn_args *a)
     l.workspace = a->workspace;
     l.workspace_bytes = a->workspace_bytes;
     l.seq_lens = a->seq_lens;
-    l.deterministic = a->deterministic ? 1 : 0;
     return l;
 }
 

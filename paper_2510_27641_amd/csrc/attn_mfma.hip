@@ -7,15 +7,15 @@
 // per CU), so the split is balanced by the *kept* count whatever the per-row counts are.  A fixed
 // permutation of the workgroup numbers puts the owners of consecutive shares on different XCDs.  A share
 // that crosses row boundaries yields one partial (m, l, o) per (row, workgroup); partial (r, w) lives in
-// slot w + r.  merge_partials_kernel combines a row's partials.  Inside a share the waves claim tiles from
-// an LDS counter as their data arrives (a wave that gets its data later simply takes fewer); a
-// deterministic mode hands tile k of a share to wave k mod 8 instead, which fixes the summation order bit
-// by bit.
-// Measured and dropped: tiles of a row claimed by all of its workgroups from a counter in memory (a
-// device-scope atomic takes about as long as a tile under load - 5 us - and claims made that far ahead leave
-// as much unbalanced work at the end as they remove), and the merge folded into this kernel (last arriver
-// per row: write-through stores, an atomic and device-scope loads in a row cost 14 us after the last tile,
-// against 8 us for the wrap-up plus the second launch).
+// slot w + r.  merge_partials_kernel combines a row's partials, in workgroup order.  Inside a share tile k goes
+// to wave k mod 8, so every sum is taken in a fixed order and the outputs are bit-identical from run to run.
+// Measured and dropped: waves claiming the tiles of a share from an LDS counter as their data arrives (no
+// faster on any workload, 1.3 us slower on the 32K layer, and it gives the fixed summation order up); tiles of
+// a row claimed by all of its workgroups from a counter in memory (a device-scope atomic takes about as long
+// as a tile under load - 5 us - and claims made that far ahead leave as much unbalanced work at the end as they
+// remove); the merge folded into this kernel (last arriver per row: write-through stores, an atomic and
+// device-scope loads in a row cost 14 us after the last tile, against 8 us for the wrap-up plus the second
+// launch).
 //
 // Data path per wave and tile: the 32 gathered K rows and the 32 V rows (256 B each) go from HBM
 // straight into LDS (global_load_lds: 16 lanes fetch one full row, four rows per instruction,
@@ -73,7 +73,6 @@ constexpr int TILE_BYTES = TILE * ROW_BYTES;          // 8 KiB per tensor
 constexpr int WAVE_LDS = 2 * TILE_BYTES;              // K buffer, V buffer
 constexpr int MAX_ROWS = ATTN_MFMA_MAX_ROWS;          // rows whose cost prefix fits the LDS table
 constexpr int MAX_BLOCKS = SPECATTN_MAX_N / SEL_BLOCK;   // selection blocks per row, at most
-constexpr int STATIC_ROUNDS = 3;      // tiles per wave that need no claim at the start of a launch
 constexpr int SLOT_BYTES = 256;       // one wave-wide LDS-DMA of 4 bytes per lane
 constexpr int KV_AUX = 2;             // cache policy of the K/V gathers: non-temporal (each row is used once)
 constexpr int SEG_COST = 12;          // cost of picking a row up, in tiles
@@ -83,7 +82,7 @@ constexpr float RESCALE_SLACK = 8.0f; // log2 units the running max may exceed t
 constexpr int OFF_PRE = NW * WAVE_LDS;                          // int[MAX_ROWS + 1] cost prefix
 constexpr int OFF_CNT = OFF_PRE + (MAX_ROWS + 1) * 4;           // int[MAX_ROWS] kept counts, clamped
 constexpr int OFF_WSUM = OFF_CNT + MAX_ROWS * 4;                // int[NW]
-constexpr int OFF_MISC = OFF_WSUM + NW * 4;                     // int[4]: tile counter, last-arriver flag
+constexpr int OFF_MISC = OFF_WSUM + NW * 4;                     // int[4]: spare
 constexpr int OFF_BLK = OFF_MISC + 16;                          // int[MAX_BLOCKS + 1] kept before block (mask source)
 constexpr int OFF_SLOT = (OFF_BLK + (MAX_BLOCKS + 1) * 4 + 255) & ~255;   // [NW][2][SLOT_BYTES] list / mask words in flight;
                                                                 // a wave's (m, l) table of the wave merge uses its first slot
@@ -243,16 +242,6 @@ __device__ __forceinline__ int kth_set_bit(uint32_t x, int k)
     c = (int)(x & 1u);       if (k >= c) { r += 1; }
     return r;
 }
-// Wave-wide fetch-and-add on an LDS counter: lane 0 adds 1, the others add 0, so lane 0 reads the
-// value before the wave's own increment; that value is returned to the whole wave.
-__device__ __forceinline__ int lds_claim(uint32_t addr, int lane)
-{
-    uint32_t v;
-    const uint32_t inc = lane == 0 ? 1u : 0u;
-    asm volatile("ds_add_rtn_u32 %0, %1, %2\n s_waitcnt lgkmcnt(0)" : "=&v"(v) : "v"(addr), "v"(inc) : "memory");
-    return (int)__builtin_amdgcn_readfirstlane(v);
-}
-
 // Workgroup barrier for data handed over through LDS only: waits for this wave's LDS operations, not for its
 // outstanding global loads (a plain __syncthreads() also waits for every gather and prefetch still in flight).
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n s_barrier" ::: "memory"); }
@@ -275,7 +264,6 @@ struct Plan {
     float *part_o;            // [slots][QTP][D]
     int32_t *cost_prefix;     // [rows + 1] in the workspace (written by workgroup 0, read by the merge kernel)
     int n_wg;
-    int deterministic;        // static tile assignment
 };
 
 // Cost of a row on the line the workgroups share out: its tiles, plus SEG_COST for picking the row up
@@ -414,7 +402,6 @@ __global__ __launch_bounds__(THREADS, WG_PER_CU) void attn_mfma_kernel(AttnLaunc
     int *pre = reinterpret_cast<int *>(smem + OFF_PRE);
     int *cnt_lds = reinterpret_cast<int *>(smem + OFF_CNT);
     int *wsum = reinterpret_cast<int *>(smem + OFF_WSUM);
-    int *misc = reinterpret_cast<int *>(smem + OFF_MISC);               // [0] tile counter, [1] last-arriver flag
     int *blk_pre = reinterpret_cast<int *>(smem + OFF_BLK);
     char *q_lds = smem + OFF_Q;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -429,7 +416,6 @@ __global__ __launch_bounds__(THREADS, WG_PER_CU) void attn_mfma_kernel(AttnLaunc
     const uint32_t scat_addr = (uint32_t)(uintptr_t)LDS_PTR(char, smem + OFF_SCAT + wave * 256);
     const uint32_t mark_addr = (uint32_t)(uintptr_t)LDS_PTR(char, smem + OFF_MARK + wave * 128);
     const uint32_t blk_addr = (uint32_t)(uintptr_t)LDS_PTR(int, blk_pre);
-    const uint32_t ctr_addr = (uint32_t)(uintptr_t)LDS_PTR(int, misc);
     const uint32_t q_addr = (uint32_t)(uintptr_t)LDS_PTR(char, q_lds);
     // K fragment of k-step c: row l16 (+16 per position tile), 16-byte chunk 4c + g
     uint32_t k_off[4];
@@ -467,7 +453,7 @@ __global__ __launch_bounds__(THREADS, WG_PER_CU) void attn_mfma_kernel(AttnLaunc
     SPECATTN_PRELOAD(a.g_first); SPECATTN_PRELOAD(a.g_count); SPECATTN_PRELOAD(a.k_new);
     SPECATTN_PRELOAD(a.out); SPECATTN_PRELOAD(a.out_lowp); SPECATTN_PRELOAD(a.lse);
     SPECATTN_PRELOAD(plan.part_ml); SPECATTN_PRELOAD(plan.part_o); SPECATTN_PRELOAD(plan.cost_prefix);
-    SPECATTN_PRELOAD(plan.n_wg); SPECATTN_PRELOAD(plan.deterministic);
+    SPECATTN_PRELOAD(plan.n_wg);
     if (LAYOUT != CONTIGUOUS) { SPECATTN_PRELOAD(a.page_table); SPECATTN_PRELOAD(a.page_shift); SPECATTN_PRELOAD(a.max_pages); SPECATTN_PRELOAD(a.kv_stride_page); }
     if (SRC == LIST) { SPECATTN_PRELOAD(a.indices); SPECATTN_PRELOAD(a.idx_stride); }
     if (SRC == MASK) { SPECATTN_PRELOAD(a.kept_mask); SPECATTN_PRELOAD(a.block_counts); SPECATTN_PRELOAD(a.blocks_per_row); SPECATTN_PRELOAD(a.n_max); }
@@ -586,15 +572,8 @@ __global__ __launch_bounds__(THREADS, WG_PER_CU) void attn_mfma_kernel(AttnLaunc
         const int n_idx = (SRC == MASK || !a.dense) ? 1 : 0;            // LDS-DMA instructions per tile for list / mask words
 
         // ---- the wave's tiles --------------------------------------------------------------------------
-        // The first STATIC_ROUNDS tiles of a wave are fixed (tile k of the share to wave k mod NW); after that the
-        // waves claim tiles from the LDS counter, or - deterministic mode - go on in the same fixed pattern.
+        // tile k of the share goes to wave k mod NW
         int t_cur = lt_begin + wave, t_nxt = t_cur + NW, t_nn = t_nxt + NW;
-        int det_next = t_nn + NW;
-        const int dyn_base = lt_begin + STATIC_ROUNDS * NW;
-        auto claim = [&]() -> int {
-            if (plan.deterministic) { const int t = det_next; det_next += NW; return t; }
-            return dyn_base + lds_claim(ctr_addr, lane);
-        };
         // Mask source: where a tile's 32 kept positions start.  Returns the block b that holds rank 32 t and
         // leaves in `skip` the kept positions of b that come before that rank.  (LDS reads by hand, see above.)
         auto mask_locate = [&](int t, int &skip) -> int {
@@ -743,7 +722,6 @@ __global__ __launch_bounds__(THREADS, WG_PER_CU) void attn_mfma_kernel(AttnLaunc
         }
         if (t_cur < tile_end) { request(t_cur, 0); request(t_nxt, 1); }
         store_q();
-        if (tid == 0) misc[0] = 0;
         lds_barrier();
 
         f32x4 o[NQT][8];                     // O^T[dv = 16t + 4g + i][q = l16]
@@ -856,10 +834,9 @@ __global__ __launch_bounds__(THREADS, WG_PER_CU) void attn_mfma_kernel(AttnLaunc
                         }
                     }
                 }
-                // ---- the tile after the next two: claim it and request its words ------------------------------
-                int t_new = tile_end;
+                // ---- the tile after the next two: request its words -------------------------------------------
+                const int t_new = t_nn + NW;
                 if (has_next) {
-                    t_new = claim();
                     request(t_new, s_nxt);                             // the slot t_nxt's words were read from
                     if (SRC == MASK && t_nn < tile_end) {              // the positions of the tile that is next but one
                         vm_wait(17);                                   // its words (requested an iteration ago) are there
@@ -1086,7 +1063,6 @@ static specattn_status launch_chunk(const AttnLaunch &a, hipStream_t stream)
     ws += align256(((size_t)rows + 1) * sizeof(int32_t));
     plan.part_ml = reinterpret_cast<float *>(ws);
     plan.part_o = plan.part_ml + slots * qtp * 2;
-    plan.deterministic = a.deterministic ? 1 : 0;
     const int layout = a.indices_are_physical ? PHYSICAL : (a.page_table ? PAGE_TABLE : CONTIGUOUS);
     const int src = a.kept_mask ? MASK : LIST;
     const bool f16 = a.dtype == SPECATTN_F16;

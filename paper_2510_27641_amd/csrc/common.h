@@ -103,7 +103,6 @@ struct AttnLaunch {
     const uint32_t *kept_mask;   // null = unfused; [rows][blocks_per_row * SEL_BLOCK / 32]
     const int32_t *block_counts; // [rows][blocks_per_row]
     int blocks_per_row;
-    int deterministic;       // 1: static tile assignment, bit-identical results from run to run
 };
 __device__ __forceinline__ int attn_group_heads(const AttnLaunch &a) { return a.g_count ? a.g_count : a.H_q / a.H_kv; }
 // query head behind head gh of this launch's share of kv head h's group

@@ -93,14 +93,14 @@ def compare_select(got: dict, ref: oracle.SelectResult, *, capacity=None, to_phy
 
 
 def gpu_attention(q, k, v, indices, counts, *, page_table=None, page_size=0, physical=False,
-                  n_max=None, want_lse=True, deterministic=False):
+                  n_max=None, want_lse=True):
     """Run specattn_sparse_decode_attn on device tensors; returns (out, lse) numpy."""
     B, H_q, T, d = q.shape
     out = torch.full((B, H_q, T, d), float("nan"), dtype=torch.float32, device="cuda")
     lse = torch.full((B, H_q, T), float("nan"), dtype=torch.float32, device="cuda") if want_lse else None
     args = sa.attn_args(q, k, v, out=out, indices=indices, counts=counts, lse=lse,
                         page_table=page_table, page_size=page_size, indices_are_physical=physical,
-                        n_max=n_max, deterministic=deterministic)
+                        n_max=n_max)
     ws = sa.alloc_workspace(sa.specattn_workspace_size(None, args))
     args.workspace, args.workspace_bytes = ws.data_ptr(), ws.numel()
     sa.specattn_sparse_decode_attn(args)
