@@ -87,8 +87,7 @@ constexpr int OFF_BLK = OFF_MISC + 16;                          // int[MAX_BLOCK
 constexpr int OFF_SLOT = (OFF_BLK + (MAX_BLOCKS + 1) * 4 + 255) & ~255;   // [NW][2][SLOT_BYTES] list / mask words in flight;
                                                                 // a wave's (m, l) table of the wave merge uses its first slot
 constexpr int OFF_SCAT = OFF_SLOT + NW * 2 * SLOT_BYTES;        // uint[NW][2][32] positions of a tile (mask source)
-constexpr int OFF_MARK = OFF_SCAT + NW * 256;                   // uint[NW][32] which mask word owns a rank (mask source)
-constexpr int OFF_Q = OFF_MARK + NW * 128;                      // Q tile [2 * 16][256 B], chunks swizzled like K
+constexpr int OFF_Q = OFF_SCAT + NW * 256;                      // Q tile [2 * 16][256 B], chunks swizzled like K
 constexpr int OFF_BC = OFF_Q + 2 * 16 * ROW_BYTES;               // int[BC_ALL] block counts of all rows (mask source, small calls)
 constexpr int BC_ALL = 2048;
 constexpr int LDS_BYTES = OFF_BC + BC_ALL * 4;
@@ -219,6 +218,28 @@ __device__ __forceinline__ uint32_t lane_read(uint32_t v, int src_lane)
 {
     uint32_t r;
     asm volatile("ds_bpermute_b32 %0, %1, %2\n s_waitcnt lgkmcnt(0)" : "=&v"(r) : "v"(src_lane << 2), "v"(v) : "memory");
+    return r;
+}
+// One word from global memory, waited for on the spot.  Written out because a load the compiler tracks makes it wait
+// for everything in flight (the gathers included) wherever the loaded value may be used, taken or not.
+__device__ __forceinline__ uint32_t global_read_word(const uint32_t *p)
+{
+    uint32_t r;
+    asm volatile("global_load_dword %0, %1, off\n s_waitcnt vmcnt(0)" : "=&v"(r) : "v"(p) : "memory");
+    return r;
+}
+// The same for two values at once (one round trip through the crossbar instead of two).
+__device__ __forceinline__ void lane_read2(uint32_t a, uint32_t b, int src_lane, uint32_t &ra, uint32_t &rb)
+{
+    asm volatile("ds_bpermute_b32 %0, %2, %3\n ds_bpermute_b32 %1, %2, %4\n s_waitcnt lgkmcnt(0)"
+                 : "=&v"(ra), "=&v"(rb) : "v"(src_lane << 2), "v"(a), "v"(b) : "memory");
+}
+// Forward permute: every lane pushes `v` to lane `dst_lane`; a lane nobody pushes to receives 0, and of several
+// pushes to one lane the highest pushing lane's value arrives.
+__device__ __forceinline__ uint32_t lane_push(uint32_t v, int dst_lane)
+{
+    uint32_t r;
+    asm volatile("ds_permute_b32 %0, %1, %2\n s_waitcnt lgkmcnt(0)" : "=&v"(r) : "v"(dst_lane << 2), "v"(v) : "memory");
     return r;
 }
 // Inclusive prefix maximum over lanes 0..31 (the two lower rows of 16 lanes) on the vector ALU.
@@ -414,7 +435,6 @@ __global__ __launch_bounds__(THREADS, WG_PER_CU) void attn_mfma_kernel(AttnLaunc
     const uint32_t vs_addr = ks_addr + TILE_BYTES;
     const uint32_t slot_addr = (uint32_t)(uintptr_t)LDS_PTR(char, slot_lds);
     const uint32_t scat_addr = (uint32_t)(uintptr_t)LDS_PTR(char, smem + OFF_SCAT + wave * 256);
-    const uint32_t mark_addr = (uint32_t)(uintptr_t)LDS_PTR(char, smem + OFF_MARK + wave * 128);
     const uint32_t blk_addr = (uint32_t)(uintptr_t)LDS_PTR(int, blk_pre);
     const uint32_t q_addr = (uint32_t)(uintptr_t)LDS_PTR(char, q_lds);
     // K fragment of k-step c: row l16 (+16 per position tile), 16-byte chunk 4c + g
@@ -574,11 +594,19 @@ __global__ __launch_bounds__(THREADS, WG_PER_CU) void attn_mfma_kernel(AttnLaunc
         // ---- the wave's tiles --------------------------------------------------------------------------
         // tile k of the share goes to wave k mod NW
         int t_cur = lt_begin + wave, t_nxt = t_cur + NW, t_nn = t_nxt + NW;
+        const bool blk_in_regs = SRC == MASK && bc_all && a.blocks_per_row <= 64;   // (uniform)
+        int blk_reg = 0;
         // Mask source: where a tile's 32 kept positions start.  Returns the block b that holds rank 32 t and
         // leaves in `skip` the kept positions of b that come before that rank.  (LDS reads by hand, see above.)
         auto mask_locate = [&](int t, int &skip) -> int {
             const int rank = t * TILE;
             const int nb = a.blocks_per_row;
+            if (blk_in_regs) {                                          // lane b holds the kept count before block b
+                const int cnum = __popcll(__ballot(lane < nb && blk_reg <= rank));
+                const int bb = cnum > 0 ? cnum - 1 : 0;
+                skip = rank - __builtin_amdgcn_readlane(blk_reg, bb);
+                return bb;
+            }
             const int stride = (nb + 63) >> 6;                          // blocks per lane of the coarse step
             int lo = lane * stride < nb ? (int)lds_read_word(blk_addr + (uint32_t)(lane * stride) * 4) : 0x7fffffff;
             int cnum = __popcll(__ballot(lo <= rank));                  // blk_pre[0] = 0 <= rank: at least 1
@@ -636,18 +664,17 @@ __global__ __launch_bounds__(THREADS, WG_PER_CU) void attn_mfma_kernel(AttnLaunc
                 const int got = __builtin_amdgcn_readlane(inc, 63) - skip;     // ranks of the tile among these words
                 if (got > 0) {
                     const int lo = ex - skip + have, hi = lo + pc;      // table slots this word's bits would take
-                    if (lane < 32) lds_write_word(mark_addr + (uint32_t)lane * 4, 0u);
-                    if (pc > 0 && hi > have && lo < need)
-                        lds_write_word(mark_addr + (uint32_t)(lo > have ? lo : have) * 4, (uint32_t)lane + 1u);
-                    lds_wait();
-                    const int mark = lane < 32 ? (int)lds_read_word(mark_addr + (uint32_t)lane * 4) : 0;
-                    const int owner = prefix_max32(lane >= have ? mark : 0) - 1;     // the word that holds rank `lane`
+                    // every word that holds ranks of the tile pushes its number to the lane of its first such rank
+                    // (the others push to lane 63, which stands for no rank)
+                    const bool holds = pc > 0 && hi > have && lo < need;
+                    const int mark = (int)lane_push(holds ? (uint32_t)lane + 1u : 0u, holds ? (lo > have ? lo : have) : 63);
+                    const int owner = prefix_max32((lane >= have && lane < 32) ? mark : 0) - 1;   // the word that holds rank `lane`
                     const int src = owner >= 0 ? owner : 0;
-                    const uint32_t wbits = lane_read(bits, src);
-                    const int wex = (int)lane_read((uint32_t)ex, src);
+                    uint32_t wbits, wex;
+                    lane_read2(bits, (uint32_t)ex, src, wbits, wex);
                     const int top = (have + got) < need ? (have + got) : need;
                     if (lane >= have && lane < top && owner >= 0) {
-                        const int k = lane - have + skip - wex;         // which of the word's bits
+                        const int k = lane - have + skip - (int)wex;    // which of the word's bits
                         lds_write_word(table + (uint32_t)lane * 4, (uint32_t)((word0 + src) * 32 + kth_set_bit(wbits, k)));
                     }
                 }
@@ -655,10 +682,11 @@ __global__ __launch_bounds__(THREADS, WG_PER_CU) void attn_mfma_kernel(AttnLaunc
                 skip = got < 0 ? -got : 0;
                 word0 += 64;
                 if (have >= need || word0 >= nw) break;
-                bits = mask_row[word0 + lane < nw ? word0 + lane : nw - 1];   // sparse row: the tile reaches further
+                bits = global_read_word(mask_row + (word0 + lane < nw ? word0 + lane : nw - 1));   // sparse row: the tile reaches further
             }
-            lds_wait();
-            if (need < TILE) {                                          // ranks past the end repeat the last kept position
+            // (no wait: the table is read by this wave's own later LDS reads, which the LDS unit serves in order)
+            if (need < TILE) {
+                lds_wait();                                          // ranks past the end repeat the last kept position
                 const uint32_t last_pos = lds_read_word(table + (uint32_t)((need > 0 ? need : 1) - 1) * 4);
                 if (lane >= need && lane < TILE) lds_write_word(table + (uint32_t)lane * 4, last_pos);
                 lds_wait();
@@ -707,18 +735,26 @@ __global__ __launch_bounds__(THREADS, WG_PER_CU) void attn_mfma_kernel(AttnLaunc
         if (SRC == MASK) {
             // the row's block prefix first: a tile's mask words are found through it
             if (first_seg && bc_all) lds_barrier();                     // the block counts of all rows are in LDS
-            if (wave == 0) {
-                const int32_t *bc = a.block_counts + (int64_t)r * a.blocks_per_row;
-                int running = 0;
-                for (int base = 0; base < a.blocks_per_row; base += 64) {
-                    const int c = (base + lane < a.blocks_per_row) ? (bc_all ? bc_lds[r * a.blocks_per_row + base + lane] : bc[base + lane]) : 0;
-                    const int inc = wave_inclusive_sum(c);
-                    if (base + lane < a.blocks_per_row) blk_pre[base + lane + 1] = running + inc;
-                    running += __builtin_amdgcn_readlane(inc, 63);
+            if (blk_in_regs) {
+                // up to 64 blocks per row, counts already in LDS: every wave scans the row's counts for itself and
+                // keeps the prefix in a register - no table, no further barrier, and a ballot instead of LDS reads
+                // whenever a tile is located
+                const int c = lane < a.blocks_per_row ? bc_lds[r * a.blocks_per_row + lane] : 0;
+                blk_reg = wave_inclusive_sum(c) - c;
+            } else {
+                if (wave == 0) {
+                    const int32_t *bc = a.block_counts + (int64_t)r * a.blocks_per_row;
+                    int running = 0;
+                    for (int base = 0; base < a.blocks_per_row; base += 64) {
+                        const int c = (base + lane < a.blocks_per_row) ? (bc_all ? bc_lds[r * a.blocks_per_row + base + lane] : bc[base + lane]) : 0;
+                        const int inc = wave_inclusive_sum(c);
+                        if (base + lane < a.blocks_per_row) blk_pre[base + lane + 1] = running + inc;
+                        running += __builtin_amdgcn_readlane(inc, 63);
+                    }
+                    if (lane == 0) blk_pre[0] = 0;
                 }
-                if (lane == 0) blk_pre[0] = 0;
+                lds_barrier();
             }
-            lds_barrier();
         }
         if (t_cur < tile_end) { request(t_cur, 0); request(t_nxt, 1); }
         store_q();
@@ -739,10 +775,11 @@ __global__ __launch_bounds__(THREADS, WG_PER_CU) void attn_mfma_kernel(AttnLaunc
             // written out.  Order of issue per wave and iteration: K(next) ... V(next) words(third).
             uint32_t ent[8];
             vm_wait(0);                                                 // the words of the first two tiles are there
-            if (SRC == MASK) { decode(t_cur, 0); decode(t_nxt, 1); }
+            if (SRC == MASK) decode(t_cur, 0);
             entries(t_cur, 0, ent);
             issue(kbh, wave_lds, ent);
             issue(vbh, wave_lds + TILE_BYTES, ent);
+            if (SRC == MASK) decode(t_nxt, 1);                          // (behind the first gathers, not ahead of them)
             request(t_nn, 0);
             int s_nxt = 1;                                              // slot with the words of t_nxt; t_nn's is the other
             while (t_cur < tile_end) {
