@@ -594,19 +594,11 @@ __global__ __launch_bounds__(THREADS, WG_PER_CU) void attn_mfma_kernel(AttnLaunc
         // ---- the wave's tiles --------------------------------------------------------------------------
         // tile k of the share goes to wave k mod NW
         int t_cur = lt_begin + wave, t_nxt = t_cur + NW, t_nn = t_nxt + NW;
-        const bool blk_in_regs = SRC == MASK && bc_all && a.blocks_per_row <= 64;   // (uniform)
-        int blk_reg = 0;
         // Mask source: where a tile's 32 kept positions start.  Returns the block b that holds rank 32 t and
         // leaves in `skip` the kept positions of b that come before that rank.  (LDS reads by hand, see above.)
         auto mask_locate = [&](int t, int &skip) -> int {
             const int rank = t * TILE;
             const int nb = a.blocks_per_row;
-            if (blk_in_regs) {                                          // lane b holds the kept count before block b
-                const int cnum = __popcll(__ballot(lane < nb && blk_reg <= rank));
-                const int bb = cnum > 0 ? cnum - 1 : 0;
-                skip = rank - __builtin_amdgcn_readlane(blk_reg, bb);
-                return bb;
-            }
             const int stride = (nb + 63) >> 6;                          // blocks per lane of the coarse step
             int lo = lane * stride < nb ? (int)lds_read_word(blk_addr + (uint32_t)(lane * stride) * 4) : 0x7fffffff;
             int cnum = __popcll(__ballot(lo <= rank));                  // blk_pre[0] = 0 <= rank: at least 1
@@ -735,14 +727,8 @@ __global__ __launch_bounds__(THREADS, WG_PER_CU) void attn_mfma_kernel(AttnLaunc
         if (SRC == MASK) {
             // the row's block prefix first: a tile's mask words are found through it
             if (first_seg && bc_all) lds_barrier();                     // the block counts of all rows are in LDS
-            if (blk_in_regs) {
-                // up to 64 blocks per row, counts already in LDS: every wave scans the row's counts for itself and
-                // keeps the prefix in a register - no table, no further barrier, and a ballot instead of LDS reads
-                // whenever a tile is located
-                const int c = lane < a.blocks_per_row ? bc_lds[r * a.blocks_per_row + lane] : 0;
-                blk_reg = wave_inclusive_sum(c) - c;
-            } else {
-                if (wave == 0) {
+            {
+                if (wave == 0) {                                        // (a scan per wave into a register was slower)
                     const int32_t *bc = a.block_counts + (int64_t)r * a.blocks_per_row;
                     int running = 0;
                     for (int base = 0; base < a.blocks_per_row; base += 64) {
