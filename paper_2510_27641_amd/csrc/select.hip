@@ -39,7 +39,7 @@ struct RowShared {
     unsigned wave_c[16];
     unsigned wave_tot[2][16];
     unsigned wt[256];            // kept entries per (item, wave), then their exclusive prefix
-    int32_t wbuf[32][256];       // per wave: the kept entries of 32 / waves items, staged for contiguous stores
+    int32_t wbuf[32][256];       // the row's list, staged in list order for contiguous stores
     double total_m;
     double m_above;
     unsigned c_above;
@@ -117,17 +117,19 @@ __device__ __forceinline__ int locate_bin(RowShared &sh, int e_field_fixed, floa
     static_assert(BPT >= 1, "more threads than bins");
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int top = NB - 1 - (int)threadIdx.x * BPT;           // this thread's highest bin
+    // (bins are re-read from LDS wherever they are needed again, rather than kept in registers: the caller holds
+    // the whole row in registers and has none to spare)
+    auto bin_entry = [&](int j) -> unsigned long long { return sh.hist[top - j]; };
+    auto bin_mass = [&](int j, unsigned long long hj) -> double {
+        return mass_of(hj, FIRST ? ((top - j) >> 3) : e_field_fixed);
+    };
     double lm = 0.0;
     unsigned lc = 0;
-    double mass[BPT];
-    unsigned long long h[BPT];
 #pragma unroll
     for (int j = 0; j < BPT; ++j) {
-        h[j] = sh.hist[top - j];
-        const int e = FIRST ? ((top - j) >> 3) : e_field_fixed;
-        mass[j] = mass_of(h[j], e);
-        lm += mass[j];
-        lc += (unsigned)(h[j] >> CNT_SHIFT);
+        const unsigned long long hj = bin_entry(j);
+        lm += bin_mass(j, hj);
+        lc += (unsigned)(hj >> CNT_SHIFT);
     }
     double incl_m = lm;
     unsigned incl_c = lc;
@@ -151,7 +153,7 @@ __device__ __forceinline__ int locate_bin(RowShared &sh, int e_field_fixed, floa
     // feasible non-empty bin exactly if the sum after its last bin reaches the target.
     double run_end = above;
 #pragma unroll
-    for (int j = 0; j < BPT; ++j) run_end += mass[j];
+    for (int j = 0; j < BPT; ++j) run_end += bin_mass(j, bin_entry(j));
     const bool holds = lc > 0 && (m_above + run_end) >= target;
     const unsigned long long has = __ballot(holds);
     // per wave: the first lane (highest bins) that holds a feasible bin looks for the highest one among its own
@@ -161,12 +163,14 @@ __device__ __forceinline__ int locate_bin(RowShared &sh, int e_field_fixed, floa
         bool found = false;
 #pragma unroll
         for (int j = 0; j < BPT; ++j) {
-            const unsigned cj = (unsigned)(h[j] >> CNT_SHIFT);
-            if (!found && cj && (m_above + (run + mass[j])) >= target) {
+            const unsigned long long hj = bin_entry(j);
+            const double mj = bin_mass(j, hj);
+            const unsigned cj = (unsigned)(hj >> CNT_SHIFT);
+            if (!found && cj && (m_above + (run + mj)) >= target) {
                 found = true;
-                sh.loc[wave].bin = top - j; sh.loc[wave].m_above = run; sh.loc[wave].c_above = runc; sh.loc[wave].packed = h[j];
+                sh.loc[wave].bin = top - j; sh.loc[wave].m_above = run; sh.loc[wave].c_above = runc; sh.loc[wave].packed = hj;
             }
-            run += mass[j];
+            run += mj;
             runc += cj;
         }
     }
@@ -185,9 +189,10 @@ __device__ __forceinline__ int locate_bin(RowShared &sh, int e_field_fixed, floa
         unsigned long long low_h = 0;
 #pragma unroll
         for (int j = 0; j < BPT; ++j) {
-            const unsigned cj = (unsigned)(h[j] >> CNT_SHIFT);
-            if (cj) { low = top - j; low_above = run; low_c = runc; low_h = h[j]; }
-            run += mass[j];
+            const unsigned long long hj = bin_entry(j);
+            const unsigned cj = (unsigned)(hj >> CNT_SHIFT);
+            if (cj) { low = top - j; low_above = run; low_c = runc; low_h = hj; }
+            run += bin_mass(j, hj);
             runc += cj;
         }
         const unsigned long long has_low = __ballot(low >= 0);
@@ -324,6 +329,8 @@ __global__ __launch_bounds__(THREADS, 4) void topp_select_kernel(SelectLaunch a)
     };
 
     // ---- pass 1: bits[30:20] -----------------------------------------------------------------
+    // (one histogram per pair of waves instead of one per workgroup measured slower: the atomics of a row's few
+    // dozen busy bins are not what bounds this pass)
     for_items([&](int, uint4 u) {
         if (u.x) atomicAdd(&sh.hist[u.x >> 20], packed_entry(u.x));
         if (u.y) atomicAdd(&sh.hist[u.y >> 20], packed_entry(u.y));
