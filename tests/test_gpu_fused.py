@@ -113,6 +113,27 @@ def test_row_lengths(n):
     assert row_rel_err(out, o) <= TOL["bf16"]
 
 
+def test_sparse_rows_whose_tiles_span_many_mask_words():
+    """Kept positions far apart: the 32 positions of a tile lie in more than the 64 mask words fetched ahead
+    (row 0: one kept position in about 130; row 1: two clusters 30000 positions apart; row 2: 3 kept positions;
+    row 3 as drawn), so the on-chip decode takes further rounds over the following words."""
+    w = W.llama8b_layer(seed=31, B=1, n=40000, H_q=8, H_kv=4, top_p=0.9)
+    rng = np.random.default_rng(5)
+    base = rng.random((3, w.n)).astype(np.float32) * 1e-9
+    spikes = np.sort(rng.choice(w.n, size=300, replace=False))
+    base[0, spikes] = 1.0 + rng.random(300).astype(np.float32)
+    base[1, 100:140] = 1.0
+    base[1, 30100:30140] = 1.0
+    base[2, [5, 20000, 39999]] = 1.0
+    w.probs[0, :3] = base
+    out, lse, counts, _ = _fused(w)
+    ref, o, l = _reference(w)
+    _check_counts(counts, ref)
+    assert 200 < counts[0] < 300 and counts[1] == 80 and counts[2] == 3      # (ties at the threshold are all kept)
+    assert row_rel_err(out, o) <= TOL["bf16"]
+    assert np.abs(lse - l).max() <= 2e-3
+
+
 def test_paged_ragged_batch_through_page_table():
     w = W.ragged_paged(seed=4, B=6, len_lo=50, len_hi=7000)
     out, lse, counts, _ = _fused(w)
