@@ -281,6 +281,9 @@ specattn_status specattn_sparse_decode_attn_static(const specattn_attn_args *att
  * attn->workspace and the attention over that list: same results, one call, nothing caller-visible in between;
  * reuse_selection, block_counts and kept_mask are not available then (SPECATTN_EUNSUPPORTED).  There is never a
  * caller-visible list, so attn->indices_are_physical does not apply (SPECATTN_EUNSUPPORTED; pass the page table).
+ * What the on-chip route saves is memory (4 KiB of mask per row of 32768 positions instead of a list of up to
+ * 128 KiB) and the list's write and read; decoding the mask costs the attention waves about as much time as the
+ * selection saves, so where speed alone matters the two separate calls are the ones to use.
  */
 specattn_status specattn_fused(const specattn_select_args *sel, const specattn_attn_args *attn,
                                void *stream);
