@@ -257,9 +257,9 @@ specattn_status specattn_sparse_decode_attn(const specattn_attn_args *attn, void
  * tight serving loops, harnesses that forbid hipMalloc.  Same computation, arguments, checks and results as
  * specattn_sparse_decode_attn, except that attn->workspace / attn->workspace_bytes are ignored: the split
  * partials live in a buffer of SPECATTN_STATIC_SCRATCH_BYTES that is part of the library image (one copy per
- * GPU, held until the process ends).  The call allocates and frees nothing.  A call whose
- * specattn_workspace_size(NULL, attn) exceeds that size is refused with SPECATTN_EWORKSPACE before anything
- * is launched.  The buffer belongs to the device that is current when the call is made; `stream` must be a
+ * GPU, held until the process ends).  The call allocates and frees nothing.  A call that cannot run in that
+ * much is refused with SPECATTN_EWORKSPACE before anything is launched (batches of more than 512 rows run in
+ * launches of 512 rows where the size specattn_workspace_size(NULL, attn) asks for would let them take 1536).  The buffer belongs to the device that is current when the call is made; `stream` must be a
  * stream of that device.  All calls on one GPU share the buffer: calls that overlap on one GPU (different
  * streams, or different threads without stream ordering between them) race on it and give wrong results;
  * calls ordered on one stream are safe, and nothing has to be cleared between them.

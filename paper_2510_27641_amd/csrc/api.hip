@@ -495,7 +495,10 @@ specattn_status specattn_sparse_decode_attn_static(const specattn_attn_args *att
     clear_error();
     specattn_status st = check_attn(attn, false);
     if (st != SPECATTN_OK) return st;
-    const size_t need = specattn_workspace_size(nullptr, attn);
+    // the least the call runs with: batches beyond 512 rows then go out in launches of 512 rows
+    const bool dense = !attn->indices && !attn->counts;
+    const int cap = dense ? attn->n_max : attn->idx_capacity * (attn->chunk_size > 1 ? attn->chunk_size : 1);
+    const size_t need = cap <= 0 ? 0 : attn_workspace_min_bytes(attn->B * attn->H_kv, attn->H_q / attn->H_kv, attn->T, attn->d, cap);
     if (need == 0 || need > (size_t)SPECATTN_STATIC_SCRATCH_BYTES) {
         set_error("this call needs %zu bytes of scratch memory; the built-in buffer holds %zu", need,
                   (size_t)SPECATTN_STATIC_SCRATCH_BYTES);

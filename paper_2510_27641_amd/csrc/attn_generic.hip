@@ -248,18 +248,21 @@ int attn_num_splits(int rows, int idx_capacity)
     return s;
 }
 
-size_t attn_workspace_bytes(int rows, int G, int T, int d, int idx_capacity)
+static size_t workspace_bytes(int rows, int G, int T, int d, int idx_capacity, bool least)
 {
     const size_t ns = (size_t)attn_num_splits(rows, idx_capacity);
     const size_t qt = (size_t)G * T;
     size_t bytes = (size_t)rows * ns * qt * (size_t)(d + 2) * sizeof(float);
     bytes = (bytes + 255) & ~(size_t)255;
     if (d == 128) {                                  // the matrix-core variant may take this shape (larger groups of
-        const size_t other = attn_mfma_workspace_bytes(rows, G, T);   // query heads run as several launches over it)
+        const size_t other = least ? attn_mfma_workspace_min_bytes(rows, G, T)   // query heads run as several launches over it)
+                                   : attn_mfma_workspace_bytes(rows, G, T);
         if (other > bytes) bytes = other;
     }
     return bytes;
 }
+size_t attn_workspace_bytes(int rows, int G, int T, int d, int idx_capacity) { return workspace_bytes(rows, G, T, d, idx_capacity, false); }
+size_t attn_workspace_min_bytes(int rows, int G, int T, int d, int idx_capacity) { return workspace_bytes(rows, G, T, d, idx_capacity, true); }
 
 specattn_status launch_attn(const AttnLaunch &a, hipStream_t stream)
 {

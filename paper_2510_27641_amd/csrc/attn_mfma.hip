@@ -79,18 +79,27 @@ constexpr int SEG_COST = 12;          // cost of picking a row up, in tiles
 constexpr float RESCALE_SLACK = 8.0f; // log2 units the running max may exceed the reference by
 
 // dynamic LDS, in bytes from the start
-constexpr int OFF_PRE = NW * WAVE_LDS;                          // int[MAX_ROWS + 1] cost prefix
-constexpr int OFF_CNT = OFF_PRE + (MAX_ROWS + 1) * 4;           // int[MAX_ROWS] kept counts, clamped
-constexpr int OFF_WSUM = OFF_CNT + MAX_ROWS * 4;                // int[NW]
+constexpr int OFF_WSUM = NW * WAVE_LDS;                         // int[NW]
 constexpr int OFF_MISC = OFF_WSUM + NW * 4;                     // int[4]: spare
-constexpr int OFF_BLK = OFF_MISC + 16;                          // int[MAX_BLOCKS + 1] kept before block (mask source)
-constexpr int OFF_SLOT = (OFF_BLK + (MAX_BLOCKS + 1) * 4 + 255) & ~255;   // [NW][2][SLOT_BYTES] list / mask words in flight;
+constexpr int OFF_SLOT = (OFF_MISC + 16 + 255) & ~255;          // [NW][2][SLOT_BYTES] list / mask words in flight;
                                                                 // a wave's (m, l) table of the wave merge uses its first slot
 constexpr int OFF_SCAT = OFF_SLOT + NW * 2 * SLOT_BYTES;        // uint[NW][2][32] positions of a tile (mask source)
 constexpr int OFF_Q = OFF_SCAT + NW * 256;                      // Q tile [2 * 16][256 B], chunks swizzled like K
-constexpr int OFF_BC = OFF_Q + 2 * 16 * ROW_BYTES;               // int[BC_ALL] block counts of all rows (mask source, small calls)
+// The tables behind Q depend on the source: an index list (or a dense call) needs the row tables only, so they
+// hold MAX_ROWS_LIST rows; the mask source shares the space between MAX_ROWS rows, a row's block prefix and
+// the block counts of all rows of a small call.
+constexpr int OFF_TAB = OFF_Q + 2 * 16 * ROW_BYTES;
+constexpr int MAX_ROWS_LIST = ATTN_MFMA_MAX_ROWS_LIST;
 constexpr int BC_ALL = 2048;
-constexpr int LDS_BYTES = OFF_BC + BC_ALL * 4;
+template <int SRC> struct Tables {
+    static constexpr int ROWS = SRC == 0 ? MAX_ROWS_LIST : MAX_ROWS;
+    static constexpr int OFF_PRE = OFF_TAB;                     // int[ROWS + 1] cost prefix
+    static constexpr int OFF_CNT = OFF_PRE + (ROWS + 1) * 4;    // int[ROWS] kept counts, clamped
+    static constexpr int OFF_BLK = OFF_CNT + ROWS * 4;          // int[MAX_BLOCKS + 1] kept before block (mask source)
+    static constexpr int OFF_BC = OFF_BLK + (MAX_BLOCKS + 1) * 4;   // int[BC_ALL] block counts of all rows (mask source, small calls)
+    static constexpr int END = SRC == 0 ? OFF_BLK : OFF_BC + BC_ALL * 4;
+};
+constexpr int LDS_BYTES = Tables<0>::END > Tables<1>::END ? Tables<0>::END : Tables<1>::END;
 static_assert(16 * 2 * 2 * 4 <= SLOT_BYTES, "a wave's (m, l) table must fit its first slot");
 static_assert(LDS_BYTES * WG_PER_CU <= 160 * 1024, "the workgroups of a CU must fit its LDS");
 
@@ -308,17 +317,37 @@ __device__ __forceinline__ void cost_prefix(const AttnLaunch &a, int rows, int *
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         return;
     }
-    static_assert(MAX_ROWS <= THREADS, "one row per thread");
-    const int c = tid < rows ? attn_row_count(a, tid) : 0;
-    const int cost = row_cost(c);
-    const int inc = wave_inclusive_sum(cost);
-    if (tid < rows) cnt[tid] = c;
-    if (lane == 63) wsum[wave] = inc;
-    lds_barrier();
-    int base = 0;
-    for (int w = 0; w < wave; ++w) base += wsum[w];
-    if (tid < rows) pre[tid] = base + inc - cost;
-    if (tid == THREADS - 1) pre[rows] = base + inc;
+    // Many rows: THREADS rows per round (the counts of all rounds are requested at once), a wave-wide scan, the
+    // wave totals through LDS, the rounds before carried along.
+    constexpr int ROUNDS = (MAX_ROWS_LIST + THREADS - 1) / THREADS;
+    int c[ROUNDS];
+#pragma unroll
+    for (int k = 0; k < ROUNDS; ++k) {
+        const int rr = k * THREADS + tid;
+        c[k] = rr < rows ? attn_row_count(a, rr) : 0;
+    }
+    int carry = 0;
+#pragma unroll
+    for (int k = 0; k < ROUNDS; ++k) {
+        if (k * THREADS >= rows) break;                  // (uniform)
+        const int rr = k * THREADS + tid;
+        const int cost = row_cost(c[k]);
+        const int inc = wave_inclusive_sum(cost);
+        if (rr < rows) cnt[rr] = c[k];
+        if (lane == 63) wsum[wave] = inc;
+        lds_barrier();
+        int base = carry, all = 0;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            const int s = wsum[w];
+            if (w < wave) base += s;
+            all += s;
+        }
+        if (rr < rows) pre[rr] = base + inc - cost;
+        carry += all;
+        lds_barrier();                                   // the wave totals are rewritten by the next round
+    }
+    if (tid == 0) pre[rows] = carry;
     lds_barrier();
 }
 
@@ -420,10 +449,10 @@ __global__ __launch_bounds__(THREADS, WG_PER_CU) void attn_mfma_kernel(AttnLaunc
     constexpr int QTP = NQT * 16;
     constexpr int QROUNDS = (NQT * 16 * 16 + THREADS - 1) / THREADS;    // 16-byte chunks of the Q tile per thread
     const int rows = a.B * a.H_kv;
-    int *pre = reinterpret_cast<int *>(smem + OFF_PRE);
-    int *cnt_lds = reinterpret_cast<int *>(smem + OFF_CNT);
+    int *pre = reinterpret_cast<int *>(smem + Tables<SRC>::OFF_PRE);
+    int *cnt_lds = reinterpret_cast<int *>(smem + Tables<SRC>::OFF_CNT);
     int *wsum = reinterpret_cast<int *>(smem + OFF_WSUM);
-    int *blk_pre = reinterpret_cast<int *>(smem + OFF_BLK);
+    int *blk_pre = reinterpret_cast<int *>(smem + Tables<SRC>::OFF_BLK);
     char *q_lds = smem + OFF_Q;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -481,7 +510,7 @@ __global__ __launch_bounds__(THREADS, WG_PER_CU) void attn_mfma_kernel(AttnLaunc
     // Mask source, small calls: the per-block kept counts of all rows are requested together with the counts (the row
     // this workgroup starts in is not known yet), so that its first segment need not go to memory for them again.
     constexpr int BC_PT = BC_ALL / THREADS;
-    int *bc_lds = reinterpret_cast<int *>(smem + OFF_BC);
+    int *bc_lds = reinterpret_cast<int *>(smem + Tables<SRC>::OFF_BC);
     const bool bc_all = SRC == MASK && rows * a.blocks_per_row <= BC_ALL;
     int bc_pf[BC_PT];
     if (bc_all) {
@@ -1057,15 +1086,17 @@ specattn_status attn_mfma_configure()
     return SPECATTN_OK;
 }
 
-size_t attn_mfma_workspace_bytes(int rows, int G, int T)
+static size_t workspace_for(int rows, int G, int T)
 {
-    if (rows > MAX_ROWS) rows = MAX_ROWS;                 // larger batches run as several launches
     const size_t qtp = (G * T <= 16) ? 16 : 32;
     const size_t slots = (size_t)attn_mfma_workgroups() + rows;
     size_t bytes = align256(((size_t)rows + 1) * sizeof(int32_t));                        // cost prefix
     bytes += slots * qtp * (D + 2) * sizeof(float);
     return align256(bytes);
 }
+// larger batches run as several launches over the same workspace
+size_t attn_mfma_workspace_bytes(int rows, int G, int T) { return workspace_for(rows < MAX_ROWS_LIST ? rows : MAX_ROWS_LIST, G, T); }
+size_t attn_mfma_workspace_min_bytes(int rows, int G, int T) { return workspace_for(rows < MAX_ROWS ? rows : MAX_ROWS, G, T); }
 
 static specattn_status launch_chunk(const AttnLaunch &a, hipStream_t stream)
 {
@@ -1077,8 +1108,8 @@ static specattn_status launch_chunk(const AttnLaunch &a, hipStream_t stream)
     plan.n_wg = attn_mfma_workgroups();
     const size_t slots = (size_t)plan.n_wg + rows;
     // every workgroup may leave a partial in slot (workgroup + row): never launch over a workspace that cannot hold them
-    if (!a.workspace || a.workspace_bytes < attn_mfma_workspace_bytes(rows, G, a.T)) {
-        set_error("attention workspace has %zu bytes, %zu needed", a.workspace_bytes, attn_mfma_workspace_bytes(rows, G, a.T));
+    if (!a.workspace || a.workspace_bytes < workspace_for(rows, G, a.T)) {
+        set_error("attention workspace has %zu bytes, %zu needed", a.workspace_bytes, workspace_for(rows, G, a.T));
         return SPECATTN_EWORKSPACE;
     }
     char *ws = static_cast<char *>(a.workspace);
@@ -1132,7 +1163,12 @@ specattn_status launch_attn_mfma(const AttnLaunch &a, hipStream_t stream)
 
 static specattn_status launch_batch(const AttnLaunch &a, hipStream_t stream)
 {
-    const int b_max = MAX_ROWS / a.H_kv;
+    // rows per launch: what the kernel's tables hold for this source, or - when the workspace was sized for
+    // less (the built-in scratch buffer) - what every source can count on
+    const int G = a.g_count ? a.g_count : a.H_q / a.H_kv;
+    int cap = a.kept_mask ? MAX_ROWS : MAX_ROWS_LIST;
+    if (a.B * a.H_kv > MAX_ROWS && a.workspace_bytes < workspace_for(a.B * a.H_kv < cap ? a.B * a.H_kv : cap, G, a.T)) cap = MAX_ROWS;
+    const int b_max = cap / a.H_kv;
     if (a.B <= b_max) return launch_chunk(a, stream);
     const int es = 2;                                       // bf16 or fp16
     for (int b0 = 0; b0 < a.B; b0 += b_max) {

@@ -235,6 +235,7 @@ __device__ __forceinline__ void tail_dots(const AttnLaunch &a, int b, int hq, in
 // number of splits per row the attention launch will use for this shape
 int attn_num_splits(int rows, int idx_capacity);
 size_t attn_workspace_bytes(int rows, int G, int T, int d, int idx_capacity);
+size_t attn_workspace_min_bytes(int rows, int G, int T, int d, int idx_capacity);   // the least the call runs with
 specattn_status launch_attn(const AttnLaunch &a, hipStream_t stream);
 
 // counts the index-list violations of an attention call into *n_bad (device memory)
@@ -248,10 +249,12 @@ specattn_status launch_csr(const int32_t *indices, int64_t idx_stride, const int
 constexpr int ATTN_MFMA_WAVES = 8;        // waves per workgroup (one workgroup per CU: two workgroups of four waves
                                           // do not share a CU's memory pipeline evenly - the one dispatched later
                                           // issues its gathers only when the earlier one's waves are waiting)
-constexpr int ATTN_MFMA_MAX_ROWS = 512;   // rows per launch (larger batches run as several launches)
+constexpr int ATTN_MFMA_MAX_ROWS = 512;   // rows per launch every call can count on (larger batches run as several launches)
+constexpr int ATTN_MFMA_MAX_ROWS_LIST = 1536;   // rows per launch for index lists and dense calls, workspace permitting
 bool attn_mfma_supported(const AttnLaunch &a);
 specattn_status attn_mfma_configure();    // one-time kernel attributes on the current device
-size_t attn_mfma_workspace_bytes(int rows, int G, int T);
+size_t attn_mfma_workspace_bytes(int rows, int G, int T);       // what lets every launch take as many rows as it can
+size_t attn_mfma_workspace_min_bytes(int rows, int G, int T);   // the least a call runs with
 specattn_status launch_attn_mfma(const AttnLaunch &a, hipStream_t stream);
 
 }  // namespace specattn

@@ -115,8 +115,16 @@ def test_other_shapes_and_dtypes(shape):
 
 
 def test_more_rows_than_one_launch_holds():
-    # 2048 rows: the matrix-core variant runs them as two launches over consecutive sequences
+    # 2048 rows: the matrix-core variant runs them as two launches over consecutive sequences (1536 + 512 rows)
     w = W.llama8b_layer(seed=12, B=256, n=256, H_q=16, H_kv=8, T=2, top_p=0.7)
+    _run_and_compare(w, _oracle_selection_mask(w))
+
+
+@pytest.mark.parametrize("B", [9, 65, 88, 192, 193])
+def test_row_counts_around_the_table_sizes(B):
+    # 72, 520, 704, 1536 and 1544 rows: one wave's scan, one, two and three rounds of the workgroup-wide cost prefix,
+    # and one row group past a full launch
+    w = W.llama8b_layer(seed=13, B=B, n=200, H_q=16, H_kv=8, T=2, top_p=0.8)
     _run_and_compare(w, _oracle_selection_mask(w))
 
 

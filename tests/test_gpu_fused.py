@@ -134,6 +134,14 @@ def test_sparse_rows_whose_tiles_span_many_mask_words():
     assert np.abs(lse - l).max() <= 2e-3
 
 
+def test_more_rows_than_one_launch_of_the_mask_source_holds():
+    w = W.llama8b_layer(seed=33, B=80, n=300, H_q=16, H_kv=8, T=2, top_p=0.8)       # 640 rows: 512 + 128
+    out, lse, counts, _ = _fused(w)
+    ref, o, l = _reference(w)
+    _check_counts(counts, ref)
+    assert row_rel_err(out, o) <= TOL["bf16"]
+
+
 def test_paged_ragged_batch_through_page_table():
     w = W.ragged_paged(seed=4, B=6, len_lo=50, len_hi=7000)
     out, lse, counts, _ = _fused(w)

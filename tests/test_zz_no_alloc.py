@@ -52,6 +52,15 @@ def test_static_scratch_matches_workspace_call_twice_in_a_row():
         assert np.abs(lses[1] - want_lse).max() <= 1e-3
 
 
+def test_static_scratch_takes_large_batches_in_smaller_launches():
+    # 1600 rows: the workspace call takes them as 1536 + 64 rows, the built-in buffer holds launches of 512 rows
+    w = W.llama8b_layer(seed=43, B=200, n=200, H_q=16, H_kv=8, T=2, top_p=0.8)
+    outs, lses, want, want_lse = _both_entry_points(w)
+    assert row_rel_err(outs[1], outs[0]) <= 1e-5
+    assert row_rel_err(outs[1], want) <= TOL[w.dtype]
+    assert np.abs(lses[1] - want_lse).max() <= 1e-3
+
+
 def test_static_scratch_fp32_route_and_size_limit():
     w = W.tiny_f32()
     outs, lses, want, _ = _both_entry_points(w)
