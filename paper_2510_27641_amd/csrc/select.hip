@@ -239,12 +239,14 @@ __global__ __launch_bounds__(THREADS, 4) void topp_select_kernel(SelectLaunch a)
     const bool aligned = (reinterpret_cast<uintptr_t>(row) & 15) == 0;
     const int n_items = (len + ITEM - 1) / ITEM;
 
-    bool bad = false;
-    // -0.0 is zero; negative, infinite and NaN entries make the row invalid
+    // -0.0 is zero; negative, infinite and NaN entries make the row invalid.  Branch-free: the largest bit pattern
+    // seen is tested once per thread, and an invalid entry is clamped to the largest finite value so that its bin
+    // stays inside the histogram (the row's result is discarded anyway).
+    uint32_t worst = 0u;
     auto clean = [&](uint32_t x) -> uint32_t {
-        if (x == 0x80000000u) return 0u;
-        if (x >= 0x7f800000u) { bad = true; return 0u; }
-        return x;
+        x = (x == 0x80000000u) ? 0u : x;
+        worst = worst > x ? worst : x;
+        return x < 0x7f7fffffu ? x : 0x7f7fffffu;
     };
     auto clean4 = [&](uint4 u) -> uint4 { return make_uint4(clean(u.x), clean(u.y), clean(u.z), clean(u.w)); };
     // Slow form of an item's load (rows that are not 16-byte aligned or hold fewer than four entries).
@@ -300,8 +302,27 @@ __global__ __launch_bounds__(THREADS, 4) void topp_select_kernel(SelectLaunch a)
     // the histogram is cleared while the loads are in flight
     clear_hist<THREADS, NB1>(sh);
     if (RESIDENT && vec_ok) {
+        // Common case first: no sign bit among the thread's entries.  Then nothing needs cleaning, an entry is invalid
+        // exactly if its exponent field is all ones, and every bin index stays below NB1 - one OR and one maximum per
+        // entry instead of a compare, two selects and a maximum.
+        uint32_t any = 0u, top = 0u;
 #pragma unroll
-        for (int i = 0; i < NV4; ++i) data[i] = finish_item(i, data[i]);
+        for (int i = 0; i < NV4; ++i) {
+            const int p = (i * THREADS + tid) * 4;
+            uint4 u = data[i];
+            if (p + 3 >= len) u = (p == tail_p) ? tailv : make_uint4(0, 0, 0, 0);
+            data[i] = u;
+            any |= u.x | u.y | u.z | u.w;
+            const uint32_t m01 = u.x > u.y ? u.x : u.y, m23 = u.z > u.w ? u.z : u.w;
+            const uint32_t m = m01 > m23 ? m01 : m23;
+            top = top > m ? top : m;
+        }
+        if (any & 0x80000000u) {                 // -0.0 or a negative entry somewhere
+#pragma unroll
+            for (int i = 0; i < NV4; ++i) data[i] = clean4(data[i]);
+        } else {
+            worst = top;
+        }
     }
     auto for_items = [&](auto &&fn) {
         if (RESIDENT) {
@@ -337,7 +358,7 @@ __global__ __launch_bounds__(THREADS, 4) void topp_select_kernel(SelectLaunch a)
         if (u.z) atomicAdd(&sh.hist[u.z >> 20], packed_entry(u.z));
         if (u.w) atomicAdd(&sh.hist[u.w >> 20], packed_entry(u.w));
     });
-    const bool any_bad = __syncthreads_or(bad ? 1 : 0) != 0;     // also orders the atomics
+    const bool any_bad = __syncthreads_or(worst >= 0x7f800000u ? 1 : 0) != 0;     // also orders the atomics
 
     double target = 0.0, m_above = 0.0;
     unsigned c_above = 0;
