@@ -495,26 +495,22 @@ __global__ __launch_bounds__(THREADS, 4) void topp_select_kernel(SelectLaunch a)
         ++it;
     };
     if (RESIDENT) {
-        // All items at once: every wave counts its kept entries per item, one workgroup-wide
-        // exclusive prefix over the (item, wave) counts gives every wave its place in the list.
+        // All items at once.  First only counts: every wave's kept entries per item (four compares and four scalar
+        // bit counts; the keep flags are not stored anywhere - comparing again later is cheaper than packing
+        // them away and unpacking them), then one workgroup-wide exclusive prefix over the (item, wave) counts,
+        // which gives every wave its place in the list.
         constexpr int NE = NV4 * NW;
-        static_assert(NE <= 256 && NE <= THREADS, "prefix table too small");
-        // per item: the keep flags of the thread's four entries (4 bits) and the number of kept entries of the
-        // lanes before it (at most 252), two items to a register
-        uint32_t note[(NV4 + 1) / 2];
-#pragma unroll
-        for (int i = 0; i < (NV4 + 1) / 2; ++i) note[i] = 0u;
+        static_assert(NE <= 256 && NE <= THREADS && NV4 <= 64, "prefix table too small");
+        unsigned my_tot = 0;                                   // lane i: this wave's kept entries of item i
 #pragma unroll
         for (int i = 0; i < NV4; ++i) {
             const uint4 u = data[i];
             const bool f0 = u.x >= tau_bits, f1 = u.y >= tau_bits, f2 = u.z >= tau_bits, f3 = u.w >= tau_bits;
-            const unsigned long long m0 = __ballot(f0), m1 = __ballot(f1), m2 = __ballot(f2), m3 = __ballot(f3);
-            const unsigned before = __popcll(m0 & lt_mask) + __popcll(m1 & lt_mask) + __popcll(m2 & lt_mask) + __popcll(m3 & lt_mask);
-            const unsigned fl = (f0 ? 1u : 0u) | (f1 ? 2u : 0u) | (f2 ? 4u : 0u) | (f3 ? 8u : 0u);
-            note[i >> 1] |= (before | (fl << 9)) << (16 * (i & 1));
-            if (mask_out) emit_mask(i, fl);
-            if (lane == 0) sh.wt[i * NW + wave] = __popcll(m0) + __popcll(m1) + __popcll(m2) + __popcll(m3);
+            const unsigned wtot = __popcll(__ballot(f0)) + __popcll(__ballot(f1)) + __popcll(__ballot(f2)) + __popcll(__ballot(f3));
+            if (lane == i) my_tot = wtot;
+            if (mask_out) emit_mask(i, (f0 ? 1u : 0u) | (f1 ? 2u : 0u) | (f2 ? 4u : 0u) | (f3 ? 8u : 0u));
         }
+        if (lane < NV4) sh.wt[lane * NW + wave] = my_tot;
         __syncthreads();
         if (a.block_counts) {
             constexpr int BPI = ITEM / SEL_BLOCK;              // selection blocks per item
@@ -540,28 +536,40 @@ __global__ __launch_bounds__(THREADS, 4) void topp_select_kernel(SelectLaunch a)
                 sh.wt[tid] = base + inc - v;
             }
             __syncthreads();
-            // The row's list is put together in LDS, in list order (every thread knows the rank of each of its
-            // kept entries), and goes out with contiguous stores over the whole workgroup: whole cache lines,
-            // whatever the kept counts of the single waves are.  Lists longer than the buffer take several rounds.
+            // The row's list is put together in LDS, in list order (a kept entry's rank is its wave's place for the
+            // item, plus the kept entries of the lanes before, plus the kept ones before it in its own lane), and goes
+            // out with contiguous stores over the whole workgroup: whole cache lines, whatever the kept counts of the
+            // single waves are.  Lists longer than the buffer take several rounds.
             constexpr unsigned CH = 32 * 256;
             int32_t *stage = &sh.wbuf[0][0];
             const unsigned cap = kept < (unsigned)a.idx_capacity ? kept : (unsigned)a.idx_capacity;
+            const unsigned my_base = lane < NV4 ? sh.wt[lane * NW + wave] : 0u;    // lane i: this wave's place for item i
             for (unsigned c0 = 0; c0 < cap; c0 += CH) {
                 if (c0) __syncthreads();                               // the round before has been read out
+                const bool one_round = cap <= CH;                      // (uniform) every rank fits the buffer
 #pragma unroll
                 for (int i = 0; i < NV4; ++i) {
-                    const unsigned nt = (note[i >> 1] >> (16 * (i & 1))) & 0xffffu;
-                    const unsigned before = nt & 0x1ffu, fl = nt >> 9;
-                    if (fl) {
-                        unsigned o = sh.wt[i * NW + wave] + before - c0;                  // (wraps around below c0: not in this round)
-                        const int p = (i * THREADS + tid) * 4;
-#pragma unroll
-                        for (int c = 0; c < 4; ++c) {
-                            if (fl & (1u << c)) {
-                                if (o < CH) stage[o] = p + c;
-                                ++o;
-                            }
-                        }
+                    const uint4 u = data[i];
+                    const bool f0 = u.x >= tau_bits, f1 = u.y >= tau_bits, f2 = u.z >= tau_bits, f3 = u.w >= tau_bits;
+                    const unsigned long long m0 = __ballot(f0), m1 = __ballot(f1), m2 = __ballot(f2), m3 = __ballot(f3);
+                    if ((m0 | m1 | m2 | m3) == 0ull) continue;         // (uniform over the wave)
+                    const unsigned before = __builtin_amdgcn_mbcnt_hi((uint32_t)(m3 >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m3,
+                                            __builtin_amdgcn_mbcnt_hi((uint32_t)(m2 >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m2,
+                                            __builtin_amdgcn_mbcnt_hi((uint32_t)(m1 >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m1,
+                                            __builtin_amdgcn_mbcnt_hi((uint32_t)(m0 >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m0, 0u))))))));
+                    const unsigned o0 = (unsigned)__builtin_amdgcn_readlane((int)my_base, i) - c0 + before;   // (wraps around below c0)
+                    const unsigned o1 = o0 + (f0 ? 1u : 0u), o2 = o1 + (f1 ? 1u : 0u), o3 = o2 + (f2 ? 1u : 0u);
+                    const int p = (i * THREADS + tid) * 4;
+                    if (one_round) {
+                        if (f0) stage[o0] = p;
+                        if (f1) stage[o1] = p + 1;
+                        if (f2) stage[o2] = p + 2;
+                        if (f3) stage[o3] = p + 3;
+                    } else {
+                        if (f0 && o0 < CH) stage[o0] = p;
+                        if (f1 && o1 < CH) stage[o1] = p + 1;
+                        if (f2 && o2 < CH) stage[o2] = p + 2;
+                        if (f3 && o3 < CH) stage[o3] = p + 3;
                     }
                 }
                 __syncthreads();
