@@ -550,7 +550,8 @@ __global__ __launch_bounds__(THREADS, 4) void topp_select_kernel(SelectLaunch a)
             const unsigned my_base = lane < NV4 ? sh.wt[lane * NW + wave] : 0u;    // lane i: this wave's place for item i
             for (unsigned c0 = 0; c0 < cap; c0 += CH) {
                 if (c0) __syncthreads();                               // the round before has been read out
-                const bool one_round = cap <= CH;                      // (uniform) every rank fits the buffer
+                const bool one_round = kept <= CH;                     // (uniform) every rank of the row fits the buffer,
+                                                                       // also those beyond a smaller capacity
 #pragma unroll
                 for (int i = 0; i < NV4; ++i) {
                     const uint4 u = data[i];

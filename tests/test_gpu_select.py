@@ -142,6 +142,16 @@ def test_capacity_overflow_truncates_and_reports_true_count():
     assert all(f & sa.ROW_OVERFLOW for f in got["flags"])
 
 
+@pytest.mark.parametrize("capacity", [100, 8192, 9000])
+def test_capacity_far_below_a_long_kept_list(capacity):
+    # more kept entries than one round of the list staging holds (8192), and a capacity below, at and above that
+    rng = np.random.default_rng(38)
+    probs = W.draft_probs(rng, 3, 32768).reshape(1, 3, 32768)
+    got, ref = _check(probs, 0.995, capacity=capacity)
+    assert (got["counts"] > 9000).all()
+    assert all(f & sa.ROW_OVERFLOW for f in got["flags"])
+
+
 def test_strided_and_unaligned_rows():
     rng = np.random.default_rng(41)
     n = 1500
