@@ -1,6 +1,7 @@
 """GPU parity at the full sizes of the workload list, in the launch configuration bench.py times:
 selection is compared on every row, attention on sampled output rows that the oracle computes one
-by one (each sample is a 1-query, 1-kv-head problem cut out of the device tensors)."""
+by one (each sample is a 1-query, 1-kv-head problem cut out of the device tensors) and, for the headline
+layer, on every output row."""
 import time
 
 import numpy as np
@@ -85,6 +86,14 @@ def test_headline_layer_b8_n32768_unfused_and_fused():
     err_f = _sample_check(out_f, q, lambda b, h: k[b, h], lambda b, h: v[b, h], ref, H_kv, H_q // H_kv, n, lens, samples)
     print(f"headline layer: sampled row-relative error unfused {err:.2e}, fused {err_f:.2e}")
     assert err <= TOL["bf16"] and err_f <= TOL["bf16"]
+    # every output row of the layer (1280 of them) against the oracle's masked dense attention over the whole layer
+    mask = ref.mask().reshape(B, H_kv, n)
+    o, _ = oracle.masked_attention(_bits(q), _bits(k), _bits(v), mask, bf16=True)
+    err_all = row_rel_err(out, o)
+    clear = np.repeat(((ref.flags & oracle.ROW_NEAR_BOUNDARY) == 0).reshape(B, H_kv), H_q // H_kv, axis=1)   # per query head
+    err_all_f = row_rel_err(out_f[clear], o[clear])
+    print(f"headline layer: row-relative error over all {B * H_q * T} output rows unfused {err_all:.2e}, fused {err_all_f:.2e}")
+    assert err_all <= TOL["bf16"] and err_all_f <= TOL["bf16"]
 
 
 @pytest.mark.parametrize("clip", [None, 8.0])
