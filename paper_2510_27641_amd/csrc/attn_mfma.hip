@@ -398,7 +398,11 @@ __device__ __forceinline__ int floor_div(int64_t a, int b)
 __device__ __forceinline__ int share_start(int total, int n_wg, int w)
 {
     const int n = n_wg < total ? n_wg : total;
-    return w < n ? floor_div((int64_t)w * total, n) : total;
+    if (w >= n) return total;
+    // (a power of two - the usual 256 workgroups - divides exactly in any arithmetic: a shift then gives the same
+    // floor as the division below at a tenth of the instructions, on the way to a workgroup's first request)
+    if ((n & (n - 1)) == 0) return (int)(((int64_t)w * total) >> (31 - __clz(n)));
+    return floor_div((int64_t)w * total, n);
 }
 __device__ __forceinline__ Share make_share(int total, int n_wg, int w)
 {
