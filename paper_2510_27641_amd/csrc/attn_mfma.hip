@@ -85,21 +85,18 @@ constexpr int OFF_SLOT = (OFF_MISC + 16 + 255) & ~255;          // [NW][2][SLOT_
                                                                 // a wave's (m, l) table of the wave merge uses its first slot
 constexpr int OFF_SCAT = OFF_SLOT + NW * 2 * SLOT_BYTES;        // uint[NW][2][32] positions of a tile (mask source)
 constexpr int OFF_Q = OFF_SCAT + NW * 256;                      // Q tile [2 * 16][256 B], chunks swizzled like K
-// The tables behind Q depend on the source: an index list (or a dense call) needs the row tables only, so they
-// hold MAX_ROWS_LIST rows; the mask source shares the space between MAX_ROWS rows, a row's block prefix and
-// the block counts of all rows of a small call.
+// Behind Q: the row tables (cost prefix and kept counts of up to MAX_ROWS_LIST rows), then a row's block prefix (mask
+// source).  Calls of up to 64 rows keep their row tables in the first kilobyte, and the mask source then uses the
+// rest of the region for the block counts of all rows.
 constexpr int OFF_TAB = OFF_Q + 2 * 16 * ROW_BYTES;
 constexpr int MAX_ROWS_LIST = ATTN_MFMA_MAX_ROWS_LIST;
 constexpr int BC_ALL = 2048;
-template <int SRC> struct Tables {
-    static constexpr int ROWS = SRC == 0 ? MAX_ROWS_LIST : MAX_ROWS;
-    static constexpr int OFF_PRE = OFF_TAB;                     // int[ROWS + 1] cost prefix
-    static constexpr int OFF_CNT = OFF_PRE + (ROWS + 1) * 4;    // int[ROWS] kept counts, clamped
-    static constexpr int OFF_BLK = OFF_CNT + ROWS * 4;          // int[MAX_BLOCKS + 1] kept before block (mask source)
-    static constexpr int OFF_BC = OFF_BLK + (MAX_BLOCKS + 1) * 4;   // int[BC_ALL] block counts of all rows (mask source, small calls)
-    static constexpr int END = SRC == 0 ? OFF_BLK : OFF_BC + BC_ALL * 4;
-};
-constexpr int LDS_BYTES = Tables<0>::END > Tables<1>::END ? Tables<0>::END : Tables<1>::END;
+constexpr int FEW_ROWS = 64;                                    // rows a single wave scans by itself
+constexpr int OFF_BC = OFF_TAB + 1024;                          // int[BC_ALL] block counts of all rows (mask source, <= FEW_ROWS rows)
+constexpr int TAB_BYTES = (2 * MAX_ROWS_LIST + 1) * 4;          // int[rows + 1] cost prefix, int[rows] kept counts, clamped
+constexpr int OFF_BLK = OFF_TAB + TAB_BYTES;                    // int[MAX_BLOCKS + 1] kept before block (mask source)
+constexpr int LDS_BYTES = OFF_BLK + (MAX_BLOCKS + 1) * 4;
+static_assert((2 * FEW_ROWS + 1) * 4 <= 1024 && 1024 + BC_ALL * 4 <= TAB_BYTES, "the block counts must fit behind the tables of a small call");
 static_assert(16 * 2 * 2 * 4 <= SLOT_BYTES, "a wave's (m, l) table must fit its first slot");
 static_assert(LDS_BYTES * WG_PER_CU <= 160 * 1024, "the workgroups of a CU must fit its LDS");
 
@@ -304,7 +301,7 @@ __device__ __forceinline__ int row_cost(int count) { return count > 0 ? (count +
 __device__ __forceinline__ void cost_prefix(const AttnLaunch &a, int rows, int *pre, int *cnt, int *wsum)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (rows <= 64) {
+    if (rows <= FEW_ROWS) {
         // Few rows: every wave scans all of them by itself and writes the (identical) tables; a wave reads
         // back only after its own writes (LDS operations of a wave complete in order), so no barrier is needed.
         const int c = lane < rows ? attn_row_count(a, lane) : 0;
@@ -453,10 +450,10 @@ __global__ __launch_bounds__(THREADS, WG_PER_CU) void attn_mfma_kernel(AttnLaunc
     constexpr int QTP = NQT * 16;
     constexpr int QROUNDS = (NQT * 16 * 16 + THREADS - 1) / THREADS;    // 16-byte chunks of the Q tile per thread
     const int rows = a.B * a.H_kv;
-    int *pre = reinterpret_cast<int *>(smem + Tables<SRC>::OFF_PRE);
-    int *cnt_lds = reinterpret_cast<int *>(smem + Tables<SRC>::OFF_CNT);
+    int *pre = reinterpret_cast<int *>(smem + OFF_TAB);
+    int *cnt_lds = pre + ((a.B * a.H_kv <= FEW_ROWS ? FEW_ROWS : MAX_ROWS_LIST) + 1);
     int *wsum = reinterpret_cast<int *>(smem + OFF_WSUM);
-    int *blk_pre = reinterpret_cast<int *>(smem + Tables<SRC>::OFF_BLK);
+    int *blk_pre = reinterpret_cast<int *>(smem + OFF_BLK);
     char *q_lds = smem + OFF_Q;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -514,8 +511,8 @@ __global__ __launch_bounds__(THREADS, WG_PER_CU) void attn_mfma_kernel(AttnLaunc
     // Mask source, small calls: the per-block kept counts of all rows are requested together with the counts (the row
     // this workgroup starts in is not known yet), so that its first segment need not go to memory for them again.
     constexpr int BC_PT = BC_ALL / THREADS;
-    int *bc_lds = reinterpret_cast<int *>(smem + Tables<SRC>::OFF_BC);
-    const bool bc_all = SRC == MASK && rows * a.blocks_per_row <= BC_ALL;
+    int *bc_lds = reinterpret_cast<int *>(smem + OFF_BC);
+    const bool bc_all = SRC == MASK && rows <= FEW_ROWS && rows * a.blocks_per_row <= BC_ALL;
     int bc_pf[BC_PT];
     if (bc_all) {
 #pragma unroll
@@ -564,7 +561,7 @@ __global__ __launch_bounds__(THREADS, WG_PER_CU) void attn_mfma_kernel(AttnLaunc
     // This workgroup's share of the cost line, and the rows of which it holds tiles.  Up to 64 rows, lane i looks
     // at row i: one LDS round trip, the share, every row's local tile range at once and a ballot, instead of a
     // binary search and a row-by-row walk over the table, each step of which waits for an LDS read.
-    const bool few_rows = rows <= 64;                    // uniform
+    const bool few_rows = rows <= FEW_ROWS;              // uniform
     int row_lo = 0, row_cnt = 0, row_hi = 0;
     if (few_rows) {
         row_lo = lane < rows ? pre[lane] : 0;
@@ -1170,7 +1167,7 @@ static specattn_status launch_batch(const AttnLaunch &a, hipStream_t stream)
     // rows per launch: what the kernel's tables hold for this source, or - when the workspace was sized for
     // less (the built-in scratch buffer) - what every source can count on
     const int G = a.g_count ? a.g_count : a.H_q / a.H_kv;
-    int cap = a.kept_mask ? MAX_ROWS : MAX_ROWS_LIST;
+    int cap = MAX_ROWS_LIST;
     if (a.B * a.H_kv > MAX_ROWS && a.workspace_bytes < workspace_for(a.B * a.H_kv < cap ? a.B * a.H_kv : cap, G, a.T)) cap = MAX_ROWS;
     const int b_max = cap / a.H_kv;
     if (a.B <= b_max) return launch_chunk(a, stream);

@@ -249,8 +249,8 @@ specattn_status launch_csr(const int32_t *indices, int64_t idx_stride, const int
 constexpr int ATTN_MFMA_WAVES = 8;        // waves per workgroup (one workgroup per CU: two workgroups of four waves
                                           // do not share a CU's memory pipeline evenly - the one dispatched later
                                           // issues its gathers only when the earlier one's waves are waiting)
-constexpr int ATTN_MFMA_MAX_ROWS = 512;   // rows per launch every call can count on (larger batches run as several launches)
-constexpr int ATTN_MFMA_MAX_ROWS_LIST = 1536;   // rows per launch for index lists and dense calls, workspace permitting
+constexpr int ATTN_MFMA_MAX_ROWS = 512;   // rows per launch every call can count on (larger batches run as several launches); most kv heads
+constexpr int ATTN_MFMA_MAX_ROWS_LIST = 1536;   // rows per launch when the workspace was sized for them
 bool attn_mfma_supported(const AttnLaunch &a);
 specattn_status attn_mfma_configure();    // one-time kernel attributes on the current device
 size_t attn_mfma_workspace_bytes(int rows, int G, int T);       // what lets every launch take as many rows as it can

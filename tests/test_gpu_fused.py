@@ -134,8 +134,10 @@ def test_sparse_rows_whose_tiles_span_many_mask_words():
     assert np.abs(lse - l).max() <= 2e-3
 
 
-def test_more_rows_than_one_launch_of_the_mask_source_holds():
-    w = W.llama8b_layer(seed=33, B=80, n=300, H_q=16, H_kv=8, T=2, top_p=0.8)       # 640 rows: 512 + 128
+@pytest.mark.parametrize("B", [80, 200])
+def test_many_rows_through_the_mask_source(B):
+    # 640 rows (two rounds of the workgroup-wide cost prefix) and 1600 rows (1536 + 64: two launches)
+    w = W.llama8b_layer(seed=33, B=B, n=300, H_q=16, H_kv=8, T=2, top_p=0.8)
     out, lse, counts, _ = _fused(w)
     ref, o, l = _reference(w)
     _check_counts(counts, ref)
