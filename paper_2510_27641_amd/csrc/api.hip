@@ -519,6 +519,8 @@ specattn_status specattn_init(void)
     void *ws = nullptr;
     const specattn_status st = static_scratch(&ws);
     if (st != SPECATTN_OK) return st;
+    const specattn_status sg = attn_generic_configure();
+    if (sg != SPECATTN_OK) return sg;
     return attn_mfma_configure();
 }
 

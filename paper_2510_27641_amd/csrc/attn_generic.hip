@@ -212,30 +212,57 @@ __global__ void merge_kernel(AttnLaunch a, int n_splits, const float *part_o, co
     if (a.lse && threadIdx.x == 0) a.lse[orow] = l > 0.0f ? m + __logf(l) : -INFINITY;
 }
 
+constexpr size_t generic_lds_bytes(int d)
+{
+    return sizeof(float) * (size_t)(MAX_QT * d + GEN_TILE * (d + 1) + GEN_TILE * d + MAX_QT * (GEN_TILE + 1) + 3 * MAX_QT);
+}
+
 template <typename T, int D>
 specattn_status run_generic(const AttnLaunch &a, int rows, int n_splits, float *part_o, float *part_ml,
                             hipStream_t stream)
 {
-    const size_t lds = sizeof(float) * (MAX_QT * D + GEN_TILE * (D + 1) + GEN_TILE * D + MAX_QT * (GEN_TILE + 1) + 3 * MAX_QT);
-    {
-        static std::mutex mu;
-        static bool configured = false;
-        std::lock_guard<std::mutex> lock(mu);
-        if (!configured) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_generic_kernel<T, D>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
-                set_error("cannot reserve %zu bytes of LDS", lds);
-                return SPECATTN_EHIP;
-            }
-            configured = true;
-        }
-    }
-    hipLaunchKernelGGL((attn_generic_kernel<T, D>), dim3(rows * n_splits), dim3(GEN_THREADS), lds, stream, a,
+    const specattn_status st = attn_generic_configure();
+    if (st != SPECATTN_OK) return st;
+    hipLaunchKernelGGL((attn_generic_kernel<T, D>), dim3(rows * n_splits), dim3(GEN_THREADS), generic_lds_bytes(D), stream, a,
                        n_splits, part_o, part_ml);
     return check_launch("attn_generic_kernel");
 }
 
 }  // namespace
+
+// The LDS size of every variant, set once per device (not on a variant's first launch: a first call may be
+// recorded in a graph, and a process may use several devices).
+specattn_status attn_generic_configure()
+{
+    constexpr int MAX_DEVICES = 64;
+    static std::mutex mu;
+    static bool done[MAX_DEVICES] = {false};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) {
+        (void)hipGetLastError();
+        set_error("no current device");
+        return SPECATTN_EHIP;
+    }
+    std::lock_guard<std::mutex> lock(mu);
+    if (done[dev]) return SPECATTN_OK;
+    const struct { const void *fn; size_t lds; } variants[] = {
+        {reinterpret_cast<const void *>(&attn_generic_kernel<float, 64>), generic_lds_bytes(64)},
+        {reinterpret_cast<const void *>(&attn_generic_kernel<float, 128>), generic_lds_bytes(128)},
+        {reinterpret_cast<const void *>(&attn_generic_kernel<__hip_bfloat16, 64>), generic_lds_bytes(64)},
+        {reinterpret_cast<const void *>(&attn_generic_kernel<__hip_bfloat16, 128>), generic_lds_bytes(128)},
+        {reinterpret_cast<const void *>(&attn_generic_kernel<_Float16, 64>), generic_lds_bytes(64)},
+        {reinterpret_cast<const void *>(&attn_generic_kernel<_Float16, 128>), generic_lds_bytes(128)},
+    };
+    for (const auto &v : variants) {
+        if (hipFuncSetAttribute(v.fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)v.lds) != hipSuccess) {
+            (void)hipGetLastError();
+            set_error("cannot reserve %zu bytes of LDS", v.lds);
+            return SPECATTN_EHIP;
+        }
+    }
+    done[dev] = true;
+    return SPECATTN_OK;
+}
 
 int attn_num_splits(int rows, int idx_capacity)
 {

@@ -253,6 +253,7 @@ constexpr int ATTN_MFMA_MAX_ROWS = 512;   // rows per launch every call can coun
 constexpr int ATTN_MFMA_MAX_ROWS_LIST = 1536;   // rows per launch when the workspace was sized for them
 bool attn_mfma_supported(const AttnLaunch &a);
 specattn_status attn_mfma_configure();    // one-time kernel attributes on the current device
+specattn_status attn_generic_configure(); // the same for the fp32-ALU variants
 size_t attn_mfma_workspace_bytes(int rows, int G, int T);       // what lets every launch take as many rows as it can
 size_t attn_mfma_workspace_min_bytes(int rows, int G, int T);   // the least a call runs with
 specattn_status launch_attn_mfma(const AttnLaunch &a, hipStream_t stream);

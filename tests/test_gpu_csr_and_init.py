@@ -78,3 +78,28 @@ def test_first_call_of_a_kernel_variant_inside_a_graph_capture():
         graph.replay()
         torch.cuda.synchronize()
         assert row_rel_err(out.cpu().numpy(), want) <= TOL["f16"]
+
+
+def test_first_call_of_a_vector_alu_variant_inside_a_graph_capture():
+    """The same for the kernels that take d = 64 (fp16 with d = 64 has not run before this test in a run of the whole suite)."""
+    sa.specattn_init()
+    w = W.tiny_f32(seed=3, n=700, B=2, H=4, T=3)
+    w.dtype = "f16"
+    ref = oracle.topp_select(w.probs.reshape(-1, w.n), w.top_p)
+    got = gpu_select(w.probs, w.top_p)
+    q, k, v = kv_tensors(w)
+    out = torch.zeros(q.shape, dtype=torch.float32, device="cuda")
+    att = sa.attn_args(q, k, v, out=out, indices=got["d_indices"], counts=got["d_counts"])
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            sa.specattn_sparse_decode_attn_static(att)
+    torch.cuda.synchronize()
+    want, _ = oracle_attention(w, ref.mask().reshape(w.B, w.H_kv, w.n))
+    for _ in range(2):
+        out.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert row_rel_err(out.cpu().numpy(), want) <= TOL["f16"]
