@@ -39,7 +39,6 @@ struct RowShared {
     unsigned wave_c[16];
     unsigned wave_tot[2][16];
     unsigned wt[256];            // kept entries per (item, wave), then their exclusive prefix
-    int32_t wbuf[32][256];       // the row's list, staged in list order for contiguous stores
     double total_m;
     double m_above;
     unsigned c_above;
@@ -226,10 +225,16 @@ __device__ __forceinline__ void clear_hist(RowShared &sh)
 }
 
 // THREADS threads per row; RESIDENT: the row sits in NV4 uint4 registers per thread.
+// Entries of the buffer in which a row's list is staged in list order for contiguous stores (dynamic LDS, so that
+// the small workgroups, which are meant to run four to a CU, are not held to three by a buffer sized for the large
+// ones; longer lists take several rounds).
+constexpr unsigned stage_entries(int threads) { return threads <= 256 ? 4096u : 8192u; }
+
 template <int THREADS, int NV4, bool RESIDENT>
 __global__ __launch_bounds__(THREADS, 4) void topp_select_kernel(SelectLaunch a)
 {
     __shared__ RowShared sh;
+    extern __shared__ __align__(16) int32_t stage_dyn[];
     constexpr int NW = THREADS / 64;
     constexpr int ITEM = THREADS * 4;                 // positions per item (one uint4 per thread)
     const int r = blockIdx.x;
@@ -544,8 +549,8 @@ __global__ __launch_bounds__(THREADS, 4) void topp_select_kernel(SelectLaunch a)
             // item, plus the kept entries of the lanes before, plus the kept ones before it in its own lane), and goes
             // out with contiguous stores over the whole workgroup: whole cache lines, whatever the kept counts of the
             // single waves are.  Lists longer than the buffer take several rounds.
-            constexpr unsigned CH = 32 * 256;
-            int32_t *stage = &sh.wbuf[0][0];
+            constexpr unsigned CH = stage_entries(THREADS);
+            int32_t *stage = stage_dyn;
             const unsigned cap = kept < (unsigned)a.idx_capacity ? kept : (unsigned)a.idx_capacity;
             const unsigned my_base = lane < NV4 ? sh.wt[lane * NW + wave] : 0u;    // lane i: this wave's place for item i
             for (unsigned c0 = 0; c0 < cap; c0 += CH) {
@@ -602,7 +607,8 @@ template <int THREADS, int NV4, bool RESIDENT>
 specattn_status launch_one(const SelectLaunch &a, hipStream_t stream)
 {
     const int rows = a.B * a.H_kv;
-    hipLaunchKernelGGL((topp_select_kernel<THREADS, NV4, RESIDENT>), dim3(rows), dim3(THREADS), 0, stream, a);
+    hipLaunchKernelGGL((topp_select_kernel<THREADS, NV4, RESIDENT>), dim3(rows), dim3(THREADS), stage_entries(THREADS) * sizeof(int32_t),
+                       stream, a);
     return check_launch("topp_select_kernel");
 }
 
